@@ -1,0 +1,197 @@
+"""ctypes front end of the CPU oracle (``iwp_oracle.cpp``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by ``__graft_entry__.smoke()``
+and by the ``cpu_baseline`` leg of ``bench.py``; never by the product package.
+Argument marshalling only -- every step of the method runs in the C++ file.
+All arrays are host numpy arrays, C-contiguous, float32 / uint32.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "iwp_oracle.cpp")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+# IEEE binary32 with no contraction and no fast-math: the flags are part of the
+# oracle's definition (Alg. 1 arithmetic read as plain fp32).
+CXXFLAGS = ["-std=c++17", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared"]
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with g++; returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["g++", *CXXFLAGS, "-o", tmp, _SRC])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+class Threshold(C.Structure):
+    _fields_ = [("key", C.c_uint32), ("n_gt", C.c_uint32), ("n_eq_take", C.c_uint32)]
+
+
+class Layer(C.Structure):
+    _fields_ = [("offset", C.c_int64), ("n", C.c_uint32), ("k", C.c_uint32),
+                ("out_offset", C.c_uint32), ("pad", C.c_uint32)]
+
+
+_lib = None
+_f32p = C.POINTER(C.c_float)
+_u32p = C.POINTER(C.c_uint32)
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        L = _lib
+        L.oracle_accumulate.argtypes = [_f32p, _f32p, C.c_uint64]
+        L.oracle_accumulate.restype = None
+        L.oracle_score.argtypes = [_f32p, _f32p, C.c_uint64, C.c_float, _f32p]
+        L.oracle_score.restype = None
+        L.oracle_score_keys.argtypes = [_f32p, _f32p, C.c_uint64, C.c_float, _u32p]
+        L.oracle_score_keys.restype = None
+        L.oracle_select.argtypes = [_f32p, C.c_uint32, C.c_uint32, _u32p, C.POINTER(Threshold)]
+        L.oracle_select.restype = C.c_int
+        L.oracle_take.argtypes = [_f32p, _u32p, C.c_uint32, _f32p]
+        L.oracle_take.restype = None
+        L.oracle_rank_of.argtypes = [_f32p, C.c_uint64, C.c_uint64]
+        L.oracle_rank_of.restype = C.c_uint64
+        L.oracle_compress_layer.argtypes = [_f32p, _f32p, _f32p, C.c_uint32, C.c_uint32, C.c_float,
+                                            _u32p, _f32p, C.POINTER(Threshold)]
+        L.oracle_compress_layer.restype = C.c_int
+        L.oracle_select_threshold.argtypes = [_f32p, _f32p, C.c_uint32, C.c_uint32, C.c_float,
+                                              C.POINTER(Threshold)]
+        L.oracle_select_threshold.restype = C.c_int
+        L.oracle_gather_sum.argtypes = [C.POINTER(_f32p), C.c_uint32, _u32p, C.c_uint64, _f32p]
+        L.oracle_gather_sum.restype = None
+        L.oracle_apply_sparse_update.argtypes = [_f32p, _u32p, _f32p, C.c_uint64, C.c_float,
+                                                 C.POINTER(_f32p), C.c_uint32]
+        L.oracle_apply_sparse_update.restype = None
+        L.oracle_step.argtypes = [_f32p, C.POINTER(_f32p), C.POINTER(_f32p), C.POINTER(C.c_uint8),
+                                  C.c_uint32, C.POINTER(Layer), _u32p, C.c_uint32, C.c_float, C.c_float,
+                                  _u32p, _f32p, _f32p, C.POINTER(Threshold)]
+        L.oracle_step.restype = C.c_int
+    return _lib
+
+
+def _f32(a: np.ndarray):
+    assert a.dtype == np.float32 and a.flags.c_contiguous, "float32 C-contiguous array required"
+    return a.ctypes.data_as(_f32p)
+
+
+def _u32(a: np.ndarray):
+    assert a.dtype == np.uint32 and a.flags.c_contiguous, "uint32 C-contiguous array required"
+    return a.ctypes.data_as(_u32p)
+
+
+def _ptr_array(arrays: Sequence[np.ndarray]):
+    return (_f32p * len(arrays))(*[_f32(a) for a in arrays])
+
+
+def accumulate(r: np.ndarray, g: np.ndarray) -> None:
+    assert r.shape == g.shape
+    lib().oracle_accumulate(_f32(r), _f32(g), r.size)
+
+
+def score(w: np.ndarray, r: np.ndarray, eps: float) -> np.ndarray:
+    s = np.empty(r.size, np.float32)
+    lib().oracle_score(_f32(w), _f32(r), r.size, C.c_float(eps), _f32(s))
+    return s
+
+
+def score_keys(w: np.ndarray, r: np.ndarray, eps: float) -> np.ndarray:
+    key = np.empty(r.size, np.uint32)
+    lib().oracle_score_keys(_f32(w), _f32(r), r.size, C.c_float(eps), _u32(key))
+    return key
+
+
+def select(s: np.ndarray, k: int):
+    """-> (idx ascending uint32[k], (key, n_gt, n_eq_take))."""
+    idx = np.empty(k, np.uint32)
+    thr = Threshold()
+    rc = lib().oracle_select(_f32(s), s.size, k, _u32(idx), C.byref(thr))
+    if rc:
+        raise ValueError("oracle_select: rc=%d" % rc)
+    return idx, (thr.key, thr.n_gt, thr.n_eq_take)
+
+
+def take(r: np.ndarray, idx: np.ndarray) -> np.ndarray:
+    val = np.empty(idx.size, np.float32)
+    lib().oracle_take(_f32(r), _u32(idx), idx.size, _f32(val))
+    return val
+
+
+def rank_of(s: np.ndarray, i: int) -> int:
+    return int(lib().oracle_rank_of(_f32(s), s.size, i))
+
+
+def compress_layer(w: np.ndarray, g: np.ndarray, r: np.ndarray, k: int, eps: float):
+    """r is updated in place.  -> (idx, val, (key, n_gt, n_eq_take))."""
+    idx = np.empty(k, np.uint32)
+    val = np.empty(k, np.float32)
+    thr = Threshold()
+    rc = lib().oracle_compress_layer(_f32(w), _f32(g), _f32(r), r.size, k, C.c_float(eps),
+                                     _u32(idx), _f32(val), C.byref(thr))
+    if rc:
+        raise ValueError("oracle_compress_layer: rc=%d" % rc)
+    return idx, val, (thr.key, thr.n_gt, thr.n_eq_take)
+
+
+def select_threshold(w: np.ndarray, r: np.ndarray, k: int, eps: float):
+    thr = Threshold()
+    rc = lib().oracle_select_threshold(_f32(w), _f32(r), r.size, k, C.c_float(eps), C.byref(thr))
+    if rc:
+        raise ValueError("oracle_select_threshold: rc=%d" % rc)
+    return (thr.key, thr.n_gt, thr.n_eq_take)
+
+
+def gather_sum(residuals: Sequence[np.ndarray], idx: np.ndarray) -> np.ndarray:
+    out = np.empty(idx.size, np.float32)
+    lib().oracle_gather_sum(_ptr_array(residuals), len(residuals), _u32(idx), idx.size, _f32(out))
+    return out
+
+
+def apply_sparse_update(w: np.ndarray, idx: np.ndarray, s: np.ndarray, scale: float,
+                        residuals: Sequence[np.ndarray]) -> None:
+    lib().oracle_apply_sparse_update(_f32(w), _u32(idx), _f32(s), idx.size, C.c_float(scale),
+                                     _ptr_array(residuals), len(residuals))
+
+
+def layer_table(rows) -> "C.Array[Layer]":
+    """rows: iterable of (offset, n, k, out_offset)."""
+    rows = list(rows)
+    tab = (Layer * len(rows))()
+    for t, (off, n, k, oo) in zip(tab, rows):
+        t.offset, t.n, t.k, t.out_offset, t.pad = int(off), int(n), int(k), int(oo), 0
+    return tab
+
+
+def step(w: np.ndarray, g: Sequence[np.ndarray], r: Sequence[np.ndarray], rows, leader: np.ndarray,
+         eps: float, scale: float, accumulate_mask: Sequence[int] | None = None):
+    """One whole emulated step on flat host buffers; w and every r[p] are updated
+    in place.  -> (idx, val, sum, thr[n_layers] as uint32 array of shape (L, 3))."""
+    rows = list(rows)
+    tab = layer_table(rows)
+    W = len(r)
+    total = sum(int(k) for (_, _, k, _) in rows)
+    idx = np.empty(total, np.uint32)
+    val = np.empty(total, np.float32)
+    sm = np.empty(total, np.float32)
+    thr = (Threshold * len(rows))()
+    acc = None
+    if accumulate_mask is not None:
+        acc = (C.c_uint8 * W)(*[1 if a else 0 for a in accumulate_mask])
+    leader = np.ascontiguousarray(leader, np.uint32)
+    rc = lib().oracle_step(_f32(w), _ptr_array(g), _ptr_array(r), acc, W, tab, _u32(leader), len(rows),
+                           C.c_float(eps), C.c_float(scale), _u32(idx), _f32(val), _f32(sm), thr)
+    if rc:
+        raise ValueError("oracle_step: rc=%d" % rc)
+    thr_np = np.array([(t.key, t.n_gt, t.n_eq_take) for t in thr], np.uint32).reshape(len(rows), 3)
+    return idx, val, sm, thr_np

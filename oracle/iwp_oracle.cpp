@@ -1,0 +1,229 @@
+// Oracle for the importance-weighted-pruning compression step (arXiv 1901.01544).
+//
+// TEST INFRASTRUCTURE ONLY.  This file is the plain, slow, single-threaded CPU
+// definition of what the GPU path must compute.  It shares no code, header,
+// table or helper with the HIP library and is called only by the tests, by the
+// smoke check and by the benchmark's cpu_baseline leg.  The product path never
+// routes through it.
+//
+// What it computes (paper, Algorithm 1, the body of the per-layer loop and the
+// reduce/update lines after it; Section 3.2 for the importance measure):
+//
+//   O1  local accumulation      r[i] <- r[i] + g[i]                   (Alg. 1, the
+//       accumulation line before the layer loop, read as residual accumulation;
+//       Eq. 3 and the "for local accumulation" line)
+//   O2  importance              s[i] = |r[i]| / (|w[i]| + eps)        (Alg. 1, mask line;
+//       abstract: ratio of gradient to parameter value)
+//   O3  selection               the k elements that come first under the total
+//       order (score descending, index ascending): a full sort.  Stands in for
+//       "choose threshold" + "Mask <- importance > thr" of Alg. 1 with the
+//       threshold placed at the k-th largest score.
+//   O4  split                   idx = selected positions ascending,
+//       val[j] = r[idx[j]] bit for bit                                (Alg. 1, G~ = grad (.) Mask)
+//   O5  reduce                  sum[j] = ((R_0[idx_j] + R_1[idx_j]) + ...) + R_{W-1}[idx_j]
+//       fixed left fold starting from R_0's value                     (Alg. 1, ring all-reduce line)
+//   O6  update                  w[idx_j] <- w[idx_j] + (scale * sum[j]), two roundings
+//                                                                     (Alg. 1, SGD line; Eq. 3)
+//   O7  clear                   R_p[idx_j] <- +0.0f for every worker  (Alg. 1, G = grad (.) not Mask)
+//
+// Arithmetic is IEEE-754 binary32, round to nearest even, denormals kept, no
+// contraction (build with -ffp-contract=off, never -ffast-math).
+//
+// Pins (tests/test_oracle_pins.py): brute-force rank count on tiny layers,
+// cardinality, exact conservation, the paper's 64x / 58.8x ratios as keep
+// fractions, numpy lexsort cross-check, threshold-mask equivalence with the
+// paper's "importance > thr" mask, dense masked formulation of the reduce and
+// update, closed forms, exact-rational check of the divide, hand-worked example.
+// No function here is "parity unpinned".
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <vector>
+
+extern "C" {
+
+typedef struct {
+    uint32_t key;        // bit pattern of the k-th largest score
+    uint32_t n_gt;       // number of elements with score strictly above it
+    uint32_t n_eq_take;  // how many of the elements equal to it are kept (lowest indices)
+} oracle_threshold;
+
+typedef struct {
+    int64_t offset;       // first element of the layer in the flat buffers
+    uint32_t n;           // elements in the layer
+    uint32_t k;           // elements kept (0 = accumulate only)
+    uint32_t out_offset;  // first pair of the layer in idx/val
+    uint32_t pad;
+} oracle_layer;
+
+}  // extern "C"
+
+namespace {
+
+// Order-preserving integer image of a non-negative float: for s >= +0 the
+// unsigned order of the bit patterns equals the float order; +inf sits above
+// every finite value and a NaN (sign cleared) above +inf.
+inline uint32_t score_key(float s) {
+    uint32_t b;
+    std::memcpy(&b, &s, sizeof b);
+    return b & 0x7fffffffu;
+}
+
+struct Ranked {
+    uint32_t key;
+    uint32_t idx;
+};
+
+}  // namespace
+
+extern "C" {
+
+// O1.  Alg. 1 accumulation line / Eq. 3: one fp32 add per element.
+void oracle_accumulate(float* r, const float* g, uint64_t n) {
+    for (uint64_t i = 0; i < n; ++i) r[i] = r[i] + g[i];
+}
+
+// O2.  Alg. 1 mask line: importance of every element, eps added to |w| in fp32
+// before the divide.
+void oracle_score(const float* w, const float* r, uint64_t n, float eps, float* s) {
+    for (uint64_t i = 0; i < n; ++i) {
+        float denom = std::fabs(w[i]) + eps;
+        s[i] = std::fabs(r[i]) / denom;
+    }
+}
+
+// Integer keys of the scores (used by tests that want to look at the order).
+void oracle_score_keys(const float* w, const float* r, uint64_t n, float eps, uint32_t* key) {
+    for (uint64_t i = 0; i < n; ++i) {
+        float denom = std::fabs(w[i]) + eps;
+        key[i] = score_key(std::fabs(r[i]) / denom);
+    }
+}
+
+// O3 + the index half of O4.  Full sort by (score descending, index ascending),
+// keep the first k, return their positions in ascending order and the threshold
+// record.  Returns 0, or -1 on k > n.
+int oracle_select(const float* s, uint32_t n, uint32_t k, uint32_t* idx_out, oracle_threshold* thr) {
+    if (k > n) return -1;
+    if (thr) { thr->key = 0; thr->n_gt = 0; thr->n_eq_take = 0; }
+    if (k == 0) return 0;
+    std::vector<Ranked> perm(n);
+    for (uint32_t i = 0; i < n; ++i) { perm[i].key = score_key(s[i]); perm[i].idx = i; }
+    std::sort(perm.begin(), perm.end(), [](const Ranked& a, const Ranked& b) {
+        if (a.key != b.key) return a.key > b.key;
+        return a.idx < b.idx;
+    });
+    uint32_t tkey = perm[k - 1].key;
+    uint32_t n_gt = 0;
+    for (uint32_t i = 0; i < n; ++i) if (perm[i].key > tkey) ++n_gt;
+    if (thr) { thr->key = tkey; thr->n_gt = n_gt; thr->n_eq_take = k - n_gt; }
+    std::vector<uint32_t> chosen(k);
+    for (uint32_t j = 0; j < k; ++j) chosen[j] = perm[j].idx;
+    std::sort(chosen.begin(), chosen.end());
+    for (uint32_t j = 0; j < k; ++j) idx_out[j] = chosen[j];
+    return 0;
+}
+
+// The value half of O4: the accumulated residual itself, copied bit for bit.
+void oracle_take(const float* r, const uint32_t* idx, uint32_t k, float* val) {
+    for (uint32_t j = 0; j < k; ++j) std::memcpy(&val[j], &r[idx[j]], sizeof(float));
+}
+
+// The rank of element i under (score descending, index ascending), by counting:
+// the number of elements that come before it.  Element i is selected iff its
+// rank is < k.  O(n) per call, no sort: the route by which single outputs are
+// checked at sizes where the full sort is too slow.
+uint64_t oracle_rank_of(const float* s, uint64_t n, uint64_t i) {
+    uint32_t ki = score_key(s[i]);
+    uint64_t before = 0;
+    for (uint64_t j = 0; j < n; ++j) {
+        uint32_t kj = score_key(s[j]);
+        if (kj > ki || (kj == ki && j < i)) ++before;
+    }
+    return before;
+}
+
+// O1..O4 for one layer on one worker.  k == 0: accumulate only.
+int oracle_compress_layer(const float* w, const float* g, float* r, uint32_t n, uint32_t k, float eps,
+                          uint32_t* idx_out, float* val_out, oracle_threshold* thr) {
+    if (k > n) return -1;
+    oracle_accumulate(r, g, n);
+    if (k == 0) return 0;
+    std::vector<float> s(n);
+    oracle_score(w, r, n, eps, s.data());
+    int rc = oracle_select(s.data(), n, k, idx_out, thr);
+    if (rc) return rc;
+    oracle_take(r, idx_out, k, val_out);
+    return 0;
+}
+
+// O2..O3 without the accumulate: the threshold record of a layer.
+int oracle_select_threshold(const float* w, const float* r, uint32_t n, uint32_t k, float eps,
+                            oracle_threshold* thr) {
+    if (k > n || k == 0) return -1;
+    std::vector<float> s(n);
+    std::vector<uint32_t> idx(k);
+    oracle_score(w, r, n, eps, s.data());
+    return oracle_select(s.data(), n, k, idx.data(), thr);
+}
+
+// O5.  Fixed left fold over the workers, starting from worker 0's value.
+void oracle_gather_sum(const float* const* residuals, uint32_t W, const uint32_t* idx, uint64_t k,
+                       float* sum) {
+    for (uint64_t j = 0; j < k; ++j) {
+        float acc = residuals[0][idx[j]];
+        for (uint32_t p = 1; p < W; ++p) acc = acc + residuals[p][idx[j]];
+        sum[j] = acc;
+    }
+}
+
+// O6 then O7.  Product rounded, then sum rounded; sent residuals become +0.
+void oracle_apply_sparse_update(float* w, const uint32_t* idx, const float* sum, uint64_t k, float scale,
+                                float* const* residuals, uint32_t W) {
+    for (uint64_t j = 0; j < k; ++j) {
+        float t = scale * sum[j];
+        w[idx[j]] = w[idx[j]] + t;
+    }
+    for (uint32_t p = 0; p < W; ++p)
+        for (uint64_t j = 0; j < k; ++j) residuals[p][idx[j]] = 0.0f;
+}
+
+// One whole emulated step over a flat parameter set (Alg. 1, one iteration of
+// the outer loop): every worker accumulates every layer; the leader of each
+// layer scores, selects and emits its pairs (global flat positions, ascending
+// within the layer, layers in table order); then reduce, update and clear over
+// the concatenated index list.  pairs_total = sum of k over the table.
+// accumulate[p] == 0 skips O1 for worker p (a peer whose residual is static).
+int oracle_step(float* w, const float* const* g, float* const* r, const uint8_t* accumulate, uint32_t W,
+                const oracle_layer* layers, const uint32_t* leader, uint32_t n_layers, float eps,
+                float scale, uint32_t* idx_out, float* val_out, float* sum_out, oracle_threshold* thr_out) {
+    uint64_t pairs_total = 0;
+    for (uint32_t j = 0; j < n_layers; ++j) {
+        const oracle_layer& L = layers[j];
+        if (L.k > L.n) return -1;
+        if (L.out_offset != pairs_total) return -3;  // pairs of the layers are packed back to back
+        for (uint32_t p = 0; p < W; ++p) {
+            if (accumulate && !accumulate[p]) continue;
+            oracle_accumulate(r[p] + L.offset, g[p] + L.offset, L.n);
+        }
+        if (L.k == 0) continue;
+        uint32_t lead = leader[j];
+        if (lead >= W) return -2;
+        std::vector<float> s(L.n);
+        oracle_score(w + L.offset, r[lead] + L.offset, L.n, eps, s.data());
+        uint32_t* idx = idx_out + L.out_offset;
+        int rc = oracle_select(s.data(), L.n, L.k, idx, thr_out ? &thr_out[j] : nullptr);
+        if (rc) return rc;
+        oracle_take(r[lead] + L.offset, idx, L.k, val_out + L.out_offset);
+        for (uint32_t q = 0; q < L.k; ++q) idx[q] += (uint32_t)L.offset;  // local -> flat position
+        pairs_total += L.k;
+    }
+    std::vector<const float*> rc_ptrs(r, r + W);
+    oracle_gather_sum(rc_ptrs.data(), W, idx_out, pairs_total, sum_out);
+    oracle_apply_sparse_update(w, idx_out, sum_out, pairs_total, scale, r, W);
+    return 0;
+}
+
+}  // extern "C"
