@@ -1,0 +1,189 @@
+/*
+ * iwp.h -- C ABI of the MI355X (gfx950) library for the per-worker gradient
+ * compression step of importance weighted pruning on a ring (arXiv 1901.01544).
+ *
+ * What the calls compute follows the paper's Algorithm 1 ("Importance Weighted
+ * Pruning"): the body of its per-layer loop and the reduce / SGD lines after it,
+ * with the importance measure of Section 3.2 (|accumulated gradient / weight|).
+ * "Choose threshold" is taken as the exact k-th largest importance of the layer,
+ * k being given by the caller as an integer, so every output has a static size.
+ *
+ * Conventions for every entry point
+ *  - All buffer pointers are DEVICE pointers unless the comment says "host".
+ *    Pointer tables (g, r, residuals) are host arrays of device pointers.
+ *  - fp32 data is IEEE-754 binary32; the library computes in binary32 with
+ *    round-to-nearest-even, denormals preserved, correctly rounded divide, no
+ *    fused multiply-add.  Indices are uint32.  Inputs must be finite.
+ *  - The caller owns every buffer, the workspace included.  The hot-path calls
+ *    allocate nothing, free nothing, read nothing back to the host and keep no
+ *    state between calls; they only enqueue kernels on `hip_stream` (a
+ *    hipStream_t passed as void*, NULL = the default stream) and return.
+ *    Outputs are valid once the stream has been synchronised.  A workspace may be
+ *    reused by the next call on the same stream; its contents are scratch.
+ *  - Buffers must be 4-byte aligned.  16-byte alignment of (pointer + layer
+ *    offset) enables 128-bit accesses; anything else is handled by a slower,
+ *    equally exact path.
+ *  - Return value: IWP_OK (0) or a negative iwp_status.  Argument errors are
+ *    detected before any kernel is launched and leave all buffers untouched.
+ *  - Determinism: identical inputs give identical output bytes, run to run.
+ *  - Limits: offset + n <= IWP_MAX_FLAT for every layer; W <= IWP_MAX_WORKERS.
+ */
+#ifndef IWP_H
+#define IWP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define IWP_MAX_WORKERS 32
+#define IWP_MAX_FLAT 0xFFFF0000ull
+
+typedef enum {
+    IWP_OK = 0,
+    IWP_EINVAL = -1,     /* null pointer, k > n, W out of range, eps negative or NaN, bad table */
+    IWP_EALIGN = -2,     /* a buffer is not 4-byte aligned */
+    IWP_EWORKSPACE = -3, /* workspace missing or smaller than iwp_*workspace_bytes() */
+    IWP_ERANGE = -4,     /* offset + n exceeds IWP_MAX_FLAT */
+    IWP_EHIP = -5        /* a HIP runtime call or a launch failed; see iwp_last_hip_error() */
+} iwp_status;
+
+/* The threshold of one layer (stands for "choose threshold: thr" of Algorithm 1).
+ * key is the bit pattern of the k-th largest importance (sign bit cleared, so
+ * unsigned order == float order); n_gt elements lie strictly above it (n_gt < k);
+ * of the elements equal to it the n_eq_take = k - n_gt with the lowest indices
+ * are kept.  Lives in device memory. */
+typedef struct {
+    uint32_t key;
+    uint32_t n_gt;
+    uint32_t n_eq_take;
+} iwp_threshold;
+
+/* One row of a layer table (the layers omega[0..M] of Algorithm 1 laid out in
+ * flat buffers).  offset: first element of the layer in w / g / r; n: elements;
+ * k: elements to keep (0 = accumulate only, nothing selected); out_offset:
+ * first (index, value) pair of the layer in idx_out / val_out -- the rows must
+ * be packed, out_offset[j] = k[0] + ... + k[j-1]; pad: ignored.  Layers must
+ * not overlap. */
+typedef struct {
+    int64_t offset;
+    uint32_t n;
+    uint32_t k;
+    uint32_t out_offset;
+    uint32_t pad;
+} iwp_layer;
+
+/* ------------------------------------------------------------------ one layer */
+
+/* Workspace size in bytes for the single-layer calls on a layer of n elements. */
+size_t iwp_workspace_bytes(uint32_t n);
+
+/* Algorithm 1, per-layer body on one worker: local accumulation r <- r + g
+ * (the accumulation line, read as residual accumulation; Eq. 3), importance
+ * |r| / (|w| + eps) of every element (mask line), selection of the k most
+ * important elements under (importance descending, index ascending), and the
+ * split into the sent part: idx_out[0..k) ascending positions in the layer,
+ * val_out[j] = r[idx_out[j]] bit for bit.  r keeps every value (the sent ones are
+ * cleared later by apply_sparse_update).  k == 0: accumulate only; idx_out /
+ * val_out may then be NULL.  w, g read-only; r read-write; capacity of idx_out,
+ * val_out >= k; exactly k pairs are written. */
+int compress_layer(const float* w, const float* g, float* r, uint32_t n, uint32_t k, float eps,
+                   uint32_t* idx_out, float* val_out,
+                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* "Choose threshold" of Algorithm 1 as exact selection, without the accumulate:
+ * the threshold record of the layer's importances |r| / (|w| + eps) for 1 <= k <= n,
+ * written to thr_out (device). */
+int select_threshold(const float* w, const float* r, uint32_t n, uint32_t k, float eps,
+                     iwp_threshold* thr_out,
+                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Mask and split lines of Algorithm 1 for a given threshold record `thr` (device,
+ * as written by select_threshold for the same w, r, eps, k): emits the k pairs
+ * (ascending index, residual value) of the elements above the threshold plus the
+ * first thr->n_eq_take elements equal to it. */
+int compact_pairs(const float* w, const float* r, uint32_t n, float eps, const iwp_threshold* thr,
+                  uint32_t k, uint32_t* idx_out, float* val_out,
+                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ------------------------------------------------------------------ exchange */
+
+/* Arithmetic of the ring all-reduce line of Algorithm 1 on one index set: every
+ * worker's residual taken at the leader's indices and summed in the fixed order
+ * sum_out[j] = ((R_0[idx_j] + R_1[idx_j]) + ...) + R_{W-1}[idx_j], starting from
+ * R_0's value.  residuals: host array of W device pointers (flat buffers that idx
+ * indexes); idx: k positions, each < the buffers' length (not checked). */
+int gather_sum_at_indices(const float* const* residuals, uint32_t W, const uint32_t* idx, uint32_t k,
+                          float* sum_out, void* hip_stream);
+
+/* SGD line of Algorithm 1 / Eq. 3 on the reduced sparse vector, then the
+ * "not Mask" line: w[idx_j] <- w[idx_j] + (scale * sum[j]) with the product and
+ * the sum each rounded once, and R_p[idx_j] <- +0.0f for the W buffers listed in
+ * residuals_to_clear (host array of device pointers; W may be 0).  idx must hold
+ * distinct positions (what compaction produces). */
+int apply_sparse_update(float* w, const uint32_t* idx, const float* sum, uint32_t k, float scale,
+                        float* const* residuals_to_clear, uint32_t W, void* hip_stream);
+
+/* ------------------------------------------------------------------ all layers in one pass */
+
+/* A plan holds a layer table (copied) and its device image.  Creating and
+ * destroying a plan are set-up calls: they allocate / free a small device table
+ * and synchronise; they are not part of the hot path. */
+typedef struct iwp_plan iwp_plan;
+
+/* layers: host array of n_layers rows, validated here (packed out_offsets, k <= n,
+ * no overlap in table order, range). */
+int iwp_plan_create(const iwp_layer* layers, uint32_t n_layers, iwp_plan** plan_out);
+void iwp_plan_destroy(iwp_plan* plan);
+/* Workspace bytes the segmented calls need for this plan. */
+size_t iwp_plan_workspace_bytes(const iwp_plan* plan);
+/* Sum of k over the plan's layers: the number of pairs the segmented calls emit. */
+uint64_t iwp_plan_total_pairs(const iwp_plan* plan);
+
+/* The whole per-layer loop of Algorithm 1 for W workers emulated on one GPU, in a
+ * number of launches that does not depend on the layer count.  For every layer j
+ * of the plan and every worker p with g[p] != NULL: r[p] <- r[p] + g[p] on the
+ * layer's range.  For every layer with k > 0 the worker leader[j] (device array
+ * of n_layers entries, each < W; NULL = worker 0 leads everything) is the
+ * randomly chosen node of Algorithm 1: its accumulated residual is scored,
+ * selected and split exactly as in compress_layer.  Emitted indices are GLOBAL
+ * positions in the flat buffers (offset + position in layer), ascending within a
+ * layer, layers in table order starting at out_offset; val_out alike.
+ * thr_out: device array of n_layers records, or NULL.  w: flat weights; g, r:
+ * host arrays of W device pointers to flat buffers with w's layout. */
+int compress_segmented(const iwp_plan* plan, const float* w, const float* const* g, float* const* r,
+                       uint32_t W, const uint32_t* leader, float eps,
+                       uint32_t* idx_out, float* val_out, iwp_threshold* thr_out,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* select_threshold for every layer of the plan with k > 0 on one flat residual
+ * buffer r; thr_out: device array of n_layers records (rows with k == 0 untouched). */
+int select_threshold_segmented(const iwp_plan* plan, const float* w, const float* r, float eps,
+                               iwp_threshold* thr_out,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* compact_pairs for every layer of the plan with k > 0, given thr (device array of
+ * n_layers records); global indices as in compress_segmented. */
+int compact_pairs_segmented(const iwp_plan* plan, const float* w, const float* r, float eps,
+                            const iwp_threshold* thr, uint32_t* idx_out, float* val_out,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ------------------------------------------------------------------ helpers */
+
+/* The importance keys exactly as the kernels compute them: key_out[i] = bit
+ * pattern of |r[i]| / (|w[i]| + eps) with the sign bit cleared.  For tests of
+ * the device arithmetic; not on the hot path. */
+int iwp_score_keys(const float* w, const float* r, uint32_t n, float eps, uint32_t* key_out,
+                   void* hip_stream);
+
+/* Text for a status code; never NULL. */
+const char* iwp_strerror(int code);
+/* Text of the last HIP error the calling thread hit inside the library ("" if none). */
+const char* iwp_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IWP_H */
