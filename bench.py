@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the whole hot path on one MI355X.
+
+A *step* is one pass of every stage over one batch of synthetic gradients:
+all W simulated workers accumulate all layers, the leader of each layer scores,
+selects and compacts its pairs (compress_segmented), every worker's residual is
+gathered at the index set and summed (gather_sum_at_indices), and the weights are
+updated and the sent residuals cleared (apply_sparse_update).  Inputs are resident
+in HBM before the timed region.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload alexnet|resnet50|many_small|tiny|flat]
+
+Prints ONE JSON line (see the design doc for the fields).  The default workload is the
+AlexNet-shaped set the headline metric is quoted on.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published peak HBM3E bandwidth
+WORKLOADS = {"tiny": 1, "alexnet": 2, "resnet50": 3, "many_small": 4, "flat": 5}
+DOMINANT_KERNEL = "k_accumulate_hist"
+
+
+def step_bytes(ps, W_acc, W_list):
+    """Algorithmic bytes of one step: W_acc workers accumulate (12 B/elem), the
+    leader also reads w (4 B/elem), 8 B per pair out, and the exchange floor
+    (12 + 8 W) B per pair (index, W gathers, weight read-modify-write, W clears)."""
+    return (12 * W_acc + 4) * ps.P + (8 + 12 + 8 * W_list) * ps.K
+
+
+def dominant_kernel_bytes(ps, W_acc):
+    """Algorithmic bytes one launch of the accumulate + score kernel moves."""
+    return (12 * W_acc + 4) * ps.P
+
+
+def traffic_from_profiles(workload):
+    """HBM bytes per launch of the dominant kernel from the committed counter runs
+    (profiles/traffic.json), or None if no such measurement exists."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload, {}).get(DOMINANT_KERNEL)
+    except (OSError, ValueError):
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="alexnet", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--scale-down", type=int, default=1, help="shrink the many_small / flat workloads (debug)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU; --gpus N with N > 1 is not supported "
+              "(the path shards by worker, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_1901_01544_amd import iwp, workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    iwp.load()
+    dev = torch.device("cuda:0")
+    cfg = WORKLOADS[args.workload]
+    ps = wl.make_config(cfg, scale_down=args.scale_down)
+    flat_cfg = cfg == 5
+    W_list = ps.W + 1 if flat_cfg else ps.W            # config 5: local worker + 8 static peers
+    W_acc = 1 if flat_cfg else ps.W
+    pool = 2 if flat_cfg else ps.W
+
+    t0 = time.time()
+    if flat_cfg:
+        # 1e9-element buffers are drawn on the device (seeded); same laws as the host generator
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(ps.seed)
+        w = torch.empty(ps.flat, device=dev).normal_(0.0, ps.weight_std, generator=gen)
+
+        def laplace():
+            u = torch.empty(ps.flat, device=dev).uniform_(-0.5, 0.5, generator=gen)
+            return -ps.grad_b * torch.sign(u) * torch.log1p(-2.0 * u.abs())
+        grads = [laplace() for _ in range(pool)]
+        r = [torch.zeros(ps.flat, device=dev)] + [laplace() for _ in range(8)]
+        w_np = grads_np = None
+    else:
+        w_np = wl.gen_weights(ps)
+        grads_np = [wl.gen_gradient(ps, s) for s in range(pool)]
+        w = torch.from_numpy(w_np).to(dev)
+        grads = [torch.from_numpy(g).to(dev) for g in grads_np]
+        r = [torch.zeros(ps.flat, device=dev) for _ in range(ps.W)]
+    gen_s = time.time() - t0
+
+    plan = iwp.Plan(ps.rows())
+    ws = torch.empty(max(1, plan.workspace_bytes), dtype=torch.uint8, device=dev)
+    idx = torch.empty(ps.K, dtype=torch.int32, device=dev)
+    val = torch.empty(ps.K, dtype=torch.float32, device=dev)
+    sm = torch.empty(ps.K, dtype=torch.float32, device=dev)
+    thr = torch.zeros(3 * len(ps.layers), dtype=torch.int32, device=dev)
+    total = args.warmup + args.steps
+    if flat_cfg:
+        lead_np = np.zeros((total, 1), np.int32)
+    else:
+        lead_np = np.stack([wl.leaders(ps, t).astype(np.int32) for t in range(total)])
+    leaders = torch.from_numpy(lead_np).to(dev)
+    eps, scale = float(ps.eps), float(ps.scale)
+    stream = torch.cuda.current_stream()
+
+    def step(t):
+        if flat_cfg:
+            g = [grads[t % pool]] + [None] * 8
+        else:
+            g = [grads[wl.gradient_set_of(ps, p, t, pool)] for p in range(ps.W)]
+        iwp.compress_segmented(plan, w, g, r, leaders[t], eps, idx, val, thr, ws, stream)
+        iwp.gather_sum_at_indices(r, idx, ps.K, sm, stream)
+        iwp.apply_sparse_update(w, idx, sm, ps.K, scale, r, stream)
+
+    # plain-copy ceiling of this machine (read 1 : write 1), quoted beside the result
+    a = torch.empty(1 << 28, device=dev)
+    b = torch.empty(1 << 28, device=dev)
+    for _ in range(3):
+        iwp.copy_f32(b, a, stream)
+    iwp.timing_enable("k_copy", 16)
+    for _ in range(10):
+        iwp.copy_f32(b, a, stream)
+    torch.cuda.synchronize()
+    ms, cnt = iwp.timing_collect()
+    copy_gbps = 2 * 4 * a.numel() * cnt / (ms * 1e-3) / 1e9
+    del a, b
+
+    for t in range(args.warmup):
+        step(t)
+    torch.cuda.synchronize()
+    iwp.timing_enable(DOMINANT_KERNEL, args.steps)
+    t0 = time.perf_counter()
+    for t in range(args.warmup, total):
+        step(t)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    k_ms, k_cnt = iwp.timing_collect()
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    params_per_s = ps.P * args.steps / elapsed
+    algo_bytes = step_bytes(ps, W_acc, W_list)
+    dom_bytes = dominant_kernel_bytes(ps, W_acc)
+    dom_ms = k_ms / max(1, k_cnt)
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    out = {
+        "metric": "params/sec and achieved HBM GB/s (% of peak) for compress+exchange step",
+        "value": params_per_s,
+        "unit": "params/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": ps.name, "config_id": cfg, "tensors": len(ps.layers), "params": ps.P,
+                   "pairs_per_step": ps.K, "workers_accumulating": W_acc, "residual_list": W_list,
+                   "keep": "1/64" if cfg in (1, 2) else ("1/58.8" if cfg == 3 else ("U(0.5%,5%)" if cfg == 4 else "0.1%")),
+                   "eps": eps, "gradient_pool": pool},
+        "worker_params_per_s": ps.P * W_acc * args.steps / elapsed,
+        "step_algorithmic_bytes": algo_bytes,
+        "step_algorithmic_GBps": algo_bytes / (ms_per_step * 1e-3) / 1e9,
+        "step_frac_of_hbm_peak": algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "copy_kernel_GBps": copy_gbps,
+        "input_generation_s": gen_s,
+        "roofline": {
+            "bound": "hbm",
+            "kernel": DOMINANT_KERNEL,
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBPS,
+            "traffic": traffic_from_profiles(args.workload),
+            "algorithmic_bytes_per_launch": dom_bytes,
+            "avg_launch_ms": dom_ms,
+            "launches_timed": k_cnt,
+            "share_of_step_time": dom_ms / ms_per_step,
+        },
+    }
+
+    if not args.no_cpu_baseline and not flat_cfg:
+        import oracle
+        # the oracle as it stands, one host core, on a bounded sample: whole steps of the
+        # same workload until ~10 s of CPU work have been spent (at least one step)
+        w_ref = w_np.copy()
+        r_ref = [np.zeros(ps.flat, np.float32) for _ in range(ps.W)]
+        n_steps, spent = 0, 0.0
+        while n_steps < 1 or (spent < 10.0 and n_steps < args.steps):
+            g = [grads_np[wl.gradient_set_of(ps, p, n_steps, pool)] for p in range(ps.W)]
+            lead = wl.leaders(ps, n_steps)
+            t1 = time.perf_counter()
+            oracle.step(w_ref, g, r_ref, ps.rows(), lead, eps, scale)
+            spent += time.perf_counter() - t1
+            n_steps += 1
+        out["cpu_baseline"] = {
+            "value": ps.P * n_steps / spent,
+            "unit": "params/s",
+            "cores": 1,
+            "kind": "oracle",
+            "sample": "%d whole step(s) of the same workload (all %d workers, all %d tensors), %.1f s"
+                      % (n_steps, ps.W, len(ps.layers), spent),
+            "host_cpus": os.cpu_count(),
+        }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

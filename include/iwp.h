@@ -178,6 +178,20 @@ int compact_pairs_segmented(const iwp_plan* plan, const float* w, const float* r
 int iwp_score_keys(const float* w, const float* r, uint32_t n, float eps, uint32_t* key_out,
                    void* hip_stream);
 
+/* dst[0..n) <- src[0..n), a plain streaming copy with 128-bit accesses (both
+ * 16-byte aligned): the measured HBM ceiling that throughput is quoted against
+ * and the known-size reference for scaling profiler byte counters. */
+int iwp_copy_f32(float* dst, const float* src, uint64_t n, void* hip_stream);
+
+/* Measurement aid, not on the hot path: time every launch of one kernel (by its
+ * name, e.g. "k_accumulate_hist") with HIP event pairs recorded on the stream the
+ * kernel is launched on.  enable() creates the events (at most max_launches pairs,
+ * 0 = the built-in maximum) and starts recording; collect() stops, waits for the
+ * recorded events and returns the summed duration in milliseconds and the number
+ * of launches seen.  Process-wide and not thread-safe. */
+int iwp_timing_enable(const char* kernel_name, uint32_t max_launches);
+int iwp_timing_collect(double* total_ms, uint32_t* launches);
+
 /* Text for a status code; never NULL. */
 const char* iwp_strerror(int code);
 /* Text of the last HIP error the calling thread hit inside the library ("" if none). */

@@ -37,6 +37,31 @@ int hip_fail(hipError_t e, const char* what) {
         if (e_ != hipSuccess) return hip_fail(e_, name);      \
     } while (0)
 
+// Optional timing of one named kernel with HIP events on the stream it is launched
+// on (iwp_timing_*): off by default, costs one string compare per launch when on.
+struct Timing {
+    static constexpr int MAX = 8192;
+    bool enabled = false;
+    char name[64] = "";
+    std::vector<hipEvent_t> start, stop;
+    int used = 0;
+    int dropped = 0;
+} g_timing;
+
+struct TimedLaunch {       // records an event pair around the launches made while it is alive
+    hipStream_t s;
+    int slot = -1;
+    TimedLaunch(const char* kernel, hipStream_t stream) : s(stream) {
+        if (!g_timing.enabled || strcmp(kernel, g_timing.name) != 0) return;
+        if (g_timing.used >= (int)g_timing.start.size()) { ++g_timing.dropped; return; }
+        slot = g_timing.used++;
+        (void)hipEventRecord(g_timing.start[slot], s);
+    }
+    ~TimedLaunch() {
+        if (slot >= 0) (void)hipEventRecord(g_timing.stop[slot], s);
+    }
+};
+
 inline bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
 inline size_t round256(size_t x) { return (x + 255) & ~size_t(255); }
 inline uint32_t tiles_of(uint32_t n) { return (uint32_t)(((uint64_t)n + TILE - 1) / TILE); }
@@ -78,26 +103,53 @@ int run_select_compact(const Table& T, const Workspace& ws, const ResidualPtrs& 
                        uint32_t* idx_out, float* val_out, iwp_threshold* thr_out, hipStream_t s) {
     if (!T.any_k || T.tiles == 0) return IWP_OK;
     if (from_thr == nullptr) {
-        k_pick<0><<<T.n_layers, BLOCK, 0, s>>>(T.layers, ws.hist, ws.state, thr_out);
+        {
+            TimedLaunch tl_("k_pick<0>", s);
+            k_pick<0><<<T.n_layers, BLOCK, 0, s>>>(T.layers, ws.hist, ws.state, thr_out);
+        }
         IWP_LAUNCHED("k_pick<0>");
-        k_refine_hist<1><<<T.tiles, BLOCK, 0, s>>>(R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.hist);
+        {
+            TimedLaunch tl_("k_refine_hist<1>", s);
+            k_refine_hist<1><<<T.tiles, BLOCK, 0, s>>>(R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.hist);
+        }
         IWP_LAUNCHED("k_refine_hist<1>");
-        k_pick<1><<<T.n_layers, BLOCK, 0, s>>>(T.layers, ws.hist, ws.state, thr_out);
+        {
+            TimedLaunch tl_("k_pick<1>", s);
+            k_pick<1><<<T.n_layers, BLOCK, 0, s>>>(T.layers, ws.hist, ws.state, thr_out);
+        }
         IWP_LAUNCHED("k_pick<1>");
-        k_refine_hist<2><<<T.tiles, BLOCK, 0, s>>>(R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.hist);
+        {
+            TimedLaunch tl_("k_refine_hist<2>", s);
+            k_refine_hist<2><<<T.tiles, BLOCK, 0, s>>>(R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.hist);
+        }
         IWP_LAUNCHED("k_refine_hist<2>");
-        k_pick<2><<<T.n_layers, BLOCK, 0, s>>>(T.layers, ws.hist, ws.state, thr_out);
+        {
+            TimedLaunch tl_("k_pick<2>", s);
+            k_pick<2><<<T.n_layers, BLOCK, 0, s>>>(T.layers, ws.hist, ws.state, thr_out);
+        }
         IWP_LAUNCHED("k_pick<2>");
     } else {
-        k_load_thresholds<<<(T.n_layers + BLOCK - 1) / BLOCK, BLOCK, 0, s>>>(T.layers, T.n_layers, from_thr, ws.state);
+        {
+            TimedLaunch tl_("k_load_thresholds", s);
+            k_load_thresholds<<<(T.n_layers + BLOCK - 1) / BLOCK, BLOCK, 0, s>>>(T.layers, T.n_layers, from_thr, ws.state);
+        }
         IWP_LAUNCHED("k_load_thresholds");
     }
     if (!do_compact) return IWP_OK;
-    k_tile_count<<<T.tiles, BLOCK, 0, s>>>(R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.counts);
+    {
+        TimedLaunch tl_("k_tile_count", s);
+        k_tile_count<<<T.tiles, BLOCK, 0, s>>>(R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.counts);
+    }
     IWP_LAUNCHED("k_tile_count");
-    k_tile_scan<<<T.n_layers, BLOCK, 0, s>>>(T.layers, ws.counts);
+    {
+        TimedLaunch tl_("k_tile_scan", s);
+        k_tile_scan<<<T.n_layers, BLOCK, 0, s>>>(T.layers, ws.counts);
+    }
     IWP_LAUNCHED("k_tile_scan");
-    k_compact_write<<<T.tiles, BLOCK, 0, s>>>(R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.counts, idx_out, val_out);
+    {
+        TimedLaunch tl_("k_compact_write", s);
+        k_compact_write<<<T.tiles, BLOCK, 0, s>>>(R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.counts, idx_out, val_out);
+    }
     IWP_LAUNCHED("k_compact_write");
     return IWP_OK;
 }
@@ -106,7 +158,10 @@ int launch_init(const Workspace& ws, uint32_t n_layers, bool single, uint32_t n,
     const uint64_t words = (uint64_t)n_layers * HIST_BINS;
     uint32_t grid = (uint32_t)std::min<uint64_t>((words + BLOCK - 1) / BLOCK, 4096);
     if (grid == 0) grid = 1;
-    k_init<<<grid, BLOCK, 0, s>>>(ws.hist, words, single ? ws.single_table : nullptr, n, k);
+    {
+        TimedLaunch tl_("k_init", s);
+        k_init<<<grid, BLOCK, 0, s>>>(ws.hist, words, single ? ws.single_table : nullptr, n, k);
+    }
     IWP_LAUNCHED("k_init");
     return IWP_OK;
 }
@@ -170,7 +225,10 @@ static int single_common(const float* w, const float* g, float* r, uint32_t n, u
     if (rc) return rc;
     Table T{ws.single_table, 1, tiles, k > 0};
     if (from_thr == nullptr) {
-        k_accumulate_hist<<<tiles, BLOCK, 0, s>>>(P, w, T.layers, 1, tiles, nullptr, 1, eps, ws.hist);
+        {
+            TimedLaunch tl_("k_accumulate_hist", s);
+            k_accumulate_hist<<<tiles, BLOCK, 0, s>>>(P, w, T.layers, 1, tiles, nullptr, 1, eps, ws.hist);
+        }
         IWP_LAUNCHED("k_accumulate_hist");
     }
     return run_select_compact(T, ws, R, w, nullptr, 1, eps, from_thr, do_compact, idx_out, val_out, thr_out, s);
@@ -213,7 +271,10 @@ int gather_sum_at_indices(const float* const* residuals, uint32_t W, const uint3
         if (!aligned4(residuals[p])) return IWP_EALIGN;
         R.r[p] = const_cast<float*>(residuals[p]);
     }
-    k_gather_sum<<<(k + BLOCK - 1) / BLOCK, BLOCK, 0, static_cast<hipStream_t>(hip_stream)>>>(R, W, idx, k, sum_out);
+    {
+        TimedLaunch tl_("k_gather_sum", static_cast<hipStream_t>(hip_stream));
+        k_gather_sum<<<(k + BLOCK - 1) / BLOCK, BLOCK, 0, static_cast<hipStream_t>(hip_stream)>>>(R, W, idx, k, sum_out);
+    }
     IWP_LAUNCHED("k_gather_sum");
     return IWP_OK;
 }
@@ -231,7 +292,10 @@ int apply_sparse_update(float* w, const uint32_t* idx, const float* sum, uint32_
         if (!aligned4(residuals_to_clear[p])) return IWP_EALIGN;
         R.r[p] = residuals_to_clear[p];
     }
-    k_apply_update<<<(k + BLOCK - 1) / BLOCK, BLOCK, 0, static_cast<hipStream_t>(hip_stream)>>>(w, idx, sum, k, scale, R, W);
+    {
+        TimedLaunch tl_("k_apply_update", static_cast<hipStream_t>(hip_stream));
+        k_apply_update<<<(k + BLOCK - 1) / BLOCK, BLOCK, 0, static_cast<hipStream_t>(hip_stream)>>>(w, idx, sum, k, scale, R, W);
+    }
     IWP_LAUNCHED("k_apply_update");
     return IWP_OK;
 }
@@ -324,7 +388,10 @@ int compress_segmented(const iwp_plan* plan, const float* w, const float* const*
     rc = launch_init(ws, plan->n_layers, false, 0, 0, s);
     if (rc) return rc;
     Table T{plan->dev, plan->n_layers, plan->tiles, plan->any_k};
-    k_accumulate_hist<<<W * plan->tiles, BLOCK, 0, s>>>(P, w, T.layers, T.n_layers, T.tiles, leader, W, eps, ws.hist);
+    {
+        TimedLaunch tl_("k_accumulate_hist", s);
+        k_accumulate_hist<<<W * plan->tiles, BLOCK, 0, s>>>(P, w, T.layers, T.n_layers, T.tiles, leader, W, eps, ws.hist);
+    }
     IWP_LAUNCHED("k_accumulate_hist");
     return run_select_compact(T, ws, R, w, leader, W, eps, nullptr, true, idx_out, val_out, thr_out, s);
 }
@@ -348,7 +415,10 @@ int select_threshold_segmented(const iwp_plan* plan, const float* w, const float
     memset(&R, 0, sizeof R);
     R.r[0] = const_cast<float*>(r);
     Table T{plan->dev, plan->n_layers, plan->tiles, plan->any_k};
-    k_accumulate_hist<<<plan->tiles, BLOCK, 0, s>>>(P, w, T.layers, T.n_layers, T.tiles, nullptr, 1, eps, ws.hist);
+    {
+        TimedLaunch tl_("k_accumulate_hist", s);
+        k_accumulate_hist<<<plan->tiles, BLOCK, 0, s>>>(P, w, T.layers, T.n_layers, T.tiles, nullptr, 1, eps, ws.hist);
+    }
     IWP_LAUNCHED("k_accumulate_hist");
     return run_select_compact(T, ws, R, w, nullptr, 1, eps, nullptr, false, nullptr, nullptr, thr_out, s);
 }
@@ -374,13 +444,65 @@ int compact_pairs_segmented(const iwp_plan* plan, const float* w, const float* r
 
 // ----------------------------------------------------------------- helpers
 
+int iwp_copy_f32(float* dst, const float* src, uint64_t n, void* hip_stream) {
+    if (n == 0) return IWP_OK;
+    if (!dst || !src) return IWP_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(dst) & 15u) || (reinterpret_cast<uintptr_t>(src) & 15u)) return IWP_EALIGN;
+    const uint64_t quads = n / 4;
+    uint32_t grid = (uint32_t)std::min<uint64_t>((quads + (uint64_t)BLOCK * 4 - 1) / ((uint64_t)BLOCK * 4), 1u << 20);
+    if (grid == 0) grid = 1;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    {
+        TimedLaunch tl_("k_copy", s);
+        k_copy<<<grid, BLOCK, 0, s>>>(dst, src, n);
+    }
+    IWP_LAUNCHED("k_copy");
+    return IWP_OK;
+}
+
+int iwp_timing_enable(const char* kernel_name, uint32_t max_launches) {
+    if (!kernel_name || strlen(kernel_name) >= sizeof g_timing.name) return IWP_EINVAL;
+    if (max_launches == 0 || max_launches > (uint32_t)Timing::MAX) max_launches = Timing::MAX;
+    while (g_timing.start.size() < max_launches) {
+        hipEvent_t a, b;
+        IWP_HIP(hipEventCreate(&a));
+        IWP_HIP(hipEventCreate(&b));
+        g_timing.start.push_back(a);
+        g_timing.stop.push_back(b);
+    }
+    strcpy(g_timing.name, kernel_name);
+    g_timing.used = 0;
+    g_timing.dropped = 0;
+    g_timing.enabled = true;
+    return IWP_OK;
+}
+
+int iwp_timing_collect(double* total_ms, uint32_t* launches) {
+    if (!total_ms || !launches) return IWP_EINVAL;
+    g_timing.enabled = false;
+    double sum = 0.0;
+    for (int i = 0; i < g_timing.used; ++i) {
+        IWP_HIP(hipEventSynchronize(g_timing.stop[i]));
+        float ms = 0.f;
+        IWP_HIP(hipEventElapsedTime(&ms, g_timing.start[i], g_timing.stop[i]));
+        sum += ms;
+    }
+    *total_ms = sum;
+    *launches = (uint32_t)g_timing.used;
+    g_timing.used = 0;
+    return IWP_OK;
+}
+
 int iwp_score_keys(const float* w, const float* r, uint32_t n, float eps, uint32_t* key_out, void* hip_stream) {
     if (check_eps(eps)) return IWP_EINVAL;
     if (n == 0) return IWP_OK;
     if (!w || !r || !key_out) return IWP_EINVAL;
     if (!aligned4(w) || !aligned4(r) || !aligned4(key_out)) return IWP_EALIGN;
     uint32_t grid = (uint32_t)std::min<uint64_t>(((uint64_t)n + BLOCK - 1) / BLOCK, 65536);
-    k_score_keys<<<grid, BLOCK, 0, static_cast<hipStream_t>(hip_stream)>>>(w, r, n, eps, key_out);
+    {
+        TimedLaunch tl_("k_score_keys", static_cast<hipStream_t>(hip_stream));
+        k_score_keys<<<grid, BLOCK, 0, static_cast<hipStream_t>(hip_stream)>>>(w, r, n, eps, key_out);
+    }
     IWP_LAUNCHED("k_score_keys");
     return IWP_OK;
 }

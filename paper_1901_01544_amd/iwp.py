@@ -63,6 +63,12 @@ def load() -> C.CDLL:
     L.select_threshold_segmented.argtypes = [_vp, _vp, _vp, C.c_float, _vp, _vp, C.c_size_t, _vp]
     L.compact_pairs_segmented.argtypes = [_vp, _vp, _vp, C.c_float, _vp, _vp, _vp, _vp, C.c_size_t, _vp]
     L.iwp_score_keys.argtypes = [_vp, _vp, C.c_uint32, C.c_float, _vp, _vp]
+    L.iwp_copy_f32.argtypes = [_vp, _vp, C.c_uint64, _vp]
+    L.iwp_copy_f32.restype = C.c_int
+    L.iwp_timing_enable.argtypes = [C.c_char_p, C.c_uint32]
+    L.iwp_timing_enable.restype = C.c_int
+    L.iwp_timing_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_uint32)]
+    L.iwp_timing_collect.restype = C.c_int
     L.iwp_strerror.argtypes = [C.c_int]
     L.iwp_strerror.restype = C.c_char_p
     L.iwp_last_hip_error.argtypes = []
@@ -196,3 +202,18 @@ def compact_pairs_segmented(plan: Plan, w, r, eps: float, thr, idx_out, val_out,
 
 def score_keys(w, r, eps: float, key_out, stream=None):
     _check(load().iwp_score_keys(_ptr(w), _ptr(r), r.numel(), eps, _ptr(key_out), _stream(stream)), "iwp_score_keys")
+
+
+def copy_f32(dst, src, stream=None):
+    _check(load().iwp_copy_f32(_ptr(dst), _ptr(src), src.numel(), _stream(stream)), "iwp_copy_f32")
+
+
+def timing_enable(kernel_name: str, max_launches: int = 0):
+    _check(load().iwp_timing_enable(kernel_name.encode(), max_launches), "iwp_timing_enable")
+
+
+def timing_collect():
+    """-> (total milliseconds, launches) of the kernel named in timing_enable()."""
+    ms, cnt = C.c_double(), C.c_uint32()
+    _check(load().iwp_timing_collect(C.byref(ms), C.byref(cnt)), "iwp_timing_collect")
+    return ms.value, cnt.value
