@@ -5,8 +5,10 @@ A *step* is one pass of every stage over one batch of synthetic gradients:
 all W simulated workers accumulate all layers, the leader of each layer scores,
 selects and compacts its pairs (compress_segmented), every worker's residual is
 gathered at the index set and summed (gather_sum_at_indices), and the weights are
-updated and the sent residuals cleared (apply_sparse_update).  Inputs are resident
-in HBM before the timed region.
+updated and the sent residuals cleared (apply_sparse_update).  The default route
+runs the step through iwp_step_segmented, which produces the same bytes as the
+three separate calls with the exchange folded into the streaming pass.  Inputs
+are resident in HBM before the timed region.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload alexnet|resnet50|many_small|tiny|flat]
 
@@ -27,7 +29,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published peak HBM3E bandwidth
 WORKLOADS = {"tiny": 1, "alexnet": 2, "resnet50": 3, "many_small": 4, "flat": 5}
-DOMINANT_KERNEL = "k_accumulate_hist"
+DOMINANT_KERNEL = {"whole_step": "k_follow_gather", "three_calls": "k_accumulate_all"}
 
 
 def step_bytes(ps, W_acc, W_list):
@@ -37,18 +39,24 @@ def step_bytes(ps, W_acc, W_list):
     return (12 * W_acc + 4) * ps.P + (8 + 12 + 8 * W_list) * ps.K
 
 
-def dominant_kernel_bytes(ps, W_acc):
-    """Algorithmic bytes one launch of the accumulate + score kernel moves."""
-    return (12 * W_acc + 4) * ps.P
+def dominant_kernel_bytes(ps, W_acc, W_list, route):
+    """Algorithmic bytes one launch of the dominant streaming kernel moves.
+    three_calls: every worker accumulates (12 B/elem) and the leader reads w (4 B/elem).
+    whole_step: the W_acc - 1 non-leading workers accumulate (12 B/elem) and all
+    W_list - 1 non-leaders hand over their value at the K pairs and clear it:
+    index read (4 B) once per worker tile is counted once, + 4 B gathered out per worker."""
+    if route == "three_calls":
+        return (12 * W_acc + 4) * ps.P
+    return 12 * (W_acc - 1) * ps.P + (4 + 4 * (W_list - 1)) * ps.K
 
 
-def traffic_from_profiles(workload):
+def traffic_from_profiles(workload, kernel):
     """HBM bytes per launch of the dominant kernel from the committed counter runs
     (profiles/traffic.json), or None if no such measurement exists."""
     path = os.path.join(ROOT, "profiles", "traffic.json")
     try:
         with open(path) as f:
-            return json.load(f).get(workload, {}).get(DOMINANT_KERNEL)
+            return json.load(f).get(workload, {}).get(kernel)
     except (OSError, ValueError):
         return None
 
@@ -59,6 +67,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="alexnet", choices=sorted(WORKLOADS))
+    ap.add_argument("--route", default="whole_step", choices=["whole_step", "three_calls"],
+                    help="whole_step: iwp_step_segmented; three_calls: compress_segmented + gather_sum_at_indices "
+                         "+ apply_sparse_update (same results)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--scale-down", type=int, default=1, help="shrink the many_small / flat workloads (debug)")
     args = ap.parse_args()
@@ -103,7 +114,10 @@ def main():
     gen_s = time.time() - t0
 
     plan = iwp.Plan(ps.rows())
-    ws = torch.empty(max(1, plan.workspace_bytes), dtype=torch.uint8, device=dev)
+    fused = args.route == "whole_step"
+    dominant = DOMINANT_KERNEL[args.route]
+    ws_bytes = plan.step_workspace_bytes(W_list) if fused else plan.workspace_bytes
+    ws = torch.empty(max(1, ws_bytes), dtype=torch.uint8, device=dev)
     idx = torch.empty(ps.K, dtype=torch.int32, device=dev)
     val = torch.empty(ps.K, dtype=torch.float32, device=dev)
     sm = torch.empty(ps.K, dtype=torch.float32, device=dev)
@@ -122,9 +136,12 @@ def main():
             g = [grads[t % pool]] + [None] * 8
         else:
             g = [grads[wl.gradient_set_of(ps, p, t, pool)] for p in range(ps.W)]
-        iwp.compress_segmented(plan, w, g, r, leaders[t], eps, idx, val, thr, ws, stream)
-        iwp.gather_sum_at_indices(r, idx, ps.K, sm, stream)
-        iwp.apply_sparse_update(w, idx, sm, ps.K, scale, r, stream)
+        if fused:
+            iwp.step_segmented(plan, w, g, r, leaders[t], eps, scale, idx, val, sm, thr, ws, stream)
+        else:
+            iwp.compress_segmented(plan, w, g, r, leaders[t], eps, idx, val, thr, ws, stream)
+            iwp.gather_sum_at_indices(r, idx, ps.K, sm, stream)
+            iwp.apply_sparse_update(w, idx, sm, ps.K, scale, r, stream)
 
     # plain-copy ceiling of this machine (read 1 : write 1), quoted beside the result
     a = torch.empty(1 << 28, device=dev)
@@ -142,7 +159,7 @@ def main():
     for t in range(args.warmup):
         step(t)
     torch.cuda.synchronize()
-    iwp.timing_enable(DOMINANT_KERNEL, args.steps)
+    iwp.timing_enable(dominant, args.steps)
     t0 = time.perf_counter()
     for t in range(args.warmup, total):
         step(t)
@@ -153,7 +170,7 @@ def main():
     ms_per_step = elapsed * 1e3 / args.steps
     params_per_s = ps.P * args.steps / elapsed
     algo_bytes = step_bytes(ps, W_acc, W_list)
-    dom_bytes = dominant_kernel_bytes(ps, W_acc)
+    dom_bytes = dominant_kernel_bytes(ps, W_acc, W_list, args.route)
     dom_ms = k_ms / max(1, k_cnt)
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     out = {
@@ -172,7 +189,7 @@ def main():
         "config": {"workload": ps.name, "config_id": cfg, "tensors": len(ps.layers), "params": ps.P,
                    "pairs_per_step": ps.K, "workers_accumulating": W_acc, "residual_list": W_list,
                    "keep": "1/64" if cfg in (1, 2) else ("1/58.8" if cfg == 3 else ("U(0.5%,5%)" if cfg == 4 else "0.1%")),
-                   "eps": eps, "gradient_pool": pool},
+                   "eps": eps, "gradient_pool": pool, "route": args.route},
         "worker_params_per_s": ps.P * W_acc * args.steps / elapsed,
         "step_algorithmic_bytes": algo_bytes,
         "step_algorithmic_GBps": algo_bytes / (ms_per_step * 1e-3) / 1e9,
@@ -181,12 +198,12 @@ def main():
         "input_generation_s": gen_s,
         "roofline": {
             "bound": "hbm",
-            "kernel": DOMINANT_KERNEL,
+            "kernel": dominant,
             "achieved": achieved,
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBPS,
-            "traffic": traffic_from_profiles(args.workload),
+            "traffic": traffic_from_profiles(args.workload, dominant),
             "algorithmic_bytes_per_launch": dom_bytes,
             "avg_launch_ms": dom_ms,
             "launches_timed": k_cnt,

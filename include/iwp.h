@@ -77,8 +77,10 @@ typedef struct {
 
 /* ------------------------------------------------------------------ one layer */
 
-/* Workspace size in bytes for the single-layer calls on a layer of n elements. */
-size_t iwp_workspace_bytes(uint32_t n);
+/* Workspace size in bytes for the single-layer calls on a layer of n elements of
+ * which k are kept (the staging areas scale with k).  The workspace must be
+ * 256-byte aligned. */
+size_t iwp_workspace_bytes(uint32_t n, uint32_t k);
 
 /* Algorithm 1, per-layer body on one worker: local accumulation r <- r + g
  * (the accumulation line, read as residual accumulation; Eq. 3), importance
@@ -137,8 +139,10 @@ typedef struct iwp_plan iwp_plan;
  * no overlap in table order, range). */
 int iwp_plan_create(const iwp_layer* layers, uint32_t n_layers, iwp_plan** plan_out);
 void iwp_plan_destroy(iwp_plan* plan);
-/* Workspace bytes the segmented calls need for this plan. */
+/* Workspace bytes the segmented calls need for this plan (256-byte aligned). */
 size_t iwp_plan_workspace_bytes(const iwp_plan* plan);
+/* Workspace bytes iwp_step_segmented needs for this plan and W residual buffers. */
+size_t iwp_plan_step_workspace_bytes(const iwp_plan* plan, uint32_t W);
 /* Sum of k over the plan's layers: the number of pairs the segmented calls emit. */
 uint64_t iwp_plan_total_pairs(const iwp_plan* plan);
 
@@ -156,6 +160,23 @@ uint64_t iwp_plan_total_pairs(const iwp_plan* plan);
 int compress_segmented(const iwp_plan* plan, const float* w, const float* const* g, float* const* r,
                        uint32_t W, const uint32_t* leader, float eps,
                        uint32_t* idx_out, float* val_out, iwp_threshold* thr_out,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* One whole iteration of Algorithm 1's outer loop for W workers emulated on one GPU:
+ * compress_segmented, gather_sum_at_indices over r[0..W) and apply_sparse_update
+ * clearing r[0..W), with the same results bit for bit, but scheduled so that the
+ * exchange needs no scattered pass over the residuals: the leaders of all layers
+ * are accumulated, scored, selected and split first; the other workers are then
+ * accumulated in one streaming pass that also copies their residual at the
+ * leader's indices into a W x K gather matrix and leaves +0 behind; a last small
+ * kernel sums the W rows in worker order (sum_out, K values), updates
+ * w[idx] += scale * sum and is done.  A worker with g[p] == NULL is not accumulated
+ * but still gathered and cleared.  Outputs as in the three separate calls:
+ * idx_out / val_out (K pairs), sum_out (K), thr_out (n_layers records or NULL);
+ * w and every r[p] are updated in place.  Workspace: iwp_plan_step_workspace_bytes. */
+int iwp_step_segmented(const iwp_plan* plan, float* w, const float* const* g, float* const* r, uint32_t W,
+                       const uint32_t* leader, float eps, float scale,
+                       uint32_t* idx_out, float* val_out, float* sum_out, iwp_threshold* thr_out,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* select_threshold for every layer of the plan with k > 0 on one flat residual

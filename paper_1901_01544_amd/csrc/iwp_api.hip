@@ -1,9 +1,10 @@
 // Host side of the C ABI declared in include/iwp.h: argument checks, workspace
 // carving and the launch sequences.  Every compute step runs in the kernels of
-// iwp_select.hpp / iwp_exchange.hpp; nothing here touches element data and
-// nothing falls back to the CPU.
+// iwp_stream.hpp / iwp_select.hpp / iwp_exchange.hpp; nothing here touches element
+// data and nothing falls back to the CPU.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -13,6 +14,7 @@
 #include "iwp_common.hpp"
 #include "iwp_exchange.hpp"
 #include "iwp_select.hpp"
+#include "iwp_stream.hpp"
 
 using namespace iwp;
 
@@ -31,12 +33,6 @@ int hip_fail(hipError_t e, const char* what) {
         if (e_ != hipSuccess) return hip_fail(e_, #call);     \
     } while (0)
 
-#define IWP_LAUNCHED(name)                                    \
-    do {                                                      \
-        hipError_t e_ = hipGetLastError();                    \
-        if (e_ != hipSuccess) return hip_fail(e_, name);      \
-    } while (0)
-
 // Optional timing of one named kernel with HIP events on the stream it is launched
 // on (iwp_timing_*): off by default, costs one string compare per launch when on.
 struct Timing {
@@ -45,15 +41,14 @@ struct Timing {
     char name[64] = "";
     std::vector<hipEvent_t> start, stop;
     int used = 0;
-    int dropped = 0;
 } g_timing;
 
-struct TimedLaunch {       // records an event pair around the launches made while it is alive
+struct TimedLaunch {       // records an event pair around the launch made while it is alive
     hipStream_t s;
     int slot = -1;
     TimedLaunch(const char* kernel, hipStream_t stream) : s(stream) {
         if (!g_timing.enabled || strcmp(kernel, g_timing.name) != 0) return;
-        if (g_timing.used >= (int)g_timing.start.size()) { ++g_timing.dropped; return; }
+        if (g_timing.used >= (int)g_timing.start.size()) return;
         slot = g_timing.used++;
         (void)hipEventRecord(g_timing.start[slot], s);
     }
@@ -62,107 +57,132 @@ struct TimedLaunch {       // records an event pair around the launches made whi
     }
 };
 
+// Launch `kernel<<<grid, BLOCK, 0, s>>>(args...)`, timed if asked for, and turn a
+// launch failure into IWP_EHIP.
+#define IWP_LAUNCH(name, kernel, grid, s, ...)                        \
+    do {                                                              \
+        {                                                             \
+            TimedLaunch tl_(name, s);                                 \
+            kernel<<<(grid), BLOCK, 0, (s)>>>(__VA_ARGS__);           \
+        }                                                             \
+        hipError_t e_ = hipGetLastError();                            \
+        if (e_ != hipSuccess) return hip_fail(e_, name);              \
+    } while (0)
+
 inline bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
 inline size_t round256(size_t x) { return (x + 255) & ~size_t(255); }
 inline uint32_t tiles_of(uint32_t n) { return (uint32_t)(((uint64_t)n + TILE - 1) / TILE); }
+inline uint32_t stiles_of(uint32_t n) { return (uint32_t)(((uint64_t)n + STILE - 1) / STILE); }
+// Capacity of a layer's threshold-bin staging.  The threshold bin normally holds a
+// few percent of k; a layer that overflows this takes the exact RAW route.
+inline uint32_t maybe_cap_of(uint32_t n, uint32_t k) { return k == 0 ? 0u : std::min(n, std::max(4096u, k)); }
+
+struct Sizes {                // everything the workspace layout depends on
+    uint32_t n_layers, tiles, stiles;
+    uint64_t pairs, maybes;
+    uint32_t W_gather;        // rows of the gather matrix (whole-step entry point), else 0
+};
 
 // Carving of a caller-supplied workspace.
 struct Workspace {
     DevLayer* single_table;   // 2 rows, used by the single-layer entry points
-    uint32_t* hist;           // n_layers * HIST_BINS
+    uint32_t* zeroed;         // start of the region k_init clears: histograms, then states
+    uint64_t zeroed_words;
+    uint32_t* hist;           // n_layers * HIST_STRIDE
     LayerState* state;        // n_layers
-    uint2* counts;            // tiles
+    TileStage* stage;         // tiles
+    uint2* tile_counts;       // tiles
+    uint2* stile_counts;      // stiles
+    uint32_t* tile_out;       // tiles
+    StageArrays A;            // pairs (sure) / maybes entries
+    float* gathered;          // W_gather * pairs
     size_t bytes;
 };
 
-Workspace carve(void* base, uint32_t n_layers, uint32_t tiles) {
+Workspace carve(void* base, const Sizes& z) {
     Workspace ws;
-    char* p = static_cast<char*>(base);
+    const uintptr_t b = reinterpret_cast<uintptr_t>(base);
     size_t off = 0;
-    ws.single_table = reinterpret_cast<DevLayer*>(p + off);   off += round256(2 * sizeof(DevLayer));
-    ws.hist = reinterpret_cast<uint32_t*>(p + off);           off += round256((size_t)n_layers * HIST_BINS * sizeof(uint32_t));
-    ws.state = reinterpret_cast<LayerState*>(p + off);        off += round256((size_t)n_layers * sizeof(LayerState));
-    ws.counts = reinterpret_cast<uint2*>(p + off);            off += round256((size_t)tiles * sizeof(uint2));
+    auto take = [&](size_t bytes) { uintptr_t p = b + off; off += round256(bytes); return p; };
+    ws.single_table = reinterpret_cast<DevLayer*>(take(2 * sizeof(DevLayer)));
+    const size_t hist_bytes = round256((size_t)z.n_layers * HIST_STRIDE * sizeof(uint32_t));
+    const size_t state_bytes = round256((size_t)z.n_layers * sizeof(LayerState));
+    ws.hist = reinterpret_cast<uint32_t*>(take(hist_bytes));
+    ws.state = reinterpret_cast<LayerState*>(take(state_bytes));
+    ws.zeroed = ws.hist;
+    ws.zeroed_words = (hist_bytes + state_bytes) / sizeof(uint32_t);
+    ws.stage = reinterpret_cast<TileStage*>(take((size_t)z.tiles * sizeof(TileStage)));
+    ws.tile_counts = reinterpret_cast<uint2*>(take((size_t)z.tiles * sizeof(uint2)));
+    ws.stile_counts = reinterpret_cast<uint2*>(take((size_t)z.stiles * sizeof(uint2)));
+    ws.tile_out = reinterpret_cast<uint32_t*>(take((size_t)z.tiles * sizeof(uint32_t)));
+    ws.A.sure_idx = reinterpret_cast<uint32_t*>(take(z.pairs * sizeof(uint32_t)));
+    ws.A.sure_val = reinterpret_cast<float*>(take(z.pairs * sizeof(float)));
+    ws.A.maybe_key = reinterpret_cast<uint32_t*>(take(z.maybes * sizeof(uint32_t)));
+    ws.A.maybe_idx = reinterpret_cast<uint32_t*>(take(z.maybes * sizeof(uint32_t)));
+    ws.A.maybe_val = reinterpret_cast<float*>(take(z.maybes * sizeof(float)));
+    ws.gathered = reinterpret_cast<float*>(take((size_t)z.W_gather * z.pairs * sizeof(float)));
     ws.bytes = off;
     return ws;
 }
 
-struct Table {                // what the kernels need to know about a layer table
+struct Table {                // what the launches need to know about a layer table
     const DevLayer* layers;   // device, n_layers rows + sentinel
-    uint32_t n_layers;
-    uint32_t tiles;           // per worker
+    uint32_t n_layers, tiles, stiles;
+    uint64_t pairs;
     bool any_k;
 };
 
 int check_eps(float eps) { return (eps >= 0.0f && std::isfinite(eps)) ? IWP_OK : IWP_EINVAL; }
 
-// Selection + compaction on the leaders' residuals, after look 1 has filled the
-// first-digit histograms (from_thr == nullptr), or from given threshold records.
-int run_select_compact(const Table& T, const Workspace& ws, const ResidualPtrs& R, const float* w,
-                       const uint32_t* leader, uint32_t W, float eps, const iwp_threshold* from_thr, bool do_compact,
-                       uint32_t* idx_out, float* val_out, iwp_threshold* thr_out, hipStream_t s) {
-    if (!T.any_k || T.tiles == 0) return IWP_OK;
-    if (from_thr == nullptr) {
-        {
-            TimedLaunch tl_("k_pick<0>", s);
-            k_pick<0><<<T.n_layers, BLOCK, 0, s>>>(T.layers, ws.hist, ws.state, thr_out);
-        }
-        IWP_LAUNCHED("k_pick<0>");
-        {
-            TimedLaunch tl_("k_refine_hist<1>", s);
-            k_refine_hist<1><<<T.tiles, BLOCK, 0, s>>>(R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.hist);
-        }
-        IWP_LAUNCHED("k_refine_hist<1>");
-        {
-            TimedLaunch tl_("k_pick<1>", s);
-            k_pick<1><<<T.n_layers, BLOCK, 0, s>>>(T.layers, ws.hist, ws.state, thr_out);
-        }
-        IWP_LAUNCHED("k_pick<1>");
-        {
-            TimedLaunch tl_("k_refine_hist<2>", s);
-            k_refine_hist<2><<<T.tiles, BLOCK, 0, s>>>(R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.hist);
-        }
-        IWP_LAUNCHED("k_refine_hist<2>");
-        {
-            TimedLaunch tl_("k_pick<2>", s);
-            k_pick<2><<<T.n_layers, BLOCK, 0, s>>>(T.layers, ws.hist, ws.state, thr_out);
-        }
-        IWP_LAUNCHED("k_pick<2>");
-    } else {
-        {
-            TimedLaunch tl_("k_load_thresholds", s);
-            k_load_thresholds<<<(T.n_layers + BLOCK - 1) / BLOCK, BLOCK, 0, s>>>(T.layers, T.n_layers, from_thr, ws.state);
-        }
-        IWP_LAUNCHED("k_load_thresholds");
-    }
-    if (!do_compact) return IWP_OK;
-    {
-        TimedLaunch tl_("k_tile_count", s);
-        k_tile_count<<<T.tiles, BLOCK, 0, s>>>(R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.counts);
-    }
-    IWP_LAUNCHED("k_tile_count");
-    {
-        TimedLaunch tl_("k_tile_scan", s);
-        k_tile_scan<<<T.n_layers, BLOCK, 0, s>>>(T.layers, ws.counts);
-    }
-    IWP_LAUNCHED("k_tile_scan");
-    {
-        TimedLaunch tl_("k_compact_write", s);
-        k_compact_write<<<T.tiles, BLOCK, 0, s>>>(R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.counts, idx_out, val_out);
-    }
-    IWP_LAUNCHED("k_compact_write");
+int launch_init(const Workspace& ws, const DevLayer* row, const DevLayer* sentinel, hipStream_t s) {
+    uint32_t grid = (uint32_t)std::min<uint64_t>((ws.zeroed_words + BLOCK - 1) / BLOCK, 4096);
+    if (grid == 0) grid = 1;
+    DevLayer zero;
+    memset(&zero, 0, sizeof zero);
+    IWP_LAUNCH("k_init", k_init, grid, s, ws.zeroed, ws.zeroed_words, row ? ws.single_table : nullptr,
+               row ? *row : zero, sentinel ? *sentinel : zero);
     return IWP_OK;
 }
 
-int launch_init(const Workspace& ws, uint32_t n_layers, bool single, uint32_t n, uint32_t k, hipStream_t s) {
-    const uint64_t words = (uint64_t)n_layers * HIST_BINS;
-    uint32_t grid = (uint32_t)std::min<uint64_t>((words + BLOCK - 1) / BLOCK, 4096);
-    if (grid == 0) grid = 1;
-    {
-        TimedLaunch tl_("k_init", s);
-        k_init<<<grid, BLOCK, 0, s>>>(ws.hist, words, single ? ws.single_table : nullptr, n, k);
-    }
-    IWP_LAUNCHED("k_init");
+enum Stop { STOP_AT_THRESHOLD, FULL };
+
+// Selection on the leaders' residuals after look 1 has filled the first-digit
+// histograms, then (FULL) the ordered split.  fused: whole-step route (leader row
+// of the gather matrix, leader residual cleared).
+int run_select(const Table& T, const Workspace& ws, const ResidualPtrs& R, const float* w, const uint32_t* leader,
+               uint32_t W, float eps, Stop stop, bool fused, uint32_t* idx_out, float* val_out,
+               iwp_threshold* thr_out, hipStream_t s) {
+    if (!T.any_k || T.tiles == 0) return IWP_OK;
+    IWP_LAUNCH("k_pick0", k_pick0, T.n_layers, s, T.layers, ws.hist, ws.state);
+    IWP_LAUNCH("k_stage", k_stage, T.tiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.hist,
+               ws.stage, ws.A);
+    IWP_LAUNCH("k_refine2_raw", k_refine2_raw, T.stiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state,
+               ws.hist);
+    IWP_LAUNCH("k_resolve", k_resolve, T.n_layers, s, T.layers, ws.hist, ws.state, ws.A, thr_out);
+    if (stop == STOP_AT_THRESHOLD) return IWP_OK;
+    IWP_LAUNCH("k_count", k_count, T.stiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.stage, ws.A,
+               ws.tile_counts, ws.stile_counts);
+    IWP_LAUNCH("k_scan", k_scan, T.n_layers, s, T.layers, ws.stile_counts);
+    if (fused)
+        IWP_LAUNCH("k_write", k_write<true>, T.stiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.stage,
+                   ws.A, ws.tile_counts, ws.stile_counts, ws.tile_out, idx_out, val_out, ws.gathered, T.pairs);
+    else
+        IWP_LAUNCH("k_write", k_write<false>, T.stiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.stage,
+                   ws.A, ws.tile_counts, ws.stile_counts, ws.tile_out, idx_out, val_out, nullptr, T.pairs);
+    return IWP_OK;
+}
+
+// Ordered split from threshold records given by the caller (RAW route throughout).
+int run_compact_from(const Table& T, const Workspace& ws, const ResidualPtrs& R, const float* w, float eps,
+                     const iwp_threshold* thr, uint32_t* idx_out, float* val_out, hipStream_t s) {
+    if (!T.any_k || T.tiles == 0) return IWP_OK;
+    IWP_LAUNCH("k_load_thresholds", k_load_thresholds, (T.n_layers + BLOCK - 1) / BLOCK, s, T.layers, T.n_layers, thr,
+               ws.state);
+    IWP_LAUNCH("k_count", k_count, T.stiles, s, R, w, T.layers, T.n_layers, nullptr, 1u, eps, ws.state, ws.stage, ws.A,
+               ws.tile_counts, ws.stile_counts);
+    IWP_LAUNCH("k_scan", k_scan, T.n_layers, s, T.layers, ws.stile_counts);
+    IWP_LAUNCH("k_write", k_write<false>, T.stiles, s, R, w, T.layers, T.n_layers, nullptr, 1u, eps, ws.state, ws.stage,
+               ws.A, ws.tile_counts, ws.stile_counts, ws.tile_out, idx_out, val_out, nullptr, T.pairs);
     return IWP_OK;
 }
 
@@ -171,11 +191,8 @@ int launch_init(const Workspace& ws, uint32_t n_layers, bool single, uint32_t n,
 struct iwp_plan {
     std::vector<iwp_layer> rows;
     DevLayer* dev = nullptr;      // n_layers + 1 rows
-    uint32_t n_layers = 0;
-    uint32_t tiles = 0;
-    uint64_t pairs = 0;
+    Sizes z{};
     bool any_k = false;
-    size_t ws_bytes = 0;
 };
 
 extern "C" {
@@ -184,7 +201,7 @@ const char* iwp_strerror(int code) {
     switch (code) {
         case IWP_OK: return "ok";
         case IWP_EINVAL: return "invalid argument";
-        case IWP_EALIGN: return "buffer not 4-byte aligned";
+        case IWP_EALIGN: return "buffer not aligned as required";
         case IWP_EWORKSPACE: return "workspace missing or too small";
         case IWP_ERANGE: return "layer does not fit the 32-bit index range";
         case IWP_EHIP: return "HIP runtime error";
@@ -194,23 +211,33 @@ const char* iwp_strerror(int code) {
 
 const char* iwp_last_hip_error(void) { return g_hip_error; }
 
-size_t iwp_workspace_bytes(uint32_t n) { return carve(nullptr, 1, tiles_of(n)).bytes; }
-
 // ----------------------------------------------------------------- single layer
 
-static int single_common(const float* w, const float* g, float* r, uint32_t n, uint32_t k, float eps,
-                         const iwp_threshold* from_thr, bool do_compact, uint32_t* idx_out, float* val_out,
-                         iwp_threshold* thr_out, void* workspace, size_t workspace_bytes, hipStream_t s) {
+static Sizes single_sizes(uint32_t n, uint32_t k) {
+    Sizes z;
+    z.n_layers = 1; z.tiles = tiles_of(n); z.stiles = stiles_of(n);
+    z.pairs = k; z.maybes = maybe_cap_of(n, k); z.W_gather = 0;
+    return z;
+}
+
+size_t iwp_workspace_bytes(uint32_t n, uint32_t k) { return carve(nullptr, single_sizes(n, std::min(n, k))).bytes; }
+
+enum SingleOp { OP_COMPRESS, OP_SELECT, OP_COMPACT };
+
+static int single_common(SingleOp op, const float* w, const float* g, float* r, uint32_t n, uint32_t k, float eps,
+                         const iwp_threshold* from_thr, uint32_t* idx_out, float* val_out, iwp_threshold* thr_out,
+                         void* workspace, size_t workspace_bytes, hipStream_t s) {
     if (k > n) return IWP_EINVAL;
     if (check_eps(eps)) return IWP_EINVAL;
     if (n > IWP_MAX_FLAT) return IWP_ERANGE;
     if (n == 0) return IWP_OK;
-    if (!r || (k > 0 && !w) || (k > 0 && do_compact && (!idx_out || !val_out))) return IWP_EINVAL;
+    const bool emits = op != OP_SELECT && k > 0;
+    if (!r || (k > 0 && !w) || (emits && (!idx_out || !val_out))) return IWP_EINVAL;
     if (!aligned4(w) || !aligned4(g) || !aligned4(r) || !aligned4(idx_out) || !aligned4(val_out) ||
         !aligned4(thr_out) || !aligned4(from_thr))
         return IWP_EALIGN;
-    const uint32_t tiles = tiles_of(n);
-    Workspace ws = carve(workspace, 1, tiles);
+    const Sizes z = single_sizes(n, k);
+    Workspace ws = carve(workspace, z);
     if (!workspace || workspace_bytes < ws.bytes) return IWP_EWORKSPACE;   // holds the one-row layer table too
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return IWP_EALIGN;
 
@@ -221,38 +248,39 @@ static int single_common(const float* w, const float* g, float* r, uint32_t n, u
     ResidualPtrs R;
     memset(&R, 0, sizeof R);
     R.r[0] = r;
-    int rc = launch_init(ws, 1, true, n, k, s);
+    DevLayer row, sentinel;
+    memset(&row, 0, sizeof row);
+    memset(&sentinel, 0, sizeof sentinel);
+    row.n = n; row.k = k; row.maybe_cap = (uint32_t)z.maybes;
+    sentinel.tile_begin = z.tiles; sentinel.stile_begin = z.stiles; sentinel.out_offset = k;
+    int rc = launch_init(ws, &row, &sentinel, s);
     if (rc) return rc;
-    Table T{ws.single_table, 1, tiles, k > 0};
-    if (from_thr == nullptr) {
-        {
-            TimedLaunch tl_("k_accumulate_hist", s);
-            k_accumulate_hist<<<tiles, BLOCK, 0, s>>>(P, w, T.layers, 1, tiles, nullptr, 1, eps, ws.hist);
-        }
-        IWP_LAUNCHED("k_accumulate_hist");
-    }
-    return run_select_compact(T, ws, R, w, nullptr, 1, eps, from_thr, do_compact, idx_out, val_out, thr_out, s);
+    Table T{ws.single_table, 1, z.tiles, z.stiles, k, k > 0};
+    if (op == OP_COMPACT) return run_compact_from(T, ws, R, w, eps, from_thr, idx_out, val_out, s);
+    IWP_LAUNCH("k_accumulate_all", k_accumulate_all, z.tiles, s, P, w, T.layers, 1u, z.tiles, nullptr, 1u, eps, ws.hist);
+    return run_select(T, ws, R, w, nullptr, 1u, eps, op == OP_SELECT ? STOP_AT_THRESHOLD : FULL, false, idx_out,
+                      val_out, thr_out, s);
 }
 
 int compress_layer(const float* w, const float* g, float* r, uint32_t n, uint32_t k, float eps,
                    uint32_t* idx_out, float* val_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (n > 0 && !g) return IWP_EINVAL;
-    return single_common(w, g, r, n, k, eps, nullptr, true, idx_out, val_out, nullptr, workspace, workspace_bytes,
-                         static_cast<hipStream_t>(hip_stream));
+    return single_common(OP_COMPRESS, w, g, r, n, k, eps, nullptr, idx_out, val_out, nullptr, workspace,
+                         workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
 int select_threshold(const float* w, const float* r, uint32_t n, uint32_t k, float eps, iwp_threshold* thr_out,
                      void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (k == 0 || !thr_out) return IWP_EINVAL;
     // r is only read: no gradient pointer means no accumulation
-    return single_common(w, nullptr, const_cast<float*>(r), n, k, eps, nullptr, false, nullptr, nullptr, thr_out,
+    return single_common(OP_SELECT, w, nullptr, const_cast<float*>(r), n, k, eps, nullptr, nullptr, nullptr, thr_out,
                          workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
 int compact_pairs(const float* w, const float* r, uint32_t n, float eps, const iwp_threshold* thr, uint32_t k,
                   uint32_t* idx_out, float* val_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (k == 0 || !thr) return IWP_EINVAL;
-    return single_common(w, nullptr, const_cast<float*>(r), n, k, eps, thr, true, idx_out, val_out, nullptr,
+    return single_common(OP_COMPACT, w, nullptr, const_cast<float*>(r), n, k, eps, thr, idx_out, val_out, nullptr,
                          workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -271,11 +299,8 @@ int gather_sum_at_indices(const float* const* residuals, uint32_t W, const uint3
         if (!aligned4(residuals[p])) return IWP_EALIGN;
         R.r[p] = const_cast<float*>(residuals[p]);
     }
-    {
-        TimedLaunch tl_("k_gather_sum", static_cast<hipStream_t>(hip_stream));
-        k_gather_sum<<<(k + BLOCK - 1) / BLOCK, BLOCK, 0, static_cast<hipStream_t>(hip_stream)>>>(R, W, idx, k, sum_out);
-    }
-    IWP_LAUNCHED("k_gather_sum");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    IWP_LAUNCH("k_gather_sum", k_gather_sum, (k + BLOCK - 1) / BLOCK, s, R, W, idx, k, sum_out);
     return IWP_OK;
 }
 
@@ -292,11 +317,8 @@ int apply_sparse_update(float* w, const uint32_t* idx, const float* sum, uint32_
         if (!aligned4(residuals_to_clear[p])) return IWP_EALIGN;
         R.r[p] = residuals_to_clear[p];
     }
-    {
-        TimedLaunch tl_("k_apply_update", static_cast<hipStream_t>(hip_stream));
-        k_apply_update<<<(k + BLOCK - 1) / BLOCK, BLOCK, 0, static_cast<hipStream_t>(hip_stream)>>>(w, idx, sum, k, scale, R, W);
-    }
-    IWP_LAUNCHED("k_apply_update");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    IWP_LAUNCH("k_apply_update", k_apply_update, (k + BLOCK - 1) / BLOCK, s, w, idx, sum, k, scale, R, W);
     return IWP_OK;
 }
 
@@ -307,7 +329,7 @@ int iwp_plan_create(const iwp_layer* layers, uint32_t n_layers, iwp_plan** plan_
     *plan_out = nullptr;
     if (!layers || n_layers == 0) return IWP_EINVAL;
     std::vector<DevLayer> dev(n_layers + 1);
-    uint64_t pairs = 0, tiles = 0, end = 0;
+    uint64_t pairs = 0, maybes = 0, tiles = 0, stiles = 0, end = 0;
     bool any_k = false;
     for (uint32_t j = 0; j < n_layers; ++j) {
         const iwp_layer& L = layers[j];
@@ -315,26 +337,35 @@ int iwp_plan_create(const iwp_layer* layers, uint32_t n_layers, iwp_plan** plan_
         if ((uint64_t)L.offset < end) return IWP_EINVAL;              // table order, no overlap
         if ((uint64_t)L.offset + L.n > IWP_MAX_FLAT) return IWP_ERANGE;
         if (L.out_offset != pairs) return IWP_EINVAL;                  // packed outputs
-        dev[j].offset = (uint64_t)L.offset;
-        dev[j].n = L.n;
-        dev[j].k = L.k;
-        dev[j].out_offset = L.out_offset;
-        dev[j].tile_begin = (uint32_t)tiles;
+        DevLayer& D = dev[j];
+        memset(&D, 0, sizeof D);
+        D.offset = (uint64_t)L.offset;
+        D.maybe_begin = maybes;
+        D.n = L.n;
+        D.k = L.k;
+        D.out_offset = L.out_offset;
+        D.tile_begin = (uint32_t)tiles;
+        D.stile_begin = (uint32_t)stiles;
+        D.maybe_cap = maybe_cap_of(L.n, L.k);
         end = (uint64_t)L.offset + L.n;
         pairs += L.k;
+        maybes += D.maybe_cap;
         tiles += tiles_of(L.n);
+        stiles += stiles_of(L.n);
         any_k = any_k || L.k > 0;
         if (pairs > 0xFFFFFFFFull || tiles > 0x7FFFFFFFull / IWP_MAX_WORKERS) return IWP_ERANGE;
     }
-    dev[n_layers] = DevLayer{0, 0, 0, (uint32_t)pairs, (uint32_t)tiles};
+    DevLayer& S = dev[n_layers];
+    memset(&S, 0, sizeof S);
+    S.out_offset = (uint32_t)pairs;
+    S.tile_begin = (uint32_t)tiles;
+    S.stile_begin = (uint32_t)stiles;
+    S.maybe_begin = maybes;
     iwp_plan* plan = new (std::nothrow) iwp_plan;
     if (!plan) return IWP_EINVAL;
     plan->rows.assign(layers, layers + n_layers);
-    plan->n_layers = n_layers;
-    plan->tiles = (uint32_t)tiles;
-    plan->pairs = pairs;
+    plan->z = Sizes{n_layers, (uint32_t)tiles, (uint32_t)stiles, pairs, maybes, 0};
     plan->any_k = any_k;
-    plan->ws_bytes = carve(nullptr, n_layers, (uint32_t)tiles).bytes;
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&plan->dev), dev.size() * sizeof(DevLayer));
     if (e == hipSuccess) e = hipMemcpy(plan->dev, dev.data(), dev.size() * sizeof(DevLayer), hipMemcpyHostToDevice);
     if (e != hipSuccess) {
@@ -352,48 +383,98 @@ void iwp_plan_destroy(iwp_plan* plan) {
     delete plan;
 }
 
-size_t iwp_plan_workspace_bytes(const iwp_plan* plan) { return plan ? plan->ws_bytes : 0; }
-uint64_t iwp_plan_total_pairs(const iwp_plan* plan) { return plan ? plan->pairs : 0; }
+size_t iwp_plan_workspace_bytes(const iwp_plan* plan) { return plan ? carve(nullptr, plan->z).bytes : 0; }
 
-static int check_ws(const iwp_plan* plan, void* workspace, size_t workspace_bytes) {
-    if (!workspace || workspace_bytes < plan->ws_bytes) return IWP_EWORKSPACE;
+size_t iwp_plan_step_workspace_bytes(const iwp_plan* plan, uint32_t W) {
+    if (!plan) return 0;
+    Sizes z = plan->z;
+    z.W_gather = W;
+    return carve(nullptr, z).bytes;
+}
+
+uint64_t iwp_plan_total_pairs(const iwp_plan* plan) { return plan ? plan->z.pairs : 0; }
+
+static int check_ws(size_t need, void* workspace, size_t workspace_bytes) {
+    if (!workspace || workspace_bytes < need) return IWP_EWORKSPACE;
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return IWP_EALIGN;
+    return IWP_OK;
+}
+
+static int worker_tables(const float* const* g, float* const* r, uint32_t W, WorkerPtrs* P, ResidualPtrs* R) {
+    if (!g || !r || W == 0 || W > IWP_MAX_WORKERS) return IWP_EINVAL;
+    memset(P, 0, sizeof *P);
+    memset(R, 0, sizeof *R);
+    for (uint32_t p = 0; p < W; ++p) {
+        if (!r[p]) return IWP_EINVAL;
+        if (!aligned4(r[p]) || !aligned4(g[p])) return IWP_EALIGN;
+        P->g[p] = g[p];
+        P->r[p] = r[p];
+        R->r[p] = r[p];
+    }
     return IWP_OK;
 }
 
 int compress_segmented(const iwp_plan* plan, const float* w, const float* const* g, float* const* r, uint32_t W,
                        const uint32_t* leader, float eps, uint32_t* idx_out, float* val_out, iwp_threshold* thr_out,
                        void* workspace, size_t workspace_bytes, void* hip_stream) {
-    if (!plan || !g || !r || W == 0 || W > IWP_MAX_WORKERS) return IWP_EINVAL;
+    if (!plan) return IWP_EINVAL;
     if (check_eps(eps)) return IWP_EINVAL;
     if (plan->any_k && (!w || !idx_out || !val_out)) return IWP_EINVAL;
     if (!aligned4(w) || !aligned4(idx_out) || !aligned4(val_out) || !aligned4(thr_out) || !aligned4(leader))
         return IWP_EALIGN;
     WorkerPtrs P;
-    memset(&P, 0, sizeof P);
     ResidualPtrs R;
-    memset(&R, 0, sizeof R);
-    for (uint32_t p = 0; p < W; ++p) {
-        if (!r[p]) return IWP_EINVAL;
-        if (!aligned4(r[p]) || !aligned4(g[p])) return IWP_EALIGN;
-        P.g[p] = g[p];
-        P.r[p] = r[p];
-        R.r[p] = r[p];
-    }
-    int rc = check_ws(plan, workspace, workspace_bytes);
+    int rc = worker_tables(g, r, W, &P, &R);
     if (rc) return rc;
-    if (plan->tiles == 0) return IWP_OK;
+    Workspace ws = carve(workspace, plan->z);
+    rc = check_ws(ws.bytes, workspace, workspace_bytes);
+    if (rc) return rc;
+    if (plan->z.tiles == 0) return IWP_OK;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    Workspace ws = carve(workspace, plan->n_layers, plan->tiles);
-    rc = launch_init(ws, plan->n_layers, false, 0, 0, s);
+    rc = launch_init(ws, nullptr, nullptr, s);
     if (rc) return rc;
-    Table T{plan->dev, plan->n_layers, plan->tiles, plan->any_k};
-    {
-        TimedLaunch tl_("k_accumulate_hist", s);
-        k_accumulate_hist<<<W * plan->tiles, BLOCK, 0, s>>>(P, w, T.layers, T.n_layers, T.tiles, leader, W, eps, ws.hist);
+    Table T{plan->dev, plan->z.n_layers, plan->z.tiles, plan->z.stiles, plan->z.pairs, plan->any_k};
+    IWP_LAUNCH("k_accumulate_all", k_accumulate_all, W * T.tiles, s, P, w, T.layers, T.n_layers, T.tiles, leader, W, eps,
+               ws.hist);
+    return run_select(T, ws, R, w, leader, W, eps, FULL, false, idx_out, val_out, thr_out, s);
+}
+
+int iwp_step_segmented(const iwp_plan* plan, float* w, const float* const* g, float* const* r, uint32_t W,
+                       const uint32_t* leader, float eps, float scale, uint32_t* idx_out, float* val_out,
+                       float* sum_out, iwp_threshold* thr_out, void* workspace, size_t workspace_bytes,
+                       void* hip_stream) {
+    if (!plan) return IWP_EINVAL;
+    if (check_eps(eps) || !std::isfinite(scale)) return IWP_EINVAL;
+    if (!w) return IWP_EINVAL;
+    if (plan->any_k && (!idx_out || !val_out || !sum_out)) return IWP_EINVAL;
+    if (!aligned4(w) || !aligned4(idx_out) || !aligned4(val_out) || !aligned4(sum_out) || !aligned4(thr_out) ||
+        !aligned4(leader))
+        return IWP_EALIGN;
+    WorkerPtrs P;
+    ResidualPtrs R;
+    int rc = worker_tables(g, r, W, &P, &R);
+    if (rc) return rc;
+    Sizes z = plan->z;
+    z.W_gather = W;
+    Workspace ws = carve(workspace, z);
+    rc = check_ws(ws.bytes, workspace, workspace_bytes);
+    if (rc) return rc;
+    if (z.tiles == 0) return IWP_OK;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    rc = launch_init(ws, nullptr, nullptr, s);
+    if (rc) return rc;
+    Table T{plan->dev, z.n_layers, z.tiles, z.stiles, z.pairs, plan->any_k};
+    if (T.any_k) {
+        IWP_LAUNCH("k_leader_pass", k_leader_pass, T.stiles, s, P, w, T.layers, T.n_layers, leader, W, eps, ws.hist);
+        rc = run_select(T, ws, R, w, leader, W, eps, FULL, true, idx_out, val_out, thr_out, s);
+        if (rc) return rc;
     }
-    IWP_LAUNCHED("k_accumulate_hist");
-    return run_select_compact(T, ws, R, w, leader, W, eps, nullptr, true, idx_out, val_out, thr_out, s);
+    IWP_LAUNCH("k_follow_gather", k_follow_gather, W * T.tiles, s, P, T.layers, T.n_layers, T.tiles, leader, W, idx_out,
+               ws.tile_out, ws.gathered, T.pairs);
+    if (T.any_k)
+        IWP_LAUNCH("k_reduce_update", k_reduce_update, (uint32_t)((T.pairs + BLOCK - 1) / BLOCK), s, ws.gathered, W,
+                   T.pairs, idx_out, w, scale, sum_out);
+    return IWP_OK;
 }
 
 int select_threshold_segmented(const iwp_plan* plan, const float* w, const float* r, float eps,
@@ -401,12 +482,12 @@ int select_threshold_segmented(const iwp_plan* plan, const float* w, const float
     if (!plan || !w || !r || !thr_out) return IWP_EINVAL;
     if (check_eps(eps)) return IWP_EINVAL;
     if (!aligned4(w) || !aligned4(r) || !aligned4(thr_out)) return IWP_EALIGN;
-    int rc = check_ws(plan, workspace, workspace_bytes);
+    Workspace ws = carve(workspace, plan->z);
+    int rc = check_ws(ws.bytes, workspace, workspace_bytes);
     if (rc) return rc;
-    if (plan->tiles == 0 || !plan->any_k) return IWP_OK;
+    if (plan->z.tiles == 0 || !plan->any_k) return IWP_OK;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    Workspace ws = carve(workspace, plan->n_layers, plan->tiles);
-    rc = launch_init(ws, plan->n_layers, false, 0, 0, s);
+    rc = launch_init(ws, nullptr, nullptr, s);
     if (rc) return rc;
     WorkerPtrs P;
     memset(&P, 0, sizeof P);
@@ -414,13 +495,9 @@ int select_threshold_segmented(const iwp_plan* plan, const float* w, const float
     ResidualPtrs R;
     memset(&R, 0, sizeof R);
     R.r[0] = const_cast<float*>(r);
-    Table T{plan->dev, plan->n_layers, plan->tiles, plan->any_k};
-    {
-        TimedLaunch tl_("k_accumulate_hist", s);
-        k_accumulate_hist<<<plan->tiles, BLOCK, 0, s>>>(P, w, T.layers, T.n_layers, T.tiles, nullptr, 1, eps, ws.hist);
-    }
-    IWP_LAUNCHED("k_accumulate_hist");
-    return run_select_compact(T, ws, R, w, nullptr, 1, eps, nullptr, false, nullptr, nullptr, thr_out, s);
+    Table T{plan->dev, plan->z.n_layers, plan->z.tiles, plan->z.stiles, plan->z.pairs, plan->any_k};
+    IWP_LAUNCH("k_leader_pass", k_leader_pass, T.stiles, s, P, w, T.layers, T.n_layers, nullptr, 1u, eps, ws.hist);
+    return run_select(T, ws, R, w, nullptr, 1u, eps, STOP_AT_THRESHOLD, false, nullptr, nullptr, thr_out, s);
 }
 
 int compact_pairs_segmented(const iwp_plan* plan, const float* w, const float* r, float eps, const iwp_threshold* thr,
@@ -430,33 +507,39 @@ int compact_pairs_segmented(const iwp_plan* plan, const float* w, const float* r
     if (check_eps(eps)) return IWP_EINVAL;
     if (plan->any_k && (!idx_out || !val_out)) return IWP_EINVAL;
     if (!aligned4(w) || !aligned4(r) || !aligned4(thr) || !aligned4(idx_out) || !aligned4(val_out)) return IWP_EALIGN;
-    int rc = check_ws(plan, workspace, workspace_bytes);
+    Workspace ws = carve(workspace, plan->z);
+    int rc = check_ws(ws.bytes, workspace, workspace_bytes);
     if (rc) return rc;
-    if (plan->tiles == 0 || !plan->any_k) return IWP_OK;
+    if (plan->z.tiles == 0 || !plan->any_k) return IWP_OK;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    Workspace ws = carve(workspace, plan->n_layers, plan->tiles);
     ResidualPtrs R;
     memset(&R, 0, sizeof R);
     R.r[0] = const_cast<float*>(r);
-    Table T{plan->dev, plan->n_layers, plan->tiles, plan->any_k};
-    return run_select_compact(T, ws, R, w, nullptr, 1, eps, thr, true, idx_out, val_out, nullptr, s);
+    Table T{plan->dev, plan->z.n_layers, plan->z.tiles, plan->z.stiles, plan->z.pairs, plan->any_k};
+    return run_compact_from(T, ws, R, w, eps, thr, idx_out, val_out, s);
 }
 
 // ----------------------------------------------------------------- helpers
+
+int iwp_score_keys(const float* w, const float* r, uint32_t n, float eps, uint32_t* key_out, void* hip_stream) {
+    if (check_eps(eps)) return IWP_EINVAL;
+    if (n == 0) return IWP_OK;
+    if (!w || !r || !key_out) return IWP_EINVAL;
+    if (!aligned4(w) || !aligned4(r) || !aligned4(key_out)) return IWP_EALIGN;
+    uint32_t grid = (uint32_t)std::min<uint64_t>(((uint64_t)n + BLOCK - 1) / BLOCK, 65536);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    IWP_LAUNCH("k_score_keys", k_score_keys, grid, s, w, r, n, eps, key_out);
+    return IWP_OK;
+}
 
 int iwp_copy_f32(float* dst, const float* src, uint64_t n, void* hip_stream) {
     if (n == 0) return IWP_OK;
     if (!dst || !src) return IWP_EINVAL;
     if ((reinterpret_cast<uintptr_t>(dst) & 15u) || (reinterpret_cast<uintptr_t>(src) & 15u)) return IWP_EALIGN;
-    const uint64_t quads = n / 4;
-    uint32_t grid = (uint32_t)std::min<uint64_t>((quads + (uint64_t)BLOCK * 4 - 1) / ((uint64_t)BLOCK * 4), 1u << 20);
-    if (grid == 0) grid = 1;
+    const uint64_t blocks = (n / 4 + BLOCK - 1) / BLOCK;
+    if (blocks > 0x7FFFFFFFull) return IWP_ERANGE;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    {
-        TimedLaunch tl_("k_copy", s);
-        k_copy<<<grid, BLOCK, 0, s>>>(dst, src, n);
-    }
-    IWP_LAUNCHED("k_copy");
+    IWP_LAUNCH("k_copy", k_copy, (uint32_t)std::max<uint64_t>(blocks, 1), s, dst, src, n);
     return IWP_OK;
 }
 
@@ -472,7 +555,6 @@ int iwp_timing_enable(const char* kernel_name, uint32_t max_launches) {
     }
     strcpy(g_timing.name, kernel_name);
     g_timing.used = 0;
-    g_timing.dropped = 0;
     g_timing.enabled = true;
     return IWP_OK;
 }
@@ -490,20 +572,6 @@ int iwp_timing_collect(double* total_ms, uint32_t* launches) {
     *total_ms = sum;
     *launches = (uint32_t)g_timing.used;
     g_timing.used = 0;
-    return IWP_OK;
-}
-
-int iwp_score_keys(const float* w, const float* r, uint32_t n, float eps, uint32_t* key_out, void* hip_stream) {
-    if (check_eps(eps)) return IWP_EINVAL;
-    if (n == 0) return IWP_OK;
-    if (!w || !r || !key_out) return IWP_EINVAL;
-    if (!aligned4(w) || !aligned4(r) || !aligned4(key_out)) return IWP_EALIGN;
-    uint32_t grid = (uint32_t)std::min<uint64_t>(((uint64_t)n + BLOCK - 1) / BLOCK, 65536);
-    {
-        TimedLaunch tl_("k_score_keys", static_cast<hipStream_t>(hip_stream));
-        k_score_keys<<<grid, BLOCK, 0, static_cast<hipStream_t>(hip_stream)>>>(w, r, n, eps, key_out);
-    }
-    IWP_LAUNCHED("k_score_keys");
     return IWP_OK;
 }
 

@@ -1,6 +1,6 @@
 // Shared device-side definitions of the gfx950 kernels: tile geometry, the
-// importance key, quad (4 consecutive elements per lane) loads and the
-// wavefront / workgroup scan primitives.  Wavefronts are 64 lanes wide.
+// importance key, quad (4 consecutive elements per lane) accesses, wavefront and
+// workgroup scans, histogram pick and bitmap ranking.  Wavefronts are 64 lanes.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -14,36 +14,57 @@
 
 namespace iwp {
 
+typedef float v4f __attribute__((ext_vector_type(4)));   // one 128-bit access
+
 constexpr int BLOCK = 256;                         // 4 wavefronts
 constexpr int WAVE = 64;
-constexpr int VEC = 4;                             // one 128-bit access per lane
+constexpr int VEC = 4;
 constexpr uint32_t CHUNK = BLOCK * VEC;            // 1024 elements per workgroup iteration
-constexpr uint32_t CHUNKS_PER_TILE = 16;
-constexpr uint32_t TILE = CHUNK * CHUNKS_PER_TILE; // 16384 elements: the unit of work and of the ordered scan
+constexpr uint32_t CHUNKS_PER_TILE = 4;
+constexpr uint32_t TILE = CHUNK * CHUNKS_PER_TILE; // 4096 elements: the streaming unit (measured best on MI355X)
+constexpr uint32_t GROUP = 8;                      // tiles per super-tile
+constexpr uint32_t STILE = TILE * GROUP;           // 32768 elements: unit of the leader-side passes
+constexpr uint32_t TILE_WORDS = TILE / 32;         // words of a one-bit-per-element tile bitmap
 
 // The 31-bit key (sign bit is always 0) is resolved most-significant digit first:
-// 11 bits (exponent + 3 mantissa bits), then 10, then 10.
+// 12 bits (exponent + 4 mantissa bits), then 10, then 9.
 constexpr int DIGITS = 3;
-constexpr int HIST_BINS = 2048;                    // bins of the widest digit; per-layer histogram stride
-__host__ __device__ constexpr int digit_shift(int level) { return level == 0 ? 20 : (level == 1 ? 10 : 0); }
-__host__ __device__ constexpr int digit_bits(int level) { return level == 0 ? 11 : 10; }
+__host__ __device__ constexpr int digit_shift(int level) { return level == 0 ? 19 : (level == 1 ? 9 : 0); }
+__host__ __device__ constexpr int digit_bits(int level) { return level == 0 ? 12 : (level == 1 ? 10 : 9); }
+constexpr uint32_t HIST0 = 1u << 12, HIST1 = 1u << 10, HIST2 = 1u << 9;
+constexpr uint32_t HIST_STRIDE = HIST0 + HIST1 + HIST2;    // words per layer; each digit has its own region
+__host__ __device__ constexpr uint32_t hist_base(int level) { return level == 0 ? 0 : (level == 1 ? HIST0 : HIST0 + HIST1); }
+
+enum : uint32_t { MODE_STAGED = 0, MODE_RAW = 1 };
 
 struct DevLayer {
-    uint64_t offset;      // first element in the flat buffers
+    uint64_t offset;       // first element in the flat buffers
+    uint64_t maybe_begin;  // first entry of the layer in the staged "threshold bin" arrays (the "sure"
+                           // arrays are laid out like the pairs: out_offset)
     uint32_t n;
     uint32_t k;
-    uint32_t out_offset;  // first pair in idx_out / val_out
-    uint32_t tile_begin;  // first tile of this layer in the per-worker tile numbering
+    uint32_t out_offset;   // first pair in idx_out / val_out
+    uint32_t tile_begin;   // first TILE of the layer in the per-worker tile numbering
+    uint32_t stile_begin;  // first STILE of the layer
+    uint32_t maybe_cap;    // capacity of the layer's threshold-bin staging
 };
 
-struct LayerState {       // selection state of one layer, lives in the workspace
-    uint32_t prefix;      // key bits resolved so far (right-aligned)
-    uint32_t k_rem;       // rank still to be found inside the prefix group (1-based)
+struct LayerState {        // selection state of one layer, lives in the workspace
+    uint32_t prefix;       // key bits resolved so far (right-aligned); finally the threshold key
+    uint32_t k_rem;        // rank still to be found inside the prefix group (1-based)
     uint32_t n_gt;
     uint32_t n_eq_take;
+    uint32_t mode;         // MODE_STAGED: candidates were copied out in look 2; MODE_RAW: every pass re-reads r, w
+    uint32_t sure_used;    // staging cursors
+    uint32_t maybe_used;
+    uint32_t pad;
 };
 
-struct WorkerPtrs {       // passed by value as a kernel argument
+struct TileStage {         // where look 2 put the candidates of one tile
+    uint32_t sure_start, sure_cnt, maybe_start, maybe_cnt;
+};
+
+struct WorkerPtrs {        // passed by value as a kernel argument
     const float* g[IWP_MAX_WORKERS];
     float* r[IWP_MAX_WORKERS];
 };
@@ -60,47 +81,70 @@ __device__ __forceinline__ uint32_t score_key(float r, float w, float eps) {
     return __float_as_uint(s) & 0x7fffffffu;
 }
 
-// Which layer does tile t (per-worker numbering) belong to: the last row whose
-// tile_begin is <= t.  Uniform across the workgroup.
+// The worker that leads layer j.  The table lives in device memory, so it cannot
+// be checked on the host: an entry that is out of range is read as worker 0, which
+// keeps a bad entry from turning into a wild pointer.
+__device__ __forceinline__ uint32_t leader_of(const uint32_t* __restrict__ leader, uint32_t j, uint32_t W) {
+    const uint32_t l = leader ? leader[j] : 0u;
+    return l < W ? l : 0u;
+}
+
+// Which layer does tile t belong to: the last row whose tile_begin (or stile_begin)
+// is <= t.  Uniform across the workgroup.
+template <bool SUPER>
 __device__ __forceinline__ uint32_t find_layer(const DevLayer* __restrict__ layers, uint32_t n_layers, uint32_t t) {
-    uint32_t lo = 0, hi = n_layers;          // invariant: layers[lo].tile_begin <= t < layers[hi].tile_begin
+    uint32_t lo = 0, hi = n_layers;          // invariant: begin[lo] <= t < begin[hi]
     while (hi - lo > 1) {
-        uint32_t mid = (lo + hi) >> 1;
-        if (layers[mid].tile_begin <= t) lo = mid; else hi = mid;
+        const uint32_t mid = (lo + hi) >> 1;
+        const uint32_t b = SUPER ? layers[mid].stile_begin : layers[mid].tile_begin;
+        if (b <= t) lo = mid; else hi = mid;
     }
     return lo;
 }
 
+__device__ __forceinline__ bool is_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+template <bool NT>
+__device__ __forceinline__ v4f load_v4(const float* p) {
+    if (NT) return __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+    return *reinterpret_cast<const v4f*>(p);
+}
+template <bool NT>
+__device__ __forceinline__ void store_v4(float* p, v4f v) {
+    if (NT) __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(p));
+    else *reinterpret_cast<v4f*>(p) = v;
+}
+
 // Four consecutive elements starting at element i of a layer of n elements.
 // vec: the layer base is 16-byte aligned, so a whole quad is one 128-bit load.
-// Lanes past the end read nothing and get 0.
-__device__ __forceinline__ void load_quad(const float* __restrict__ base, uint32_t i, uint32_t n, bool vec, float (&v)[4]) {
+// Lanes past the end read nothing and get `fill`.
+__device__ __forceinline__ void load_quad(const float* __restrict__ base, uint32_t i, uint32_t n, bool vec,
+                                          float (&v)[4], float fill = 0.0f) {
     if (vec && i + 4 <= n) {
-        float4 t = *reinterpret_cast<const float4*>(base + i);
+        const v4f t = *reinterpret_cast<const v4f*>(base + i);
         v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
     } else {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) v[c] = (i + c < n) ? base[i + c] : 0.0f;
+        for (int c = 0; c < 4; ++c) v[c] = (i + c < n) ? base[i + c] : fill;
     }
 }
 
 __device__ __forceinline__ void store_quad(float* __restrict__ base, uint32_t i, uint32_t n, bool vec, const float (&v)[4]) {
     if (vec && i + 4 <= n) {
-        *reinterpret_cast<float4*>(base + i) = make_float4(v[0], v[1], v[2], v[3]);
+        v4f t; t.x = v[0]; t.y = v[1]; t.z = v[2]; t.w = v[3];
+        *reinterpret_cast<v4f*>(base + i) = t;
     } else {
 #pragma unroll
         for (int c = 0; c < 4; ++c) if (i + c < n) base[i + c] = v[c];
     }
 }
 
-__device__ __forceinline__ bool is_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-
 // Inclusive scan across the 64 lanes of a wavefront.
 __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x) {
     const int lane = threadIdx.x & (WAVE - 1);
 #pragma unroll
     for (int d = 1; d < WAVE; d <<= 1) {
-        uint32_t y = __shfl_up(x, d, WAVE);
+        const uint32_t y = __shfl_up(x, d, WAVE);
         if (lane >= d) x += y;
     }
     return x;
@@ -111,13 +155,70 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x) {
 __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t x, uint32_t* slot, uint32_t* total) {
     const int lane = threadIdx.x & (WAVE - 1);
     const int wave = threadIdx.x >> 6;
-    uint32_t inc = wave_inclusive_scan(x);
+    const uint32_t inc = wave_inclusive_scan(x);
     if (lane == WAVE - 1) slot[wave] = inc;
     __syncthreads();
-    uint32_t w0 = slot[0], w1 = slot[1], w2 = slot[2], w3 = slot[3];
-    uint32_t before = (wave > 0 ? w0 : 0) + (wave > 1 ? w1 : 0) + (wave > 2 ? w2 : 0);
+    const uint32_t w0 = slot[0], w1 = slot[1], w2 = slot[2], w3 = slot[3];
+    const uint32_t before = (wave > 0 ? w0 : 0) + (wave > 1 ? w1 : 0) + (wave > 2 ? w2 : 0);
     *total = w0 + w1 + w2 + w3;
     return before + inc - x;
+}
+
+// Digit pick over a histogram of NB bins (LDS or global): the bin that holds rank
+// k_rem counted from the top bin down, and the rank inside that bin.  All 256
+// threads call it; the result is broadcast through `sh` (BLOCK + 2 words of LDS).
+// Requires sum(hist) >= k_rem >= 1.
+template <int NB>
+__device__ __forceinline__ void block_pick(const uint32_t* hist, uint32_t k_rem, uint32_t* sh,
+                                           uint32_t* bin_out, uint32_t* k_rem_out) {
+    constexpr int PER = NB / BLOCK;
+    const uint32_t tid = threadIdx.x;
+    uint32_t h[PER];
+    uint32_t local = 0;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) { h[q] = hist[tid * PER + q]; local += h[q]; }
+    __syncthreads();                       // sh may still be in use by a previous call
+    sh[tid] = local;
+    if (tid == 0) { sh[BLOCK] = 0u; sh[BLOCK + 1] = 1u; }
+    __syncthreads();
+    for (int d = 1; d < BLOCK; d <<= 1) {  // inclusive suffix sums over the threads
+        const uint32_t v = (tid + d < BLOCK) ? sh[tid + d] : 0u;
+        __syncthreads();
+        sh[tid] += v;
+        __syncthreads();
+    }
+    const uint32_t incl = sh[tid];
+    const uint32_t above = incl - local;
+    if (above < k_rem && k_rem <= incl) {  // true for exactly one thread
+        uint32_t acc = above, bin = tid * PER;
+#pragma unroll
+        for (int q = PER - 1; q >= 0; --q) {
+            if (acc + h[q] >= k_rem) { bin = tid * PER + q; break; }
+            acc += h[q];
+        }
+        sh[BLOCK] = bin;
+        sh[BLOCK + 1] = k_rem - acc;
+    }
+    __syncthreads();
+    *bin_out = sh[BLOCK];
+    *k_rem_out = sh[BLOCK + 1];
+}
+
+// One bit per element of a tile.  prefix[w] = number of set bits in words < w.
+// Called by all 256 threads after the bitmap is complete (and synchronised).
+__device__ __forceinline__ void bitmap_prefix(const uint32_t* map, uint32_t* prefix, uint32_t* slot) {
+    const uint32_t tid = threadIdx.x;
+    const uint32_t c = tid < TILE_WORDS ? __popc(map[tid]) : 0u;
+    uint32_t tot;
+    const uint32_t ex = block_exclusive_scan(c, slot, &tot);
+    if (tid < TILE_WORDS) prefix[tid] = ex;
+    __syncthreads();
+}
+
+// Number of set bits strictly below position `local` of the tile.
+__device__ __forceinline__ uint32_t bitmap_rank(const uint32_t* map, const uint32_t* prefix, uint32_t local) {
+    const uint32_t wd = local >> 5, b = local & 31u;
+    return prefix[wd] + __popc(map[wd] & ((1u << b) - 1u));
 }
 
 }  // namespace iwp

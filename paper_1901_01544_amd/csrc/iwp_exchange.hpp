@@ -29,4 +29,21 @@ __global__ __launch_bounds__(BLOCK) void k_apply_update(float* __restrict__ w, c
     for (uint32_t p = 0; p < W; ++p) R.r[p][i] = 0.0f;
 }
 
+// Whole-step route: the residuals were already gathered into `gathered`
+// (row p = worker p's values at the K pairs, leader's row included) and cleared
+// while they streamed by, so what is left is the ordered sum over the workers and
+// the weight update.
+__global__ __launch_bounds__(BLOCK) void k_reduce_update(const float* __restrict__ gathered, uint32_t W, uint64_t K,
+                                                         const uint32_t* __restrict__ idx, float* __restrict__ w,
+                                                         float scale, float* __restrict__ sum_out) {
+    const uint64_t j = (uint64_t)blockIdx.x * BLOCK + threadIdx.x;
+    if (j >= K) return;
+    float acc = gathered[j];
+    for (uint32_t p = 1; p < W; ++p) acc = acc + gathered[(size_t)p * K + j];
+    sum_out[j] = acc;
+    const uint32_t i = idx[j];
+    const float t = scale * acc;
+    w[i] = w[i] + t;
+}
+
 }  // namespace iwp

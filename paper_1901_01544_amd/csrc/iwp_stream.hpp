@@ -1,0 +1,238 @@
+// The streaming kernels: Alg. 1's accumulation line (r <- r + g for every worker
+// and layer) fused with what can ride along on the same pass over HBM --
+//  * on the leader of a layer: the importance of every element and the histogram
+//    of its most significant key digit (first look of the selection);
+//  * on the other workers, once the leader's index set is known: the gather of
+//    the residual at those indices and the clearing of the sent positions
+//    (Alg. 1 split lines), so the exchange needs no scattered second pass.
+//
+// Work unit: one TILE (4096 elements = 4 quads per lane) per workgroup, all loads
+// of a tile issued before the first use, non-temporal accesses for data that is
+// not read again soon.  This shape measured fastest for a 2-read-1-write stream
+// on MI355X (about 6.2 TB/s against 5.3 TB/s for 16K-element tiles and 4.6 TB/s
+// for a grid-stride loop).
+#pragma once
+
+#include "iwp_common.hpp"
+
+namespace iwp {
+
+__device__ __forceinline__ void hist_add4(uint32_t* lh, v4f r, v4f w, float eps) {
+    atomicAdd(&lh[score_key(r.x, w.x, eps) >> digit_shift(0)], 1u);
+    atomicAdd(&lh[score_key(r.y, w.y, eps) >> digit_shift(0)], 1u);
+    atomicAdd(&lh[score_key(r.z, w.z, eps) >> digit_shift(0)], 1u);
+    atomicAdd(&lh[score_key(r.w, w.w, eps) >> digit_shift(0)], 1u);
+}
+
+// One tile of one worker.  ACC: add the gradient.  LEAD: score and histogram.
+// The residual written by a leader is read again by the second look, so it is
+// stored with a normal (cacheable) store; everything else streams.
+template <bool ACC, bool LEAD>
+__device__ __forceinline__ void stream_tile(const float* __restrict__ gl, float* __restrict__ rl,
+                                            const float* __restrict__ wl, uint32_t n, uint32_t base, bool vec,
+                                            float eps, uint32_t* lh) {
+    const uint32_t tid = threadIdx.x;
+    if (vec && base + TILE <= n) {
+        v4f rr[CHUNKS_PER_TILE], gg[CHUNKS_PER_TILE], ww[CHUNKS_PER_TILE];
+#pragma unroll
+        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+            const uint32_t i = base + u * CHUNK + tid * VEC;
+            rr[u] = load_v4<true>(rl + i);
+            if (ACC) gg[u] = load_v4<true>(gl + i);
+            if (LEAD) ww[u] = load_v4<false>(wl + i);
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+            const uint32_t i = base + u * CHUNK + tid * VEC;
+            if (ACC) {
+                rr[u] = rr[u] + gg[u];
+                if (LEAD) store_v4<false>(rl + i, rr[u]); else store_v4<true>(rl + i, rr[u]);
+            }
+            if (LEAD) hist_add4(lh, rr[u], ww[u], eps);
+        }
+    } else {
+        // ragged tail of a layer, or a layer whose base is not 16-byte aligned
+        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+            const uint32_t i = base + u * CHUNK + tid * VEC;
+            if (i >= n) break;
+            float rv[4], gv[4], wv[4];
+            load_quad(rl, i, n, vec, rv);
+            if (ACC) {
+                load_quad(gl, i, n, vec, gv);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) rv[q] = rv[q] + gv[q];
+                store_quad(rl, i, n, vec, rv);
+            }
+            if (LEAD) {
+                load_quad(wl, i, n, vec, wv);
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (i + q < n) atomicAdd(&lh[score_key(rv[q], wv[q], eps) >> digit_shift(0)], 1u);
+            }
+        }
+    }
+}
+
+// The leader's share of one super-tile (up to GROUP tiles of the same layer):
+// one LDS histogram of the top digit for the whole group, flushed once.
+__device__ __forceinline__ void leader_group(const float* gp, float* rp, const float* __restrict__ w, const DevLayer& L,
+                                             uint32_t first_tile /*in layer*/, float eps, uint32_t* lh,
+                                             uint32_t* __restrict__ ghist) {
+    for (uint32_t b = threadIdx.x; b < HIST0; b += BLOCK) lh[b] = 0u;
+    __syncthreads();
+    float* rl = rp + L.offset;
+    const float* gl = gp ? gp + L.offset : nullptr;
+    const float* wl = w + L.offset;
+    const bool vec = is_aligned16(rl) && is_aligned16(wl) && (!gp || is_aligned16(gl));
+    const uint32_t ntiles = (L.n + TILE - 1) / TILE;
+    const uint32_t last = min(first_tile + GROUP, ntiles);
+    for (uint32_t t = first_tile; t < last; ++t) {
+        if (gp) stream_tile<true, true>(gl, rl, wl, L.n, t * TILE, vec, eps, lh);
+        else stream_tile<false, true>(gl, rl, wl, L.n, t * TILE, vec, eps, lh);
+    }
+    __syncthreads();
+    for (uint32_t b = threadIdx.x; b < HIST0; b += BLOCK) {
+        const uint32_t v = lh[b];
+        if (v) atomicAdd(&ghist[b], v);
+    }
+}
+
+// Every worker, every layer, one launch: W * tiles workgroups, worker-major.
+// A worker without a gradient pointer is not accumulated.  The leader of a layer
+// (k > 0) works in groups of GROUP tiles: the first workgroup of a group does the
+// group, the others leave at once.
+__global__ __launch_bounds__(BLOCK) void k_accumulate_all(WorkerPtrs P, const float* __restrict__ w,
+                                                          const DevLayer* __restrict__ layers, uint32_t n_layers,
+                                                          uint32_t tiles, const uint32_t* __restrict__ leader,
+                                                          uint32_t W, float eps, uint32_t* __restrict__ hist) {
+    __shared__ uint32_t lh[HIST0];
+    const uint32_t p = blockIdx.x / tiles;
+    const uint32_t t = blockIdx.x - p * tiles;
+    const uint32_t j = find_layer<false>(layers, n_layers, t);
+    const DevLayer L = layers[j];
+    const uint32_t lt = t - L.tile_begin;
+    const float* gp = P.g[p];
+    float* rp = P.r[p];
+    if (L.k > 0 && leader_of(leader, j, W) == p) {
+        if (lt % GROUP) return;
+        leader_group(gp, rp, w, L, lt, eps, lh, hist + (size_t)j * HIST_STRIDE);
+        return;
+    }
+    if (!gp) return;
+    float* rl = rp + L.offset;
+    const float* gl = gp + L.offset;
+    stream_tile<true, false>(gl, rl, nullptr, L.n, lt * TILE, is_aligned16(rl) && is_aligned16(gl), eps, lh);
+}
+
+// Leaders only: one workgroup per super-tile of every layer with k > 0.
+__global__ __launch_bounds__(BLOCK) void k_leader_pass(WorkerPtrs P, const float* __restrict__ w,
+                                                       const DevLayer* __restrict__ layers, uint32_t n_layers,
+                                                       const uint32_t* __restrict__ leader, uint32_t W, float eps,
+                                                       uint32_t* __restrict__ hist) {
+    __shared__ uint32_t lh[HIST0];
+    const uint32_t s = blockIdx.x;
+    const uint32_t j = find_layer<true>(layers, n_layers, s);
+    const DevLayer L = layers[j];
+    if (L.k == 0) return;
+    const uint32_t p = leader_of(leader, j, W);
+    leader_group(P.g[p], P.r[p], w, L, (s - L.stile_begin) * GROUP, eps, lh, hist + (size_t)j * HIST_STRIDE);
+}
+
+// The other workers, after the leader's pairs are known: accumulate, and where the
+// tile holds sent positions, copy the accumulated value into the worker's row of
+// the gather matrix and leave +0 behind.  tile_out[t] = position (inside the
+// layer's pairs) of the first pair that falls into tile t; the pairs are ascending,
+// so a tile's pairs are contiguous.  A worker without a gradient pointer is only
+// gathered and cleared at the sent positions.
+__global__ __launch_bounds__(BLOCK) void k_follow_gather(WorkerPtrs P, const DevLayer* __restrict__ layers,
+                                                         uint32_t n_layers, uint32_t tiles,
+                                                         const uint32_t* __restrict__ leader, uint32_t W,
+                                                         const uint32_t* __restrict__ idx,
+                                                         const uint32_t* __restrict__ tile_out,
+                                                         float* __restrict__ gathered, uint64_t K) {
+    __shared__ uint32_t map[TILE_WORDS], pre[TILE_WORDS], slot[4];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t p = blockIdx.x / tiles;
+    const uint32_t t = blockIdx.x - p * tiles;
+    const uint32_t j = find_layer<false>(layers, n_layers, t);
+    const DevLayer L = layers[j];
+    const bool has_sel = L.k > 0;
+    if (has_sel && leader_of(leader, j, W) == p) return;       // done by the leader pass
+    const uint32_t lt = t - L.tile_begin;
+    const uint32_t base = lt * TILE;
+    const float* gp = P.g[p];
+    float* rl = P.r[p] + L.offset;
+    uint32_t lo = 0, cnt = 0;
+    if (has_sel) {
+        const uint32_t ntiles = (L.n + TILE - 1) / TILE;
+        lo = tile_out[t];
+        const uint32_t hi = (lt + 1 < ntiles) ? tile_out[t + 1] : L.k;
+        cnt = hi > lo ? min(hi - lo, TILE) : 0u;
+    }
+    const uint32_t* ix = idx + L.out_offset + lo;
+    float* go = gathered + (size_t)p * K + L.out_offset + lo;
+    const uint32_t first = (uint32_t)L.offset + base;           // flat position of the tile's first element
+    if (!gp) {
+        for (uint32_t e = tid; e < cnt; e += BLOCK) {
+            const uint32_t loc = ix[e] - first;
+            if (loc < TILE && base + loc < L.n) { go[e] = rl[base + loc]; rl[base + loc] = 0.0f; }
+        }
+        return;
+    }
+    const float* gl = gp + L.offset;
+    const bool vec = is_aligned16(rl) && is_aligned16(gl);
+    if (cnt == 0) {
+        stream_tile<true, false>(gl, rl, nullptr, L.n, base, vec, 0.0f, nullptr);
+        return;
+    }
+    if (tid < TILE_WORDS) map[tid] = 0u;
+    __syncthreads();
+    for (uint32_t e = tid; e < cnt; e += BLOCK) {
+        const uint32_t loc = ix[e] - first;
+        if (loc < TILE) atomicOr(&map[loc >> 5], 1u << (loc & 31u));
+    }
+    __syncthreads();
+    bitmap_prefix(map, pre, slot);
+    if (vec && base + TILE <= L.n) {
+        v4f rr[CHUNKS_PER_TILE], gg[CHUNKS_PER_TILE];
+#pragma unroll
+        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+            const uint32_t i = base + u * CHUNK + tid * VEC;
+            rr[u] = load_v4<true>(rl + i);
+            gg[u] = load_v4<true>(gl + i);
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+            const uint32_t loc = u * CHUNK + tid * VEC;
+            rr[u] = rr[u] + gg[u];
+            const uint32_t nib = (map[loc >> 5] >> (loc & 31u)) & 0xFu;
+            if (nib) {
+                uint32_t rank = bitmap_rank(map, pre, loc);
+                if (nib & 1u) { go[rank++] = rr[u].x; rr[u].x = 0.0f; }
+                if (nib & 2u) { go[rank++] = rr[u].y; rr[u].y = 0.0f; }
+                if (nib & 4u) { go[rank++] = rr[u].z; rr[u].z = 0.0f; }
+                if (nib & 8u) { go[rank++] = rr[u].w; rr[u].w = 0.0f; }
+            }
+            store_v4<true>(rl + base + loc, rr[u]);
+        }
+    } else {
+        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+            const uint32_t loc = u * CHUNK + tid * VEC;
+            const uint32_t i = base + loc;
+            if (i >= L.n) break;
+            float rv[4], gv[4];
+            load_quad(rl, i, L.n, vec, rv);
+            load_quad(gl, i, L.n, vec, gv);
+            const uint32_t nib = (map[loc >> 5] >> (loc & 31u)) & 0xFu;
+            uint32_t rank = nib ? bitmap_rank(map, pre, loc) : 0u;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                rv[q] = rv[q] + gv[q];
+                if ((nib >> q) & 1u) { go[rank++] = rv[q]; rv[q] = 0.0f; }
+            }
+            store_quad(rl, i, L.n, vec, rv);
+        }
+    }
+}
+
+}  // namespace iwp

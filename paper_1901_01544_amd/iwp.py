@@ -44,7 +44,7 @@ def load() -> C.CDLL:
             "%s is missing: build it with `python -m paper_1901_01544_amd.build`; "
             "there is no fallback path" % LIB_PATH)
     L = C.CDLL(LIB_PATH)
-    L.iwp_workspace_bytes.argtypes = [C.c_uint32]
+    L.iwp_workspace_bytes.argtypes = [C.c_uint32, C.c_uint32]
     L.iwp_workspace_bytes.restype = C.c_size_t
     L.compress_layer.argtypes = [_vp, _vp, _vp, C.c_uint32, C.c_uint32, C.c_float, _vp, _vp, _vp, C.c_size_t, _vp]
     L.select_threshold.argtypes = [_vp, _vp, C.c_uint32, C.c_uint32, C.c_float, _vp, _vp, C.c_size_t, _vp]
@@ -56,6 +56,11 @@ def load() -> C.CDLL:
     L.iwp_plan_destroy.restype = None
     L.iwp_plan_workspace_bytes.argtypes = [_vp]
     L.iwp_plan_workspace_bytes.restype = C.c_size_t
+    L.iwp_plan_step_workspace_bytes.argtypes = [_vp, C.c_uint32]
+    L.iwp_plan_step_workspace_bytes.restype = C.c_size_t
+    L.iwp_step_segmented.argtypes = [_vp, _vp, C.POINTER(_vp), C.POINTER(_vp), C.c_uint32, _vp, C.c_float, C.c_float,
+                                     _vp, _vp, _vp, _vp, _vp, C.c_size_t, _vp]
+    L.iwp_step_segmented.restype = C.c_int
     L.iwp_plan_total_pairs.argtypes = [_vp]
     L.iwp_plan_total_pairs.restype = C.c_uint64
     L.compress_segmented.argtypes = [_vp, _vp, C.POINTER(_vp), C.POINTER(_vp), C.c_uint32, _vp, C.c_float,
@@ -113,8 +118,8 @@ def _stream(stream) -> Optional[int]:
 
 # ------------------------------------------------------------------ one layer
 
-def workspace_bytes(n: int) -> int:
-    return int(load().iwp_workspace_bytes(n))
+def workspace_bytes(n: int, k: int) -> int:
+    return int(load().iwp_workspace_bytes(n, k))
 
 
 def compress_layer(w, g, r, k: int, eps: float, idx_out, val_out, workspace, stream=None, n: Optional[int] = None):
@@ -167,6 +172,9 @@ class Plan:
         self.workspace_bytes = int(load().iwp_plan_workspace_bytes(self._h))
         self.total_pairs = int(load().iwp_plan_total_pairs(self._h))
 
+    def step_workspace_bytes(self, W: int) -> int:
+        return int(load().iwp_plan_step_workspace_bytes(self._h, W))
+
     def close(self):
         if getattr(self, "_h", None):
             load().iwp_plan_destroy(self._h)
@@ -186,6 +194,15 @@ def compress_segmented(plan: Plan, w, g: Sequence, r: Sequence, leader, eps: flo
     _check(load().compress_segmented(plan._h, _ptr(w), _ptr_table(g), _ptr_table(r), len(r), _ptr(leader), eps,
                                      _ptr(idx_out), _ptr(val_out), _ptr(thr_out), _ptr(workspace), ws_bytes,
                                      _stream(stream)), "compress_segmented")
+
+
+def step_segmented(plan: Plan, w, g: Sequence, r: Sequence, leader, eps: float, scale: float, idx_out, val_out,
+                   sum_out, thr_out, workspace, stream=None):
+    assert len(g) == len(r)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().iwp_step_segmented(plan._h, _ptr(w), _ptr_table(g), _ptr_table(r), len(r), _ptr(leader), eps, scale,
+                                     _ptr(idx_out), _ptr(val_out), _ptr(sum_out), _ptr(thr_out), _ptr(workspace),
+                                     ws_bytes, _stream(stream)), "iwp_step_segmented")
 
 
 def select_threshold_segmented(plan: Plan, w, r, eps: float, thr_out, workspace, stream=None):

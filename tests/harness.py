@@ -12,9 +12,11 @@ def bits(x):
 
 class GpuSet:
     """Device-resident state of one parameter set: weights, W residuals, a pool of
-    gradient sets, plan and workspace.  All compute goes through ``iwp``."""
+    gradient sets, plan and workspace.  All compute goes through ``iwp``: either the
+    three separate calls (compress_segmented, gather_sum_at_indices,
+    apply_sparse_update) or, with fused=True, the whole-step entry point."""
 
-    def __init__(self, iwp, ps, w_np, grads_np, r_np=None, W=None):
+    def __init__(self, iwp, ps, w_np, grads_np, r_np=None, W=None, fused=False):
         import torch
         self.torch = torch
         self.iwp = iwp
@@ -29,7 +31,9 @@ class GpuSet:
             self.r = [torch.from_numpy(x).to(dev) for x in r_np]
         self.plan = iwp.Plan(ps.rows())
         assert self.plan.total_pairs == ps.K
-        self.ws = torch.empty(max(1, self.plan.workspace_bytes), dtype=torch.uint8, device=dev)
+        self.fused = fused
+        ws_bytes = self.plan.step_workspace_bytes(self.W) if fused else self.plan.workspace_bytes
+        self.ws = torch.empty(max(1, ws_bytes), dtype=torch.uint8, device=dev)
         K = max(1, ps.K)
         self.idx = torch.empty(K, dtype=torch.int32, device=dev)
         self.val = torch.empty(K, dtype=torch.float32, device=dev)
@@ -44,11 +48,17 @@ class GpuSet:
         self.val.fill_(float("nan"))
         self.leader.copy_(self.torch.from_numpy(leader_np.astype(np.int32)))
         g = [None if i is None else self.grads[i] for i in g_ids]
+        sc = float(ps.scale if scale is None else scale)
+        if self.fused:
+            self.sum.fill_(float("nan"))
+            iwp.step_segmented(self.plan, self.w, g, self.r, self.leader, float(ps.eps), sc, self.idx, self.val,
+                               self.sum, self.thr, self.ws)
+            self.torch.cuda.synchronize()
+            return
         iwp.compress_segmented(self.plan, self.w, g, self.r, self.leader, float(ps.eps), self.idx, self.val,
                                self.thr, self.ws)
         iwp.gather_sum_at_indices(self.r, self.idx, ps.K, self.sum)
-        iwp.apply_sparse_update(self.w, self.idx, self.sum, ps.K, float(ps.scale if scale is None else scale),
-                                self.r)
+        iwp.apply_sparse_update(self.w, self.idx, self.sum, ps.K, sc, self.r)
         self.torch.cuda.synchronize()
 
     def download(self):

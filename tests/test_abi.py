@@ -29,7 +29,8 @@ def declared_functions():
 def test_header_declares_the_five_named_calls():
     names = declared_functions()
     for must in ("compress_layer", "select_threshold", "compact_pairs", "gather_sum_at_indices",
-                 "apply_sparse_update", "compress_segmented", "iwp_plan_create", "iwp_workspace_bytes"):
+                 "apply_sparse_update", "compress_segmented", "iwp_step_segmented", "iwp_plan_create",
+                 "iwp_workspace_bytes"):
         assert must in names, (must, names)
 
 
@@ -41,8 +42,8 @@ def test_every_declared_symbol_is_exported(lib):
 def test_bad_arguments_are_rejected_on_the_host(lib):
     from paper_1901_01544_amd import iwp
     fake = 0x10000                                    # never dereferenced: the checks come first
-    ws_bytes = lib.iwp_workspace_bytes(1000)
-    assert ws_bytes > 0 and lib.iwp_workspace_bytes(10 ** 9) > lib.iwp_workspace_bytes(1000)
+    ws_bytes = lib.iwp_workspace_bytes(1000, 1)
+    assert ws_bytes > 0 and lib.iwp_workspace_bytes(10 ** 9, 10 ** 6) > lib.iwp_workspace_bytes(1000, 10)
     cl = lib.compress_layer
     assert cl(fake, fake, fake, 10, 11, 1e-8, fake, fake, fake, ws_bytes, None) == iwp.IWP_EINVAL      # k > n
     assert cl(fake, fake, fake, 10, 1, -1.0, fake, fake, fake, ws_bytes, None) == iwp.IWP_EINVAL       # eps < 0
@@ -83,4 +84,4 @@ def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(iwp, "_lib", None)
     monkeypatch.setattr(iwp, "LIB_PATH", str(tmp_path / "libiwp.so"))
     with pytest.raises(FileNotFoundError):
-        iwp.workspace_bytes(10)
+        iwp.workspace_bytes(10, 1)

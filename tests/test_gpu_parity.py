@@ -10,7 +10,8 @@ from paper_1901_01544_amd import workloads as wl
 from harness import GpuSet, assert_step_equal, bits
 
 pytestmark = pytest.mark.gpu
-TILE = 16384
+TILE = 4096          # streaming tile; the leader-side passes work on super-tiles of 8 tiles
+STILE = 8 * TILE
 EPS = 1e-8
 
 
@@ -34,7 +35,7 @@ def _run_single(iwp, torch, w, g, r, k, eps=EPS, misalign=0):
     rb, rd = place(r, torch.float32)
     ib = torch.full((max(1, k) + 8,), -1, dtype=torch.int32, device="cuda:0")
     vb = torch.full((max(1, k) + 8,), float("nan"), dtype=torch.float32, device="cuda:0")
-    ws = torch.empty(iwp.workspace_bytes(n), dtype=torch.uint8, device="cuda:0")
+    ws = torch.empty(iwp.workspace_bytes(n, k), dtype=torch.uint8, device="cuda:0")
     iwp.compress_layer(wd, gd, rd, k, eps, ib[misalign:], vb[misalign:], ws, n=n)
     torch.cuda.synchronize()
     idx = ib.cpu().numpy().view(np.uint32)
@@ -117,7 +118,7 @@ def test_update_is_two_roundings_not_fma(gpu_lib):
 # ---------------------------------------------------------------- one layer, edge cases
 
 @pytest.mark.parametrize("n", [1, 2, 3, 63, 64, 65, 255, 256, 257, 1023, 1024, 1025, 4097,
-                               TILE - 1, TILE, TILE + 1, 65535, 65537, 3 * TILE + 5])
+                               TILE - 1, TILE, TILE + 1, STILE - 1, STILE, STILE + 1, 65535, 65537, 3 * STILE + 5])
 def test_single_layer_sizes(gpu_lib, n):
     import torch
     rng = np.random.default_rng(n)
@@ -131,7 +132,7 @@ def test_single_layer_sizes(gpu_lib, n):
 def test_single_layer_misaligned_buffers(gpu_lib, misalign):
     import torch
     rng = np.random.default_rng(40 + misalign)
-    for n in (5, 1000, TILE + 77, 70001):
+    for n in (5, 1000, TILE + 77, STILE + TILE + 77, 70001):
         w, g, r = _layer(rng, n)
         _check_single(gpu_lib, torch, w, g, r, max(1, n // 50), misalign=misalign, tag="n=%d mis=%d" % (n, misalign))
 
@@ -139,14 +140,14 @@ def test_single_layer_misaligned_buffers(gpu_lib, misalign):
 def test_single_layer_degenerate_values(gpu_lib):
     import torch
     rng = np.random.default_rng(50)
-    n = 2 * TILE + 100
+    n = 2 * STILE + 100
     w, g, r = _layer(rng, n)
     z = np.zeros(n, np.float32)
     one = np.ones(n, np.float32)
     # all-zero residual and gradient: every score +0, first k positions
     _check_single(gpu_lib, torch, w, z, z, 300, tag="all zero")
     # all scores equal; the tie cut falls on, just before and just after a tile boundary
-    for k in (1, TILE - 1, TILE, TILE + 1, n - 1, n):
+    for k in (1, TILE - 1, TILE, TILE + 1, STILE - 1, STILE, STILE + 1, n - 1, n):
         _check_single(gpu_lib, torch, one, z, np.full(n, 0.5, np.float32), k, eps=0.0, tag="all equal k=%d" % k)
     # w == 0 everywhere: score = |r| / eps
     _check_single(gpu_lib, torch, z, g, r, 777, tag="w zero")
@@ -175,10 +176,10 @@ def test_single_layer_degenerate_values(gpu_lib):
 def test_select_then_compact_equals_compress(gpu_lib):
     import torch
     rng = np.random.default_rng(60)
-    n, k = 5 * TILE + 123, 4000
+    n, k = 5 * STILE + 123, 4000
     w, g, r = _layer(rng, n)
     wd, rd = _dev(torch, w), _dev(torch, r)
-    ws = torch.empty(gpu_lib.workspace_bytes(n), dtype=torch.uint8, device="cuda:0")
+    ws = torch.empty(gpu_lib.workspace_bytes(n, k), dtype=torch.uint8, device="cuda:0")
     thr = torch.zeros(3, dtype=torch.int32, device="cuda:0")
     idx = torch.empty(k, dtype=torch.int32, device="cuda:0")
     val = torch.empty(k, dtype=torch.float32, device="cuda:0")
@@ -219,12 +220,12 @@ def test_exchange_kernels(gpu_lib):
 
 # ---------------------------------------------------------------- whole steps on parameter sets
 
-def _run_steps(iwp, ps, steps, pool, W=None, r0=None, g_ids_fn=None, leader_fn=None, tag=""):
+def _run_steps(iwp, ps, steps, pool, W=None, r0=None, g_ids_fn=None, leader_fn=None, tag="", fused=False):
     W = ps.W if W is None else W
     w = wl.gen_weights(ps)
     sets = [wl.gen_gradient(ps, s) for s in range(pool)]
     r_ref = [np.zeros(ps.flat, np.float32) for _ in range(W)] if r0 is None else [x.copy() for x in r0]
-    gs = GpuSet(iwp, ps, w, sets, r_np=r0, W=W)
+    gs = GpuSet(iwp, ps, w, sets, r_np=r0, W=W, fused=fused)
     w_ref = w.copy()
     for t in range(steps):
         lead = wl.leaders(ps, t, n_candidates=W) if leader_fn is None else leader_fn(t)
@@ -239,49 +240,72 @@ def _run_steps(iwp, ps, steps, pool, W=None, r0=None, g_ids_fn=None, leader_fn=N
     return gs
 
 
-def test_config1_tiny_mlp_all_steps(gpu_lib):
+ROUTES = pytest.mark.parametrize("fused", [False, True], ids=["three_calls", "whole_step"])
+
+
+@ROUTES
+def test_config1_tiny_mlp_all_steps(gpu_lib, fused):
     ps = wl.make_config(1)
-    _run_steps(gpu_lib, ps, ps.steps, pool=4, tag="cfg1")
+    _run_steps(gpu_lib, ps, ps.steps, pool=4, tag="cfg1", fused=fused)
 
 
-def test_config1_packed_layout_misaligned_layers(gpu_lib):
+@ROUTES
+def test_config1_packed_layout_misaligned_layers(gpu_lib, fused):
     ps = wl.make_config(1, align=1)
-    _run_steps(gpu_lib, ps, 3, pool=4, tag="cfg1 packed")
+    _run_steps(gpu_lib, ps, 3, pool=4, tag="cfg1 packed", fused=fused)
 
 
-def test_custom_edge_set_segmented(gpu_lib):
+@ROUTES
+def test_custom_edge_set_segmented(gpu_lib, fused):
     """Ragged mix in one table: empty layer, k = 0 rows, n = 1, k = n, tile-boundary sizes."""
     sizes = [(300, 5), (0, 0), (1, 1), (TILE, 256), (64, 64), (1000, 0), (TILE + 1, 1), (777, 13),
-             (2 * TILE - 1, 2 * TILE - 1), (5, 0), (40000, 625)]
+             (2 * TILE - 1, 2 * TILE - 1), (5, 0), (40000, 625), (STILE + 3, 600), (3 * STILE, 3 * STILE - 1)]
     for align, start in ((1, 0), (1, 3), (4, 0), (64, 0)):
         ps = wl.custom_set(sizes, W=3, seed=80 + align + start, align=align, start=start, zero_frac=0.01)
-        _run_steps(gpu_lib, ps, 3, pool=3, tag="edge align=%d start=%d" % (align, start))
+        _run_steps(gpu_lib, ps, 3, pool=3, tag="edge align=%d start=%d" % (align, start), fused=fused)
 
 
+@ROUTES
+def test_leader_table_out_of_range_reads_as_worker_zero(gpu_lib, fused):
+    ps = wl.custom_set([(5000, 80), (300, 5)], W=2, seed=91, align=4)
+    bad = np.array([7, 0xFFFFFFFF], np.uint32)
+    w = wl.gen_weights(ps)
+    sets = [wl.gen_gradient(ps, s) for s in range(2)]
+    gs = GpuSet(gpu_lib, ps, w, sets, fused=fused)
+    gs.step([0, 1], bad)
+    r_ref = [np.zeros(ps.flat, np.float32) for _ in range(2)]
+    ref = oracle.step(w, sets, r_ref, ps.rows(), np.zeros(2, np.uint32), float(ps.eps), float(ps.scale))
+    assert_step_equal(gs.download(), w, r_ref, *ref, ps.layers, tag="bad leader")
+
+
+@ROUTES
 @pytest.mark.timeout(600)
-def test_config3_resnet50_shaped(gpu_lib):
+def test_config3_resnet50_shaped(gpu_lib, fused):
     ps = wl.make_config(3)
-    _run_steps(gpu_lib, ps, 3, pool=4, tag="cfg3")
+    _run_steps(gpu_lib, ps, 3, pool=4, tag="cfg3", fused=fused)
 
 
+@ROUTES
 @pytest.mark.timeout(600)
-def test_config4_many_small_tie_heavy(gpu_lib):
+def test_config4_many_small_tie_heavy(gpu_lib, fused):
     ps = wl.make_config(4)
-    gs = _run_steps(gpu_lib, ps, 2, pool=3, tag="cfg4")
+    gs = _run_steps(gpu_lib, ps, 2, pool=3, tag="cfg4", fused=fused)
     # the tie-heavy layers really put their cut inside the run of equal scores
     thr = gs.download()["thr"]
     tie_cut = [j for j, L in enumerate(ps.layers) if L.block is not None and thr[j][0] == 0]
     assert len(tie_cut) >= 10
 
 
+@ROUTES
 @pytest.mark.timeout(900)
-def test_config2_alexnet_shaped_full_size(gpu_lib):
+def test_config2_alexnet_shaped_full_size(gpu_lib, fused):
     ps = wl.make_config(2)
-    _run_steps(gpu_lib, ps, 2, pool=3, tag="cfg2")
+    _run_steps(gpu_lib, ps, 2, pool=3, tag="cfg2", fused=fused)
 
 
+@ROUTES
 @pytest.mark.timeout(600)
-def test_config5_scaled_local_plus_static_peers(gpu_lib):
+def test_config5_scaled_local_plus_static_peers(gpu_lib, fused):
     """Config 5's structure at 1/50 of its length: one flat layer, a local worker
     that accumulates and leads, and 8 peers whose residuals are static (no gradient
     buffer): the pointer list is [local, peer 0..7]."""
@@ -290,8 +314,39 @@ def test_config5_scaled_local_plus_static_peers(gpu_lib):
     peers = [wl.gen_gradient(ps, 100 + p) for p in range(8)]
     r0 = [np.zeros(ps.flat, np.float32)] + peers
     ps.W = 9
-    _run_steps(gpu_lib, ps, 3, pool=2, W=W, r0=r0, tag="cfg5/50",
+    _run_steps(gpu_lib, ps, 3, pool=2, W=W, r0=r0, tag="cfg5/50", fused=fused,
                g_ids_fn=lambda t: [t % 2] + [None] * 8, leader_fn=lambda t: np.zeros(1, np.uint32))
+
+
+@ROUTES
+def test_staging_overflow_takes_the_raw_route(gpu_lib, fused):
+    """Layers whose threshold bin is far larger than the staging capacity (nearly all
+    scores equal, or all in one top-digit bin) next to ordinary layers."""
+    n = 3 * STILE + 17
+    ps = wl.custom_set([(n, 700), (n, 5000), (50000, 800), (n, 100)], W=2, seed=92, align=4)
+    w = wl.gen_weights(ps)
+    rng = np.random.default_rng(5)
+    L0, L1, L2, L3 = ps.layers
+    g0 = wl.gen_gradient(ps, 0)
+    g1 = wl.gen_gradient(ps, 1)
+    for g in (g0, g1):
+        # layer 0: all scores identical; layer 1: identical top digit, different low bits; layer 3: zeros but a block
+        g[L0.offset:L0.offset + n] = 0.5
+        g[L1.offset:L1.offset + n] = (np.float32(1.0).view(np.uint32) + rng.integers(0, 4096, n).astype(np.uint32)).view(np.float32)
+        g[L3.offset:L3.offset + n] = 0.0
+        g[L3.offset + 1000:L3.offset + 1050] = rng.standard_normal(50).astype(np.float32)
+    w[L0.offset:L0.offset + n] = 1.0
+    w[L1.offset:L1.offset + n] = 1.0
+    sets = [g0, g1]
+    gs = GpuSet(gpu_lib, ps, w, sets, fused=fused)
+    w_ref = w.copy()
+    r_ref = [np.zeros(ps.flat, np.float32) for _ in range(2)]
+    for t in range(2):
+        lead = wl.leaders(ps, t)
+        ref = oracle.step(w_ref, sets, r_ref, ps.rows(), lead, 0.0, float(ps.scale))
+        ps.eps = 0.0
+        gs.step([0, 1], lead)
+        assert_step_equal(gs.download(), w_ref, r_ref, *ref, ps.layers, tag="raw route step %d" % t)
 
 
 def test_determinism_run_to_run(gpu_lib):
@@ -319,7 +374,7 @@ def test_argument_errors_launch_nothing(gpu_lib):
     r = torch.zeros(n, device="cuda:0")
     idx = torch.empty(n, dtype=torch.int32, device="cuda:0")
     val = torch.empty(n, device="cuda:0")
-    ws = torch.empty(iwp.workspace_bytes(n), dtype=torch.uint8, device="cuda:0")
+    ws = torch.empty(iwp.workspace_bytes(n, n), dtype=torch.uint8, device="cuda:0")
     for kwargs, code in [
         (dict(k=n + 1), iwp.IWP_EINVAL),
         (dict(k=5, eps=-1.0), iwp.IWP_EINVAL),
