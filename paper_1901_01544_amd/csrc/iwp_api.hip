@@ -73,13 +73,18 @@ inline bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3
 inline size_t round256(size_t x) { return (x + 255) & ~size_t(255); }
 inline uint32_t tiles_of(uint32_t n) { return (uint32_t)(((uint64_t)n + TILE - 1) / TILE); }
 inline uint32_t stiles_of(uint32_t n) { return (uint32_t)(((uint64_t)n + STILE - 1) / STILE); }
-// Capacity of a layer's threshold-bin staging.  The threshold bin normally holds a
-// few percent of k; a layer that overflows this takes the exact RAW route.
-inline uint32_t maybe_cap_of(uint32_t n, uint32_t k) { return k == 0 ? 0u : std::min(n, std::max(4096u, k)); }
+// Staging entries per tile of a layer: three times the number of kept elements an
+// average tile holds, plus room for the threshold bin.  A tile that overflows its
+// slot is re-read by the later passes instead, which is exact as well.
+inline uint32_t slot_cap_of(uint32_t n, uint32_t k) {
+    if (k == 0) return 0u;
+    const uint64_t per_tile = ((uint64_t)TILE * k + n - 1) / n;
+    return (uint32_t)std::min<uint64_t>(TILE, 64 + 3 * per_tile);
+}
 
 struct Sizes {                // everything the workspace layout depends on
     uint32_t n_layers, tiles, stiles;
-    uint64_t pairs, maybes;
+    uint64_t pairs, slots;    // slots: staging entries over all tiles
     uint32_t W_gather;        // rows of the gather matrix (whole-step entry point), else 0
 };
 
@@ -94,7 +99,7 @@ struct Workspace {
     uint2* tile_counts;       // tiles
     uint2* stile_counts;      // stiles
     uint32_t* tile_out;       // tiles
-    StageArrays A;            // pairs (sure) / maybes entries
+    StageArrays A;            // `slots` entries each
     float* gathered;          // W_gather * pairs
     size_t bytes;
 };
@@ -115,11 +120,9 @@ Workspace carve(void* base, const Sizes& z) {
     ws.tile_counts = reinterpret_cast<uint2*>(take((size_t)z.tiles * sizeof(uint2)));
     ws.stile_counts = reinterpret_cast<uint2*>(take((size_t)z.stiles * sizeof(uint2)));
     ws.tile_out = reinterpret_cast<uint32_t*>(take((size_t)z.tiles * sizeof(uint32_t)));
-    ws.A.sure_idx = reinterpret_cast<uint32_t*>(take(z.pairs * sizeof(uint32_t)));
-    ws.A.sure_val = reinterpret_cast<float*>(take(z.pairs * sizeof(float)));
-    ws.A.maybe_key = reinterpret_cast<uint32_t*>(take(z.maybes * sizeof(uint32_t)));
-    ws.A.maybe_idx = reinterpret_cast<uint32_t*>(take(z.maybes * sizeof(uint32_t)));
-    ws.A.maybe_val = reinterpret_cast<float*>(take(z.maybes * sizeof(float)));
+    ws.A.key = reinterpret_cast<uint32_t*>(take(z.slots * sizeof(uint32_t)));
+    ws.A.idx = reinterpret_cast<uint32_t*>(take(z.slots * sizeof(uint32_t)));
+    ws.A.val = reinterpret_cast<float*>(take(z.slots * sizeof(float)));
     ws.gathered = reinterpret_cast<float*>(take((size_t)z.W_gather * z.pairs * sizeof(float)));
     ws.bytes = off;
     return ws;
@@ -153,36 +156,37 @@ int run_select(const Table& T, const Workspace& ws, const ResidualPtrs& R, const
                uint32_t W, float eps, Stop stop, bool fused, uint32_t* idx_out, float* val_out,
                iwp_threshold* thr_out, hipStream_t s) {
     if (!T.any_k || T.tiles == 0) return IWP_OK;
-    IWP_LAUNCH("k_pick0", k_pick0, T.n_layers, s, T.layers, ws.hist, ws.state);
+    IWP_LAUNCH("k_pick<0>", k_pick<0>, T.n_layers, s, T.layers, ws.hist, ws.state, thr_out);
     IWP_LAUNCH("k_stage", k_stage, T.tiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.hist,
                ws.stage, ws.A);
-    IWP_LAUNCH("k_refine2_raw", k_refine2_raw, T.stiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state,
-               ws.hist);
-    IWP_LAUNCH("k_resolve", k_resolve, T.n_layers, s, T.layers, ws.hist, ws.state, ws.A, thr_out);
+    IWP_LAUNCH("k_pick<1>", k_pick<1>, T.n_layers, s, T.layers, ws.hist, ws.state, thr_out);
+    IWP_LAUNCH("k_refine2", k_refine2, T.stiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.stage,
+               ws.A, ws.hist);
+    IWP_LAUNCH("k_pick<2>", k_pick<2>, T.n_layers, s, T.layers, ws.hist, ws.state, thr_out);
     if (stop == STOP_AT_THRESHOLD) return IWP_OK;
     IWP_LAUNCH("k_count", k_count, T.stiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.stage, ws.A,
-               ws.tile_counts, ws.stile_counts);
+               false, ws.tile_counts, ws.stile_counts);
     IWP_LAUNCH("k_scan", k_scan, T.n_layers, s, T.layers, ws.stile_counts);
     if (fused)
         IWP_LAUNCH("k_write", k_write<true>, T.stiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.stage,
-                   ws.A, ws.tile_counts, ws.stile_counts, ws.tile_out, idx_out, val_out, ws.gathered, T.pairs);
+                   ws.A, false, ws.tile_counts, ws.stile_counts, ws.tile_out, idx_out, val_out, ws.gathered, T.pairs);
     else
         IWP_LAUNCH("k_write", k_write<false>, T.stiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.stage,
-                   ws.A, ws.tile_counts, ws.stile_counts, ws.tile_out, idx_out, val_out, nullptr, T.pairs);
+                   ws.A, false, ws.tile_counts, ws.stile_counts, ws.tile_out, idx_out, val_out, nullptr, T.pairs);
     return IWP_OK;
 }
 
-// Ordered split from threshold records given by the caller (RAW route throughout).
+// Ordered split from threshold records given by the caller (nothing is staged: every tile is re-read).
 int run_compact_from(const Table& T, const Workspace& ws, const ResidualPtrs& R, const float* w, float eps,
                      const iwp_threshold* thr, uint32_t* idx_out, float* val_out, hipStream_t s) {
     if (!T.any_k || T.tiles == 0) return IWP_OK;
     IWP_LAUNCH("k_load_thresholds", k_load_thresholds, (T.n_layers + BLOCK - 1) / BLOCK, s, T.layers, T.n_layers, thr,
                ws.state);
     IWP_LAUNCH("k_count", k_count, T.stiles, s, R, w, T.layers, T.n_layers, nullptr, 1u, eps, ws.state, ws.stage, ws.A,
-               ws.tile_counts, ws.stile_counts);
+               true, ws.tile_counts, ws.stile_counts);
     IWP_LAUNCH("k_scan", k_scan, T.n_layers, s, T.layers, ws.stile_counts);
     IWP_LAUNCH("k_write", k_write<false>, T.stiles, s, R, w, T.layers, T.n_layers, nullptr, 1u, eps, ws.state, ws.stage,
-               ws.A, ws.tile_counts, ws.stile_counts, ws.tile_out, idx_out, val_out, nullptr, T.pairs);
+               ws.A, true, ws.tile_counts, ws.stile_counts, ws.tile_out, idx_out, val_out, nullptr, T.pairs);
     return IWP_OK;
 }
 
@@ -216,7 +220,7 @@ const char* iwp_last_hip_error(void) { return g_hip_error; }
 static Sizes single_sizes(uint32_t n, uint32_t k) {
     Sizes z;
     z.n_layers = 1; z.tiles = tiles_of(n); z.stiles = stiles_of(n);
-    z.pairs = k; z.maybes = maybe_cap_of(n, k); z.W_gather = 0;
+    z.pairs = k; z.slots = (uint64_t)z.tiles * slot_cap_of(n, k); z.W_gather = 0;
     return z;
 }
 
@@ -251,7 +255,7 @@ static int single_common(SingleOp op, const float* w, const float* g, float* r, 
     DevLayer row, sentinel;
     memset(&row, 0, sizeof row);
     memset(&sentinel, 0, sizeof sentinel);
-    row.n = n; row.k = k; row.maybe_cap = (uint32_t)z.maybes;
+    row.n = n; row.k = k; row.slot_cap = slot_cap_of(n, k);
     sentinel.tile_begin = z.tiles; sentinel.stile_begin = z.stiles; sentinel.out_offset = k;
     int rc = launch_init(ws, &row, &sentinel, s);
     if (rc) return rc;
@@ -329,7 +333,7 @@ int iwp_plan_create(const iwp_layer* layers, uint32_t n_layers, iwp_plan** plan_
     *plan_out = nullptr;
     if (!layers || n_layers == 0) return IWP_EINVAL;
     std::vector<DevLayer> dev(n_layers + 1);
-    uint64_t pairs = 0, maybes = 0, tiles = 0, stiles = 0, end = 0;
+    uint64_t pairs = 0, slots = 0, tiles = 0, stiles = 0, end = 0;
     bool any_k = false;
     for (uint32_t j = 0; j < n_layers; ++j) {
         const iwp_layer& L = layers[j];
@@ -340,16 +344,16 @@ int iwp_plan_create(const iwp_layer* layers, uint32_t n_layers, iwp_plan** plan_
         DevLayer& D = dev[j];
         memset(&D, 0, sizeof D);
         D.offset = (uint64_t)L.offset;
-        D.maybe_begin = maybes;
+        D.slot_begin = slots;
         D.n = L.n;
         D.k = L.k;
         D.out_offset = L.out_offset;
         D.tile_begin = (uint32_t)tiles;
         D.stile_begin = (uint32_t)stiles;
-        D.maybe_cap = maybe_cap_of(L.n, L.k);
+        D.slot_cap = slot_cap_of(L.n, L.k);
         end = (uint64_t)L.offset + L.n;
         pairs += L.k;
-        maybes += D.maybe_cap;
+        slots += (uint64_t)tiles_of(L.n) * D.slot_cap;
         tiles += tiles_of(L.n);
         stiles += stiles_of(L.n);
         any_k = any_k || L.k > 0;
@@ -360,11 +364,11 @@ int iwp_plan_create(const iwp_layer* layers, uint32_t n_layers, iwp_plan** plan_
     S.out_offset = (uint32_t)pairs;
     S.tile_begin = (uint32_t)tiles;
     S.stile_begin = (uint32_t)stiles;
-    S.maybe_begin = maybes;
+    S.slot_begin = slots;
     iwp_plan* plan = new (std::nothrow) iwp_plan;
     if (!plan) return IWP_EINVAL;
     plan->rows.assign(layers, layers + n_layers);
-    plan->z = Sizes{n_layers, (uint32_t)tiles, (uint32_t)stiles, pairs, maybes, 0};
+    plan->z = Sizes{n_layers, (uint32_t)tiles, (uint32_t)stiles, pairs, slots, 0};
     plan->any_k = any_k;
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&plan->dev), dev.size() * sizeof(DevLayer));
     if (e == hipSuccess) e = hipMemcpy(plan->dev, dev.data(), dev.size() * sizeof(DevLayer), hipMemcpyHostToDevice);

@@ -35,18 +35,17 @@ constexpr uint32_t HIST0 = 1u << 12, HIST1 = 1u << 10, HIST2 = 1u << 9;
 constexpr uint32_t HIST_STRIDE = HIST0 + HIST1 + HIST2;    // words per layer; each digit has its own region
 __host__ __device__ constexpr uint32_t hist_base(int level) { return level == 0 ? 0 : (level == 1 ? HIST0 : HIST0 + HIST1); }
 
-enum : uint32_t { MODE_STAGED = 0, MODE_RAW = 1 };
+constexpr uint32_t RAW_TILE = 0xFFFFFFFFu;     // TileStage.n_sure of a tile whose candidates did not fit its slot
 
 struct DevLayer {
     uint64_t offset;       // first element in the flat buffers
-    uint64_t maybe_begin;  // first entry of the layer in the staged "threshold bin" arrays (the "sure"
-                           // arrays are laid out like the pairs: out_offset)
+    uint64_t slot_begin;   // first entry of the layer's first tile slot in the staging arrays
     uint32_t n;
     uint32_t k;
     uint32_t out_offset;   // first pair in idx_out / val_out
     uint32_t tile_begin;   // first TILE of the layer in the per-worker tile numbering
     uint32_t stile_begin;  // first STILE of the layer
-    uint32_t maybe_cap;    // capacity of the layer's threshold-bin staging
+    uint32_t slot_cap;     // staging entries per tile of this layer
 };
 
 struct LayerState {        // selection state of one layer, lives in the workspace
@@ -54,14 +53,11 @@ struct LayerState {        // selection state of one layer, lives in the workspa
     uint32_t k_rem;        // rank still to be found inside the prefix group (1-based)
     uint32_t n_gt;
     uint32_t n_eq_take;
-    uint32_t mode;         // MODE_STAGED: candidates were copied out in look 2; MODE_RAW: every pass re-reads r, w
-    uint32_t sure_used;    // staging cursors
-    uint32_t maybe_used;
-    uint32_t pad;
 };
 
-struct TileStage {         // where look 2 put the candidates of one tile
-    uint32_t sure_start, sure_cnt, maybe_start, maybe_cnt;
+struct TileStage {         // what look 2 left in the slot of one tile: n_sure entries whose top digit
+    uint32_t n_sure;       // lies above the threshold bin, then n_maybe entries inside it;
+    uint32_t n_maybe;      // n_sure == RAW_TILE: nothing staged, later passes re-read the tile
 };
 
 struct WorkerPtrs {        // passed by value as a kernel argument

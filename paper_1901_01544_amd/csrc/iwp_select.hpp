@@ -5,30 +5,30 @@
 // The selection is an MSB-first radix select on the 31-bit importance key
 // (digits of 12 + 10 + 9 bits).  Look 1 (iwp_stream.hpp) histograms the top digit
 // of every element.  k_pick0 finds the bin b1 that holds rank k.  Look 2 (k_stage)
-// reads the leader's residual and weights once more and copies out the only
-// elements that can still matter: those above b1 ("sure": all of them are kept)
-// and those inside b1 ("maybe": the threshold lies among them), per tile, together
-// with the histogram of the maybes' second digit.  Everything after that works on
-// the staged copies, a few percent of the layer: k_resolve finishes the threshold
-// (digits 2 and 3), k_count / k_scan / k_write place every kept element at its
-// rank in index order.  A layer whose threshold bin is too large to stage (heavy
-// ties, e.g. a layer that is mostly zeros) takes the RAW route instead: the same
-// kernels re-read r and w in every pass.  Both routes are exact.
+// reads the leader's residual and weights once more and copies out, per tile, the
+// only elements that can still matter: those above b1 ("sure": all of them are
+// kept) and those inside b1 ("maybe": the threshold lies among them), and
+// histograms the maybes' second digit.  Every tile owns a fixed slot in the staging
+// arrays, so look 2 needs no cross-workgroup coordination at all.  Everything after
+// that works on the staged copies, a few percent of the layer: k_pick1, k_refine2
+// and k_pick2 finish the threshold, k_count / k_scan / k_write place every kept
+// element at its rank in index order.  A tile whose candidates do not fit its slot
+// (heavy ties, e.g. a tile that is all zeros) is marked RAW and is simply re-read
+// from r and w by the later passes.  Both routes are exact.
 #pragma once
 
 #include "iwp_common.hpp"
 
 namespace iwp {
 
-struct StageArrays {        // staged candidates, structure of arrays
-    uint32_t* sure_idx;     // position inside the layer
-    float* sure_val;
-    uint32_t* maybe_key;
-    uint32_t* maybe_idx;
-    float* maybe_val;
+struct StageArrays {        // staged candidates, structure of arrays; tile t of a layer owns entries
+    uint32_t* key;          // [slot_begin + t * slot_cap, + slot_cap)
+    uint32_t* idx;          // position inside the layer
+    float* val;
 };
 
 constexpr uint32_t NOT_AN_ELEMENT = 0xFFFFFFFFu;   // key slot of a lane position past the layer's end
+constexpr uint32_t DIRECT_ATOMICS_MAX = 64;        // up to this many histogram updates per tile go straight to global memory
 
 // ---------------------------------------------------------------------------
 // Workspace initialisation with vector stores (a fill kernel rather than a memset
@@ -46,30 +46,38 @@ __global__ __launch_bounds__(BLOCK) void k_init(uint32_t* __restrict__ words, ui
 }
 
 // ---------------------------------------------------------------------------
-// First digit: the bin that holds rank k, and the route the layer takes.
+// Digit pick, one workgroup per layer: the bin of digit LEVEL that holds rank
+// k_rem, appended to the key prefix.  After the last digit the prefix is the
+// exact k-th largest key and k_rem the number of ties to keep.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(BLOCK) void k_pick0(const DevLayer* __restrict__ layers, const uint32_t* __restrict__ hist,
-                                                 LayerState* __restrict__ state) {
+template <int LEVEL>
+__global__ __launch_bounds__(BLOCK) void k_pick(const DevLayer* __restrict__ layers, const uint32_t* __restrict__ hist,
+                                                LayerState* __restrict__ state, iwp_threshold* __restrict__ thr_out) {
     __shared__ uint32_t sh[BLOCK + 2];
     const uint32_t j = blockIdx.x;
     const DevLayer L = layers[j];
     if (L.k == 0) return;
-    const uint32_t* h0 = hist + (size_t)j * HIST_STRIDE + hist_base(0);
+    const uint32_t* h = hist + (size_t)j * HIST_STRIDE + hist_base(LEVEL);
+    const uint32_t k_in = LEVEL == 0 ? L.k : state[j].k_rem;
+    const uint32_t prefix = LEVEL == 0 ? 0u : state[j].prefix;
     uint32_t bin, k_rem;
-    block_pick<HIST0>(h0, L.k, sh, &bin, &k_rem);
+    block_pick<(1 << digit_bits(LEVEL))>(h, k_in, sh, &bin, &k_rem);
     if (threadIdx.x == 0) {
         LayerState st;
-        st.prefix = bin;
+        st.prefix = (prefix << digit_bits(LEVEL)) | bin;
         st.k_rem = k_rem;
-        st.n_gt = 0; st.n_eq_take = 0;
-        st.mode = (h0[bin] <= L.maybe_cap) ? MODE_STAGED : MODE_RAW;
-        st.sure_used = 0; st.maybe_used = 0; st.pad = 0;
+        st.n_eq_take = k_rem;
+        st.n_gt = L.k - k_rem;
         state[j] = st;
+        if (LEVEL == DIGITS - 1 && thr_out) {
+            iwp_threshold th;
+            th.key = st.prefix; th.n_gt = st.n_gt; th.n_eq_take = st.n_eq_take;
+            thr_out[j] = th;
+        }
     }
 }
 
-// Threshold records supplied by the caller -> selection state (compact_pairs):
-// nothing was staged, so the layer takes the RAW route.
+// Threshold records supplied by the caller -> selection state (compact_pairs).
 __global__ __launch_bounds__(BLOCK) void k_load_thresholds(const DevLayer* __restrict__ layers, uint32_t n_layers,
                                                            const iwp_threshold* __restrict__ thr,
                                                            LayerState* __restrict__ state) {
@@ -77,31 +85,39 @@ __global__ __launch_bounds__(BLOCK) void k_load_thresholds(const DevLayer* __res
     if (j >= n_layers || layers[j].k == 0) return;
     LayerState st;
     st.prefix = thr[j].key; st.k_rem = thr[j].n_eq_take; st.n_gt = thr[j].n_gt; st.n_eq_take = thr[j].n_eq_take;
-    st.mode = MODE_RAW; st.sure_used = 0; st.maybe_used = 0; st.pad = 0;
     state[j] = st;
 }
 
+// LDS histogram -> global, non-empty bins only.
+template <int NB>
+__device__ __forceinline__ void flush_hist(const uint32_t* lh, uint32_t* __restrict__ gh) {
+    for (uint32_t b = threadIdx.x; b < NB; b += BLOCK) {
+        const uint32_t v = lh[b];
+        if (v) atomicAdd(&gh[b], v);
+    }
+}
+
 // ---------------------------------------------------------------------------
-// Look 2, one workgroup per tile of the leader's residual.  STAGED route: copy
-// the sure and maybe elements of the tile out (in index order) and histogram the
-// maybes' second digit.  RAW route: only the second-digit histogram.
+// Look 2, one workgroup per tile of the leader's residual: copy the sure and maybe
+// elements of the tile into the tile's slot (in index order) and histogram the
+// maybes' second digit.  A tile with more candidates than its slot holds is marked
+// RAW; its second-digit counts still go into the histogram.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(BLOCK) void k_stage(ResidualPtrs R, const float* __restrict__ w,
                                                  const DevLayer* __restrict__ layers, uint32_t n_layers,
                                                  const uint32_t* __restrict__ leader, uint32_t W, float eps,
-                                                 LayerState* __restrict__ state, uint32_t* __restrict__ hist,
+                                                 const LayerState* __restrict__ state, uint32_t* __restrict__ hist,
                                                  TileStage* __restrict__ stage, StageArrays A) {
     __shared__ uint32_t lh[HIST1];
     __shared__ uint32_t slot[4];
-    __shared__ uint32_t starts[2];
     const uint32_t tid = threadIdx.x;
     const uint32_t t = blockIdx.x;
     const uint32_t j = find_layer<false>(layers, n_layers, t);
     const DevLayer L = layers[j];
     if (L.k == 0) return;
     const uint32_t b1 = state[j].prefix;
-    const uint32_t mode = state[j].mode;
-    const uint32_t base = (t - L.tile_begin) * TILE;
+    const uint32_t lt = t - L.tile_begin;
+    const uint32_t base = lt * TILE;
     const float* rl = R.r[leader_of(leader, j, W)] + L.offset;
     const float* wl = w + L.offset;
     const bool vec = is_aligned16(rl) && is_aligned16(wl);
@@ -133,168 +149,115 @@ __global__ __launch_bounds__(BLOCK) void k_stage(ResidualPtrs R, const float* __
             }
         }
     }
-
-    if (mode == MODE_RAW) {
-        for (uint32_t b = tid; b < HIST1; b += BLOCK) lh[b] = 0u;
-        __syncthreads();
-#pragma unroll
-        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u)
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                if (key[u][q] != NOT_AN_ELEMENT && (key[u][q] >> digit_shift(0)) == b1)
-                    atomicAdd(&lh[(key[u][q] >> digit_shift(1)) & (HIST1 - 1)], 1u);
-        __syncthreads();
-        for (uint32_t b = tid; b < HIST1; b += BLOCK) {
-            const uint32_t v = lh[b];
-            if (v) atomicAdd(&h1[b], v);
-        }
-        return;
-    }
-
     uint32_t tot;
     const uint32_t ex = block_exclusive_scan(packed, slot, &tot);
     const uint32_t n_sure = tot & 0xFFFFu, n_maybe = tot >> 16;
+    const bool fits = n_sure + n_maybe <= L.slot_cap;
     if (tid == 0) {
         TileStage ts;
-        ts.sure_start = n_sure ? atomicAdd(&state[j].sure_used, n_sure) : 0u;
-        ts.maybe_start = n_maybe ? atomicAdd(&state[j].maybe_used, n_maybe) : 0u;
-        ts.sure_cnt = n_sure;
-        ts.maybe_cnt = n_maybe;
-        // the counts are bounded by construction (sure < k, maybe = hist[b1] <= maybe_cap); a
-        // tile that would not fit is recorded as empty rather than written out of range
-        if ((uint64_t)ts.sure_start + n_sure > L.k) ts.sure_cnt = 0;
-        if ((uint64_t)ts.maybe_start + n_maybe > L.maybe_cap) ts.maybe_cnt = 0;
+        ts.n_sure = fits ? n_sure : RAW_TILE;
+        ts.n_maybe = fits ? n_maybe : 0u;
         stage[t] = ts;
-        starts[0] = ts.sure_cnt ? ts.sure_start : NOT_AN_ELEMENT;
-        starts[1] = ts.maybe_cnt ? ts.maybe_start : NOT_AN_ELEMENT;
     }
-    __syncthreads();
-    if (packed == 0) return;
-    uint32_t so = ex & 0xFFFFu, mo = ex >> 16;
-    const bool sure_ok = starts[0] != NOT_AN_ELEMENT, maybe_ok = starts[1] != NOT_AN_ELEMENT;
-    const uint64_t sb = L.out_offset + (uint64_t)starts[0];       // the sure region is laid out like the pairs
-    const uint64_t mb = L.maybe_begin + (uint64_t)starts[1];
+    if (tot == 0) return;                      // uniform
+    const bool use_lds = n_maybe > DIRECT_ATOMICS_MAX;     // uniform
+    if (use_lds) {
+        for (uint32_t b = tid; b < HIST1; b += BLOCK) lh[b] = 0u;
+        __syncthreads();
+    }
+    if (packed) {
+        const uint64_t sb = L.slot_begin + (uint64_t)lt * L.slot_cap;
+        uint32_t so = ex & 0xFFFFu;                        // sures first ...
+        uint32_t mo = n_sure + (ex >> 16);                 // ... then the maybes
 #pragma unroll
-    for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
-        const uint32_t i = base + u * CHUNK + tid * VEC;
+        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+            const uint32_t i = base + u * CHUNK + tid * VEC;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            if (key[u][q] == NOT_AN_ELEMENT) continue;
-            const uint32_t d0 = key[u][q] >> digit_shift(0);
-            if (d0 > b1) {
-                if (sure_ok) { A.sure_idx[sb + so] = i + q; A.sure_val[sb + so] = val[u][q]; }
-                ++so;
-            } else if (d0 == b1) {
-                if (maybe_ok) {
-                    A.maybe_key[mb + mo] = key[u][q]; A.maybe_idx[mb + mo] = i + q; A.maybe_val[mb + mo] = val[u][q];
+            for (int q = 0; q < 4; ++q) {
+                if (key[u][q] == NOT_AN_ELEMENT) continue;
+                const uint32_t d0 = key[u][q] >> digit_shift(0);
+                if (d0 > b1) {
+                    if (fits) { A.key[sb + so] = key[u][q]; A.idx[sb + so] = i + q; A.val[sb + so] = val[u][q]; }
+                    ++so;
+                } else if (d0 == b1) {
+                    if (fits) { A.key[sb + mo] = key[u][q]; A.idx[sb + mo] = i + q; A.val[sb + mo] = val[u][q]; }
+                    ++mo;
+                    const uint32_t d1 = (key[u][q] >> digit_shift(1)) & (HIST1 - 1);
+                    if (use_lds) atomicAdd(&lh[d1], 1u); else atomicAdd(&h1[d1], 1u);
                 }
-                ++mo;
-                atomicAdd(&h1[(key[u][q] >> digit_shift(1)) & (HIST1 - 1)], 1u);
             }
         }
     }
+    if (use_lds) {
+        __syncthreads();
+        flush_hist<HIST1>(lh, h1);
+    }
 }
 
 // ---------------------------------------------------------------------------
-// RAW route only: histogram of the third digit over the elements whose first two
-// digits match.  One workgroup per super-tile; staged layers leave at once.
+// Third digit: histogram over the elements whose first two digits match the prefix,
+// taken from the tile slots (or from r, w for RAW tiles).  One workgroup per
+// super-tile.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(BLOCK) void k_refine2_raw(ResidualPtrs R, const float* __restrict__ w,
-                                                       const DevLayer* __restrict__ layers, uint32_t n_layers,
-                                                       const uint32_t* __restrict__ leader, uint32_t W, float eps,
-                                                       const LayerState* __restrict__ state,
-                                                       uint32_t* __restrict__ hist) {
+__global__ __launch_bounds__(BLOCK) void k_refine2(ResidualPtrs R, const float* __restrict__ w,
+                                                   const DevLayer* __restrict__ layers, uint32_t n_layers,
+                                                   const uint32_t* __restrict__ leader, uint32_t W, float eps,
+                                                   const LayerState* __restrict__ state,
+                                                   const TileStage* __restrict__ stage, StageArrays A,
+                                                   uint32_t* __restrict__ hist) {
     __shared__ uint32_t lh[HIST2];
-    __shared__ uint32_t sh[BLOCK + 2];
+    const uint32_t tid = threadIdx.x;
     const uint32_t s = blockIdx.x;
     const uint32_t j = find_layer<true>(layers, n_layers, s);
     const DevLayer L = layers[j];
-    if (L.k == 0 || state[j].mode != MODE_RAW) return;
-    uint32_t* hl = hist + (size_t)j * HIST_STRIDE;
-    uint32_t b2, k_rem2;
-    block_pick<HIST1>(hl + hist_base(1), state[j].k_rem, sh, &b2, &k_rem2);
-    const uint32_t prefix = (state[j].prefix << digit_bits(1)) | b2;
-    const uint32_t base = (s - L.stile_begin) * STILE;
+    if (L.k == 0) return;
+    const uint32_t prefix = state[j].prefix;                    // 22 bits
+    const uint32_t ntiles = (L.n + TILE - 1) / TILE;
+    const uint32_t lt0 = (s - L.stile_begin) * GROUP;
+    const uint32_t nt = min(GROUP, ntiles - lt0);
     const float* rl = R.r[leader_of(leader, j, W)] + L.offset;
     const float* wl = w + L.offset;
     const bool vec = is_aligned16(rl) && is_aligned16(wl);
-    for (uint32_t b = threadIdx.x; b < HIST2; b += BLOCK) lh[b] = 0u;
+    for (uint32_t b = tid; b < HIST2; b += BLOCK) lh[b] = 0u;
     __syncthreads();
-    for (uint32_t c = 0; c < STILE / CHUNK; ++c) {
-        const uint32_t i = base + c * CHUNK + threadIdx.x * VEC;
-        if (i >= L.n) break;
-        float rv[4], wv[4];
-        load_quad(rl, i, L.n, vec, rv);
-        load_quad(wl, i, L.n, vec, wv, 1.0f);
+    for (uint32_t tl = 0; tl < nt; ++tl) {
+        const TileStage ts = stage[L.tile_begin + lt0 + tl];
+        if (ts.n_sure != RAW_TILE) {
+            const uint64_t sb = L.slot_begin + (uint64_t)(lt0 + tl) * L.slot_cap + ts.n_sure;
+            for (uint32_t e = tid; e < ts.n_maybe; e += BLOCK) {
+                const uint32_t key = A.key[sb + e];
+                if ((key >> digit_shift(1)) == prefix) atomicAdd(&lh[key & (HIST2 - 1)], 1u);
+            }
+        } else {
+            for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+                const uint32_t i = (lt0 + tl) * TILE + u * CHUNK + tid * VEC;
+                if (i >= L.n) break;
+                float rv[4], wv[4];
+                load_quad(rl, i, L.n, vec, rv);
+                load_quad(wl, i, L.n, vec, wv, 1.0f);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const uint32_t key = score_key(rv[q], wv[q], eps);
-            if (i + q < L.n && (key >> digit_shift(1)) == prefix) atomicAdd(&lh[key & (HIST2 - 1)], 1u);
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t key = score_key(rv[q], wv[q], eps);
+                    if (i + q < L.n && (key >> digit_shift(1)) == prefix) atomicAdd(&lh[key & (HIST2 - 1)], 1u);
+                }
+            }
         }
     }
     __syncthreads();
-    for (uint32_t b = threadIdx.x; b < HIST2; b += BLOCK) {
-        const uint32_t v = lh[b];
-        if (v) atomicAdd(&hl[hist_base(2) + b], v);
-    }
+    flush_hist<HIST2>(lh, hist + (size_t)j * HIST_STRIDE + hist_base(2));
 }
 
 // ---------------------------------------------------------------------------
-// Digits 2 and 3 -> the exact threshold.  One workgroup per layer.  STAGED: the
-// third-digit histogram is built here from the layer's staged maybes.
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(BLOCK) void k_resolve(const DevLayer* __restrict__ layers, const uint32_t* __restrict__ hist,
-                                                   LayerState* __restrict__ state, StageArrays A,
-                                                   iwp_threshold* __restrict__ thr_out) {
-    __shared__ uint32_t lh[HIST2];
-    __shared__ uint32_t sh[BLOCK + 2];
-    const uint32_t j = blockIdx.x;
-    const DevLayer L = layers[j];
-    if (L.k == 0) return;
-    const LayerState st = state[j];
-    const uint32_t* hl = hist + (size_t)j * HIST_STRIDE;
-    uint32_t b2, k_rem2, b3, k_rem3;
-    block_pick<HIST1>(hl + hist_base(1), st.k_rem, sh, &b2, &k_rem2);
-    const uint32_t prefix = (st.prefix << digit_bits(1)) | b2;
-    if (st.mode == MODE_STAGED) {
-        for (uint32_t b = threadIdx.x; b < HIST2; b += BLOCK) lh[b] = 0u;
-        __syncthreads();
-        const uint32_t used = min(st.maybe_used, L.maybe_cap);
-        const uint32_t* mk = A.maybe_key + L.maybe_begin;
-        for (uint32_t e = threadIdx.x; e < used; e += BLOCK) {
-            const uint32_t key = mk[e];
-            if ((key >> digit_shift(1)) == prefix) atomicAdd(&lh[key & (HIST2 - 1)], 1u);
-        }
-        __syncthreads();
-        block_pick<HIST2>(lh, k_rem2, sh, &b3, &k_rem3);
-    } else {
-        block_pick<HIST2>(hl + hist_base(2), k_rem2, sh, &b3, &k_rem3);
-    }
-    if (threadIdx.x == 0) {
-        const uint32_t key = (prefix << digit_bits(2)) | b3;
-        state[j].prefix = key;
-        state[j].k_rem = k_rem3;
-        state[j].n_eq_take = k_rem3;
-        state[j].n_gt = L.k - k_rem3;
-        if (thr_out) {
-            iwp_threshold th;
-            th.key = key; th.n_gt = L.k - k_rem3; th.n_eq_take = k_rem3;
-            thr_out[j] = th;
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------
-// Ordered split, part 1: per tile, how many kept-for-sure elements (key above the
-// threshold) and how many ties (key equal to it).  One workgroup per super-tile;
-// writes each tile's exclusive prefix inside the super-tile and the super-tile's
-// totals.
+// Ordered split, part 1: per tile, how many elements lie above the threshold and
+// how many tie with it.  One workgroup per super-tile; writes each tile's exclusive
+// prefix inside the super-tile and the super-tile's totals.  all_raw: there is no
+// stage table (compact_pairs), every tile is re-read.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(BLOCK) void k_count(ResidualPtrs R, const float* __restrict__ w,
                                                  const DevLayer* __restrict__ layers, uint32_t n_layers,
                                                  const uint32_t* __restrict__ leader, uint32_t W, float eps,
                                                  const LayerState* __restrict__ state,
-                                                 const TileStage* __restrict__ stage, StageArrays A,
+                                                 const TileStage* __restrict__ stage, StageArrays A, bool all_raw,
                                                  uint2* __restrict__ tile_counts, uint2* __restrict__ stile_counts) {
     __shared__ uint32_t cg[GROUP], ce[GROUP];
     const uint32_t tid = threadIdx.x;
@@ -302,30 +265,29 @@ __global__ __launch_bounds__(BLOCK) void k_count(ResidualPtrs R, const float* __
     const uint32_t j = find_layer<true>(layers, n_layers, s);
     const DevLayer L = layers[j];
     if (L.k == 0) return;
-    const LayerState st = state[j];
-    const uint32_t thr = st.prefix;
+    const uint32_t thr = state[j].prefix;
     const uint32_t ntiles = (L.n + TILE - 1) / TILE;
     const uint32_t lt0 = (s - L.stile_begin) * GROUP;           // first tile of the super-tile, in the layer
     const uint32_t nt = min(GROUP, ntiles - lt0);
+    const float* rl = R.r[leader_of(leader, j, W)] + L.offset;
+    const float* wl = w + L.offset;
+    const bool vec = is_aligned16(rl) && is_aligned16(wl);
     if (tid < GROUP) { cg[tid] = 0u; ce[tid] = 0u; }
     __syncthreads();
-    if (st.mode == MODE_STAGED) {
-        const uint32_t* mk = A.maybe_key + L.maybe_begin;
-        for (uint32_t tl = 0; tl < nt; ++tl) {
-            const TileStage ts = stage[L.tile_begin + lt0 + tl];
-            if (tid == 0 && ts.sure_cnt) atomicAdd(&cg[tl], ts.sure_cnt);
-            for (uint32_t e = tid; e < ts.maybe_cnt; e += BLOCK) {
-                const uint32_t key = mk[ts.maybe_start + e];
-                if (key > thr) atomicAdd(&cg[tl], 1u);
-                else if (key == thr) atomicAdd(&ce[tl], 1u);
+    for (uint32_t tl = 0; tl < nt; ++tl) {
+        TileStage ts;
+        ts.n_sure = RAW_TILE; ts.n_maybe = 0;
+        if (!all_raw) ts = stage[L.tile_begin + lt0 + tl];
+        uint32_t gt = 0, eq = 0;
+        if (ts.n_sure != RAW_TILE) {
+            if (tid == 0) gt = ts.n_sure;
+            const uint64_t sb = L.slot_begin + (uint64_t)(lt0 + tl) * L.slot_cap + ts.n_sure;
+            for (uint32_t e = tid; e < ts.n_maybe; e += BLOCK) {
+                const uint32_t key = A.key[sb + e];
+                gt += key > thr ? 1u : 0u;
+                eq += key == thr ? 1u : 0u;
             }
-        }
-    } else {
-        const float* rl = R.r[leader_of(leader, j, W)] + L.offset;
-        const float* wl = w + L.offset;
-        const bool vec = is_aligned16(rl) && is_aligned16(wl);
-        for (uint32_t tl = 0; tl < nt; ++tl) {
-            uint32_t gt = 0, eq = 0;
+        } else {
             for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
                 const uint32_t i = (lt0 + tl) * TILE + u * CHUNK + tid * VEC;
                 if (i >= L.n) break;
@@ -340,9 +302,9 @@ __global__ __launch_bounds__(BLOCK) void k_count(ResidualPtrs R, const float* __
                     eq += (valid && key == thr) ? 1u : 0u;
                 }
             }
-            if (gt) atomicAdd(&cg[tl], gt);
-            if (eq) atomicAdd(&ce[tl], eq);
         }
+        if (gt) atomicAdd(&cg[tl], gt);
+        if (eq) atomicAdd(&ce[tl], eq);
     }
     __syncthreads();
     if (tid == 0) {
@@ -389,7 +351,7 @@ __global__ __launch_bounds__(BLOCK) void k_write(ResidualPtrs R, const float* __
                                                  const DevLayer* __restrict__ layers, uint32_t n_layers,
                                                  const uint32_t* __restrict__ leader, uint32_t W, float eps,
                                                  const LayerState* __restrict__ state,
-                                                 const TileStage* __restrict__ stage, StageArrays A,
+                                                 const TileStage* __restrict__ stage, StageArrays A, bool all_raw,
                                                  const uint2* __restrict__ tile_counts,
                                                  const uint2* __restrict__ stile_counts,
                                                  uint32_t* __restrict__ tile_out,
@@ -406,6 +368,8 @@ __global__ __launch_bounds__(BLOCK) void k_write(ResidualPtrs R, const float* __
     const uint32_t thr = st.prefix, quota = st.n_eq_take;
     const uint32_t lead = leader_of(leader, j, W);
     float* rl = R.r[lead] + L.offset;
+    const float* wl = w + L.offset;
+    const bool vec = is_aligned16(rl) && is_aligned16(wl);
     const uint32_t ntiles = (L.n + TILE - 1) / TILE;
     const uint32_t lt0 = (s - L.stile_begin) * GROUP;
     const uint32_t nt = min(GROUP, ntiles - lt0);
@@ -414,58 +378,49 @@ __global__ __launch_bounds__(BLOCK) void k_write(ResidualPtrs R, const float* __
     float* vo = val_out + L.out_offset;
     float* go = FUSED ? gathered + (size_t)lead * K + L.out_offset : nullptr;
 
-    if (st.mode == MODE_STAGED) {
-        const uint32_t* mk = A.maybe_key + L.maybe_begin;
-        const uint32_t* mi = A.maybe_idx + L.maybe_begin;
-        const float* mv = A.maybe_val + L.maybe_begin;
-        const uint32_t* si = A.sure_idx + L.out_offset;
-        const float* sv = A.sure_val + L.out_offset;
-        for (uint32_t tl = 0; tl < nt; ++tl) {
-            const uint32_t t = L.tile_begin + lt0 + tl;
-            const TileStage ts = stage[t];
-            const uint2 tc = tile_counts[t];
-            const uint32_t Gt = sc.x + tc.x, Et = sc.y + tc.y;
-            const uint32_t out_base = Gt + min(Et, quota);
-            const uint32_t tile_first = (lt0 + tl) * TILE;
-            if (tid == 0) tile_out[t] = out_base;
-            if (ts.sure_cnt == 0 && ts.maybe_cnt == 0) continue;           // uniform
+    for (uint32_t tl = 0; tl < nt; ++tl) {
+        const uint32_t t = L.tile_begin + lt0 + tl;
+        TileStage ts;
+        ts.n_sure = RAW_TILE; ts.n_maybe = 0;
+        if (!all_raw) ts = stage[t];
+        const uint2 tc = tile_counts[t];
+        const uint32_t Gt = sc.x + tc.x, Et = sc.y + tc.y;     // elements above / tying, before this tile
+        const uint32_t out_base = Gt + min(Et, quota);
+        const uint32_t tile_first = (lt0 + tl) * TILE;
+        if (tid == 0) tile_out[t] = out_base;
+
+        if (ts.n_sure != RAW_TILE) {
+            const uint32_t cnt = ts.n_sure + ts.n_maybe;
+            if (cnt == 0) continue;                                          // uniform
+            const uint64_t sb = L.slot_begin + (uint64_t)(lt0 + tl) * L.slot_cap;
             if (tid < TILE_WORDS) { eqmap[tid] = 0u; selmap[tid] = 0u; }
             __syncthreads();
-            for (uint32_t e = tid; e < ts.maybe_cnt; e += BLOCK) {
-                if (mk[ts.maybe_start + e] == thr) {
-                    const uint32_t loc = (mi[ts.maybe_start + e] - tile_first) & (TILE - 1);
+            for (uint32_t e = ts.n_sure + tid; e < cnt; e += BLOCK) {
+                if (A.key[sb + e] == thr) {
+                    const uint32_t loc = (A.idx[sb + e] - tile_first) & (TILE - 1);
                     atomicOr(&eqmap[loc >> 5], 1u << (loc & 31u));
                 }
             }
             __syncthreads();
             bitmap_prefix(eqmap, eqpre, slot[0]);
-            for (uint32_t e = tid; e < ts.maybe_cnt; e += BLOCK) {
-                const uint32_t key = mk[ts.maybe_start + e];
-                const uint32_t loc = (mi[ts.maybe_start + e] - tile_first) & (TILE - 1);
-                const bool sel = key > thr || (key == thr && Et + bitmap_rank(eqmap, eqpre, loc) < quota);
+            for (uint32_t e = tid; e < cnt; e += BLOCK) {
+                const uint32_t loc = (A.idx[sb + e] - tile_first) & (TILE - 1);
+                bool sel = true;                                             // a sure entry
+                if (e >= ts.n_sure) {
+                    const uint32_t key = A.key[sb + e];
+                    sel = key > thr || (key == thr && Et + bitmap_rank(eqmap, eqpre, loc) < quota);
+                }
                 if (sel) atomicOr(&selmap[loc >> 5], 1u << (loc & 31u));
-            }
-            for (uint32_t e = tid; e < ts.sure_cnt; e += BLOCK) {
-                const uint32_t loc = (si[ts.sure_start + e] - tile_first) & (TILE - 1);
-                atomicOr(&selmap[loc >> 5], 1u << (loc & 31u));
             }
             __syncthreads();
             bitmap_prefix(selmap, selpre, slot[1]);
-            for (uint32_t e = tid; e < ts.sure_cnt + ts.maybe_cnt; e += BLOCK) {
-                uint32_t li;
-                float v;
-                if (e < ts.sure_cnt) {
-                    li = si[ts.sure_start + e];
-                    v = sv[ts.sure_start + e];
-                } else {
-                    const uint32_t m = ts.maybe_start + (e - ts.sure_cnt);
-                    li = mi[m];
-                    v = mv[m];
-                }
+            for (uint32_t e = tid; e < cnt; e += BLOCK) {
+                const uint32_t li = A.idx[sb + e];
                 const uint32_t loc = (li - tile_first) & (TILE - 1);
                 if ((selmap[loc >> 5] >> (loc & 31u)) & 1u) {
                     const uint32_t pos = out_base + bitmap_rank(selmap, selpre, loc);
                     if (pos < L.k && li < L.n) {
+                        const float v = A.val[sb + e];
                         io[pos] = (uint32_t)(L.offset + li);
                         vo[pos] = v;
                         if (FUSED) { go[pos] = v; rl[li] = 0.0f; }
@@ -473,54 +428,50 @@ __global__ __launch_bounds__(BLOCK) void k_write(ResidualPtrs R, const float* __
                 }
             }
             __syncthreads();
-        }
-        return;
-    }
-
-    // RAW route: every element of the super-tile is scored again, chunk by chunk
-    const float* wl = w + L.offset;
-    const bool vec = is_aligned16(rl) && is_aligned16(wl);
-    const uint2 tc0 = tile_counts[L.tile_begin + lt0];
-    uint32_t G = sc.x + tc0.x, E = sc.y + tc0.y;
-    for (uint32_t c = 0; c < nt * CHUNKS_PER_TILE; ++c) {
-        const uint32_t cbase = lt0 * TILE + c * CHUNK;
-        if (cbase >= L.n) break;                                            // uniform
-        if ((c % CHUNKS_PER_TILE) == 0 && tid == 0) tile_out[L.tile_begin + lt0 + c / CHUNKS_PER_TILE] = G + min(E, quota);
-        const uint32_t i = cbase + tid * VEC;
-        float rv[4] = {0.f, 0.f, 0.f, 0.f}, wv[4] = {1.f, 1.f, 1.f, 1.f};
-        if (i < L.n) {
-            load_quad(rl, i, L.n, vec, rv);
-            load_quad(wl, i, L.n, vec, wv, 1.0f);
-        }
-        uint32_t key[4];
-        uint32_t packed = 0;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            key[q] = score_key(rv[q], wv[q], eps);
-            const bool valid = i + q < L.n;
-            packed += (valid && key[q] > thr) ? 1u : 0u;
-            packed += (valid && key[q] == thr) ? 0x10000u : 0u;
-        }
-        uint32_t tot;
-        const uint32_t ex = block_exclusive_scan(packed, slot[c & 1], &tot);
-        uint32_t gpre = G + (ex & 0xffffu);
-        uint32_t epre = E + (ex >> 16);
-        if (packed) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                if (i + q >= L.n) break;
-                uint32_t pos = 0xFFFFFFFFu;
-                if (key[q] > thr) { pos = gpre + min(epre, quota); ++gpre; }
-                else if (key[q] == thr) { if (epre < quota) pos = gpre + epre; ++epre; }
-                if (pos < L.k) {
-                    io[pos] = (uint32_t)(L.offset + i + q);
-                    vo[pos] = rv[q];
-                    if (FUSED) { go[pos] = rv[q]; rl[i + q] = 0.0f; }
+        } else {
+            // RAW tile: every element is scored again, chunk by chunk
+            uint32_t G = Gt, E = Et;
+            for (uint32_t c = 0; c < CHUNKS_PER_TILE; ++c) {
+                const uint32_t cbase = tile_first + c * CHUNK;
+                if (cbase >= L.n) break;                                        // uniform
+                const uint32_t i = cbase + tid * VEC;
+                float rv[4] = {0.f, 0.f, 0.f, 0.f}, wv[4] = {1.f, 1.f, 1.f, 1.f};
+                if (i < L.n) {
+                    load_quad(rl, i, L.n, vec, rv);
+                    load_quad(wl, i, L.n, vec, wv, 1.0f);
                 }
+                uint32_t key[4];
+                uint32_t packed = 0;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    key[q] = score_key(rv[q], wv[q], eps);
+                    const bool valid = i + q < L.n;
+                    packed += (valid && key[q] > thr) ? 1u : 0u;
+                    packed += (valid && key[q] == thr) ? 0x10000u : 0u;
+                }
+                uint32_t tot;
+                const uint32_t ex = block_exclusive_scan(packed, slot[c & 1], &tot);
+                uint32_t gpre = G + (ex & 0xffffu);
+                uint32_t epre = E + (ex >> 16);
+                if (packed) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        if (i + q >= L.n) break;
+                        uint32_t pos = 0xFFFFFFFFu;
+                        if (key[q] > thr) { pos = gpre + min(epre, quota); ++gpre; }
+                        else if (key[q] == thr) { if (epre < quota) pos = gpre + epre; ++epre; }
+                        if (pos < L.k) {
+                            io[pos] = (uint32_t)(L.offset + i + q);
+                            vo[pos] = rv[q];
+                            if (FUSED) { go[pos] = rv[q]; rl[i + q] = 0.0f; }
+                        }
+                    }
+                }
+                G += tot & 0xffffu;
+                E += tot >> 16;
             }
+            __syncthreads();
         }
-        G += tot & 0xffffu;
-        E += tot >> 16;
     }
 }
 
