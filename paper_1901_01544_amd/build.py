@@ -40,15 +40,16 @@ def hipcc() -> str:
     return "hipcc"
 
 
-def build(verbose: bool = False) -> str:
-    """Compile csrc/ into libiwp.so (always recompiles); returns the path."""
-    tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [hipcc(), *HIPCC_FLAGS, "-o", tmp, SRC]
+def build(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
+    """Compile csrc/ into libiwp.so (always recompiles); returns the path.
+    extra_flags / out: build a tuning variant (e.g. -DIWP_LGROUP=4) somewhere else."""
+    tmp = out + ".tmp.%d" % os.getpid()
+    cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags, "-o", tmp, SRC]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, out)
+    return out
 
 
 if __name__ == "__main__":

@@ -168,10 +168,10 @@ int run_select(const Table& T, const Workspace& ws, const ResidualPtrs& R, const
                false, ws.tile_counts, ws.stile_counts);
     IWP_LAUNCH("k_scan", k_scan, T.n_layers, s, T.layers, ws.stile_counts);
     if (fused)
-        IWP_LAUNCH("k_write", k_write<true>, T.stiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.stage,
+        IWP_LAUNCH("k_write", k_write<true>, T.tiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.stage,
                    ws.A, false, ws.tile_counts, ws.stile_counts, ws.tile_out, idx_out, val_out, ws.gathered, T.pairs);
     else
-        IWP_LAUNCH("k_write", k_write<false>, T.stiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.stage,
+        IWP_LAUNCH("k_write", k_write<false>, T.tiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.stage,
                    ws.A, false, ws.tile_counts, ws.stile_counts, ws.tile_out, idx_out, val_out, nullptr, T.pairs);
     return IWP_OK;
 }
@@ -185,7 +185,7 @@ int run_compact_from(const Table& T, const Workspace& ws, const ResidualPtrs& R,
     IWP_LAUNCH("k_count", k_count, T.stiles, s, R, w, T.layers, T.n_layers, nullptr, 1u, eps, ws.state, ws.stage, ws.A,
                true, ws.tile_counts, ws.stile_counts);
     IWP_LAUNCH("k_scan", k_scan, T.n_layers, s, T.layers, ws.stile_counts);
-    IWP_LAUNCH("k_write", k_write<false>, T.stiles, s, R, w, T.layers, T.n_layers, nullptr, 1u, eps, ws.state, ws.stage,
+    IWP_LAUNCH("k_write", k_write<false>, T.tiles, s, R, w, T.layers, T.n_layers, nullptr, 1u, eps, ws.state, ws.stage,
                ws.A, true, ws.tile_counts, ws.stile_counts, ws.tile_out, idx_out, val_out, nullptr, T.pairs);
     return IWP_OK;
 }
@@ -469,7 +469,7 @@ int iwp_step_segmented(const iwp_plan* plan, float* w, const float* const* g, fl
     if (rc) return rc;
     Table T{plan->dev, z.n_layers, z.tiles, z.stiles, z.pairs, plan->any_k};
     if (T.any_k) {
-        IWP_LAUNCH("k_leader_pass", k_leader_pass, T.stiles, s, P, w, T.layers, T.n_layers, leader, W, eps, ws.hist);
+        IWP_LAUNCH("k_leader_pass", k_leader_pass, T.stiles * (GROUP / LGROUP), s, P, w, T.layers, T.n_layers, leader, W, eps, ws.hist);
         rc = run_select(T, ws, R, w, leader, W, eps, FULL, true, idx_out, val_out, thr_out, s);
         if (rc) return rc;
     }
@@ -500,7 +500,7 @@ int select_threshold_segmented(const iwp_plan* plan, const float* w, const float
     memset(&R, 0, sizeof R);
     R.r[0] = const_cast<float*>(r);
     Table T{plan->dev, plan->z.n_layers, plan->z.tiles, plan->z.stiles, plan->z.pairs, plan->any_k};
-    IWP_LAUNCH("k_leader_pass", k_leader_pass, T.stiles, s, P, w, T.layers, T.n_layers, nullptr, 1u, eps, ws.hist);
+    IWP_LAUNCH("k_leader_pass", k_leader_pass, T.stiles * (GROUP / LGROUP), s, P, w, T.layers, T.n_layers, nullptr, 1u, eps, ws.hist);
     return run_select(T, ws, R, w, nullptr, 1u, eps, STOP_AT_THRESHOLD, false, nullptr, nullptr, thr_out, s);
 }
 

@@ -125,22 +125,38 @@ __global__ __launch_bounds__(BLOCK) void k_stage(ResidualPtrs R, const float* __
 
     uint32_t key[CHUNKS_PER_TILE][4];
     float val[CHUNKS_PER_TILE][4];
+    float wgt[CHUNKS_PER_TILE][4];
+    const bool full = vec && base + TILE <= L.n;
+    if (full) {
+#pragma unroll
+        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+            const uint32_t i = base + u * CHUNK + tid * VEC;
+            const v4f a = load_v4<true>(rl + i);
+            const v4f b = load_v4<true>(wl + i);
+            val[u][0] = a.x; val[u][1] = a.y; val[u][2] = a.z; val[u][3] = a.w;
+            wgt[u][0] = b.x; wgt[u][1] = b.y; wgt[u][2] = b.z; wgt[u][3] = b.w;
+        }
+    } else {
+#pragma unroll
+        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+            const uint32_t i = base + u * CHUNK + tid * VEC;
+            if (i < L.n) {
+                load_quad(rl, i, L.n, vec, val[u]);
+                load_quad(wl, i, L.n, vec, wgt[u], 1.0f);
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) { val[u][q] = 0.0f; wgt[u][q] = 1.0f; }
+            }
+        }
+    }
     uint32_t packed = 0;                      // low half: sure count, high half: maybe count (this lane)
 #pragma unroll
     for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
         const uint32_t i = base + u * CHUNK + tid * VEC;
-        float wv[4];
-        if (i < L.n) {
-            load_quad(rl, i, L.n, vec, val[u]);
-            load_quad(wl, i, L.n, vec, wv, 1.0f);
-        } else {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) { val[u][q] = 0.0f; wv[q] = 1.0f; }
-        }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            if (i + q < L.n) {
-                key[u][q] = score_key(val[u][q], wv[q], eps);
+            if (full || i + q < L.n) {
+                key[u][q] = score_key(val[u][q], wgt[u][q], eps);
                 const uint32_t d0 = key[u][q] >> digit_shift(0);
                 if (d0 > b1) packed += 1u;
                 else if (d0 == b1) packed += 0x10000u;
@@ -346,6 +362,7 @@ __global__ __launch_bounds__(BLOCK) void k_scan(const DevLayer* __restrict__ lay
 // residual itself).  tile_out[t] receives the position of the tile's first pair.
 // FUSED (whole-step entry point): the value also goes into the leader's row of the
 // gather matrix and the leader's residual is cleared at the sent position.
+// One workgroup per tile.
 template <bool FUSED>
 __global__ __launch_bounds__(BLOCK) void k_write(ResidualPtrs R, const float* __restrict__ w,
                                                  const DevLayer* __restrict__ layers, uint32_t n_layers,
@@ -360,118 +377,111 @@ __global__ __launch_bounds__(BLOCK) void k_write(ResidualPtrs R, const float* __
     __shared__ uint32_t eqmap[TILE_WORDS], eqpre[TILE_WORDS], selmap[TILE_WORDS], selpre[TILE_WORDS];
     __shared__ uint32_t slot[2][4];
     const uint32_t tid = threadIdx.x;
-    const uint32_t s = blockIdx.x;
-    const uint32_t j = find_layer<true>(layers, n_layers, s);
+    const uint32_t t = blockIdx.x;
+    const uint32_t j = find_layer<false>(layers, n_layers, t);
     const DevLayer L = layers[j];
     if (L.k == 0) return;
     const LayerState st = state[j];
     const uint32_t thr = st.prefix, quota = st.n_eq_take;
     const uint32_t lead = leader_of(leader, j, W);
     float* rl = R.r[lead] + L.offset;
-    const float* wl = w + L.offset;
-    const bool vec = is_aligned16(rl) && is_aligned16(wl);
-    const uint32_t ntiles = (L.n + TILE - 1) / TILE;
-    const uint32_t lt0 = (s - L.stile_begin) * GROUP;
-    const uint32_t nt = min(GROUP, ntiles - lt0);
-    const uint2 sc = stile_counts[s];
+    const uint32_t lt = t - L.tile_begin;
+    const uint2 sc = stile_counts[L.stile_begin + lt / GROUP];
+    const uint2 tc = tile_counts[t];
+    const uint32_t Gt = sc.x + tc.x, Et = sc.y + tc.y;         // elements above / tying, before this tile
+    const uint32_t out_base = Gt + min(Et, quota);
+    const uint32_t tile_first = lt * TILE;
     uint32_t* io = idx_out + L.out_offset;
     float* vo = val_out + L.out_offset;
     float* go = FUSED ? gathered + (size_t)lead * K + L.out_offset : nullptr;
+    if (tid == 0) tile_out[t] = out_base;
+    TileStage ts;
+    ts.n_sure = RAW_TILE; ts.n_maybe = 0;
+    if (!all_raw) ts = stage[t];
 
-    for (uint32_t tl = 0; tl < nt; ++tl) {
-        const uint32_t t = L.tile_begin + lt0 + tl;
-        TileStage ts;
-        ts.n_sure = RAW_TILE; ts.n_maybe = 0;
-        if (!all_raw) ts = stage[t];
-        const uint2 tc = tile_counts[t];
-        const uint32_t Gt = sc.x + tc.x, Et = sc.y + tc.y;     // elements above / tying, before this tile
-        const uint32_t out_base = Gt + min(Et, quota);
-        const uint32_t tile_first = (lt0 + tl) * TILE;
-        if (tid == 0) tile_out[t] = out_base;
-
-        if (ts.n_sure != RAW_TILE) {
-            const uint32_t cnt = ts.n_sure + ts.n_maybe;
-            if (cnt == 0) continue;                                          // uniform
-            const uint64_t sb = L.slot_begin + (uint64_t)(lt0 + tl) * L.slot_cap;
-            if (tid < TILE_WORDS) { eqmap[tid] = 0u; selmap[tid] = 0u; }
-            __syncthreads();
-            for (uint32_t e = ts.n_sure + tid; e < cnt; e += BLOCK) {
-                if (A.key[sb + e] == thr) {
-                    const uint32_t loc = (A.idx[sb + e] - tile_first) & (TILE - 1);
-                    atomicOr(&eqmap[loc >> 5], 1u << (loc & 31u));
-                }
-            }
-            __syncthreads();
-            bitmap_prefix(eqmap, eqpre, slot[0]);
-            for (uint32_t e = tid; e < cnt; e += BLOCK) {
+    if (ts.n_sure != RAW_TILE) {
+        const uint32_t cnt = ts.n_sure + ts.n_maybe;
+        if (cnt == 0) return;                                            // uniform
+        const uint64_t sb = L.slot_begin + (uint64_t)lt * L.slot_cap;
+        if (tid < TILE_WORDS) { eqmap[tid] = 0u; selmap[tid] = 0u; }
+        __syncthreads();
+        for (uint32_t e = ts.n_sure + tid; e < cnt; e += BLOCK) {
+            if (A.key[sb + e] == thr) {
                 const uint32_t loc = (A.idx[sb + e] - tile_first) & (TILE - 1);
-                bool sel = true;                                             // a sure entry
-                if (e >= ts.n_sure) {
-                    const uint32_t key = A.key[sb + e];
-                    sel = key > thr || (key == thr && Et + bitmap_rank(eqmap, eqpre, loc) < quota);
-                }
-                if (sel) atomicOr(&selmap[loc >> 5], 1u << (loc & 31u));
+                atomicOr(&eqmap[loc >> 5], 1u << (loc & 31u));
             }
-            __syncthreads();
-            bitmap_prefix(selmap, selpre, slot[1]);
-            for (uint32_t e = tid; e < cnt; e += BLOCK) {
-                const uint32_t li = A.idx[sb + e];
-                const uint32_t loc = (li - tile_first) & (TILE - 1);
-                if ((selmap[loc >> 5] >> (loc & 31u)) & 1u) {
-                    const uint32_t pos = out_base + bitmap_rank(selmap, selpre, loc);
-                    if (pos < L.k && li < L.n) {
-                        const float v = A.val[sb + e];
-                        io[pos] = (uint32_t)(L.offset + li);
-                        vo[pos] = v;
-                        if (FUSED) { go[pos] = v; rl[li] = 0.0f; }
-                    }
-                }
-            }
-            __syncthreads();
-        } else {
-            // RAW tile: every element is scored again, chunk by chunk
-            uint32_t G = Gt, E = Et;
-            for (uint32_t c = 0; c < CHUNKS_PER_TILE; ++c) {
-                const uint32_t cbase = tile_first + c * CHUNK;
-                if (cbase >= L.n) break;                                        // uniform
-                const uint32_t i = cbase + tid * VEC;
-                float rv[4] = {0.f, 0.f, 0.f, 0.f}, wv[4] = {1.f, 1.f, 1.f, 1.f};
-                if (i < L.n) {
-                    load_quad(rl, i, L.n, vec, rv);
-                    load_quad(wl, i, L.n, vec, wv, 1.0f);
-                }
-                uint32_t key[4];
-                uint32_t packed = 0;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    key[q] = score_key(rv[q], wv[q], eps);
-                    const bool valid = i + q < L.n;
-                    packed += (valid && key[q] > thr) ? 1u : 0u;
-                    packed += (valid && key[q] == thr) ? 0x10000u : 0u;
-                }
-                uint32_t tot;
-                const uint32_t ex = block_exclusive_scan(packed, slot[c & 1], &tot);
-                uint32_t gpre = G + (ex & 0xffffu);
-                uint32_t epre = E + (ex >> 16);
-                if (packed) {
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        if (i + q >= L.n) break;
-                        uint32_t pos = 0xFFFFFFFFu;
-                        if (key[q] > thr) { pos = gpre + min(epre, quota); ++gpre; }
-                        else if (key[q] == thr) { if (epre < quota) pos = gpre + epre; ++epre; }
-                        if (pos < L.k) {
-                            io[pos] = (uint32_t)(L.offset + i + q);
-                            vo[pos] = rv[q];
-                            if (FUSED) { go[pos] = rv[q]; rl[i + q] = 0.0f; }
-                        }
-                    }
-                }
-                G += tot & 0xffffu;
-                E += tot >> 16;
-            }
-            __syncthreads();
         }
+        __syncthreads();
+        bitmap_prefix(eqmap, eqpre, slot[0]);
+        for (uint32_t e = tid; e < cnt; e += BLOCK) {
+            const uint32_t loc = (A.idx[sb + e] - tile_first) & (TILE - 1);
+            bool sel = true;                                             // a sure entry
+            if (e >= ts.n_sure) {
+                const uint32_t key = A.key[sb + e];
+                sel = key > thr || (key == thr && Et + bitmap_rank(eqmap, eqpre, loc) < quota);
+            }
+            if (sel) atomicOr(&selmap[loc >> 5], 1u << (loc & 31u));
+        }
+        __syncthreads();
+        bitmap_prefix(selmap, selpre, slot[1]);
+        for (uint32_t e = tid; e < cnt; e += BLOCK) {
+            const uint32_t li = A.idx[sb + e];
+            const uint32_t loc = (li - tile_first) & (TILE - 1);
+            if ((selmap[loc >> 5] >> (loc & 31u)) & 1u) {
+                const uint32_t pos = out_base + bitmap_rank(selmap, selpre, loc);
+                if (pos < L.k && li < L.n) {
+                    const float v = A.val[sb + e];
+                    io[pos] = (uint32_t)(L.offset + li);
+                    vo[pos] = v;
+                    if (FUSED) { go[pos] = v; rl[li] = 0.0f; }
+                }
+            }
+        }
+        return;
+    }
+
+    // RAW tile: every element is scored again, chunk by chunk
+    const float* wl = w + L.offset;
+    const bool vec = is_aligned16(rl) && is_aligned16(wl);
+    uint32_t G = Gt, E = Et;
+    for (uint32_t c = 0; c < CHUNKS_PER_TILE; ++c) {
+        const uint32_t cbase = tile_first + c * CHUNK;
+        if (cbase >= L.n) break;                                            // uniform
+        const uint32_t i = cbase + tid * VEC;
+        float rv[4] = {0.f, 0.f, 0.f, 0.f}, wv[4] = {1.f, 1.f, 1.f, 1.f};
+        if (i < L.n) {
+            load_quad(rl, i, L.n, vec, rv);
+            load_quad(wl, i, L.n, vec, wv, 1.0f);
+        }
+        uint32_t key[4];
+        uint32_t packed = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            key[q] = score_key(rv[q], wv[q], eps);
+            const bool valid = i + q < L.n;
+            packed += (valid && key[q] > thr) ? 1u : 0u;
+            packed += (valid && key[q] == thr) ? 0x10000u : 0u;
+        }
+        uint32_t tot;
+        const uint32_t ex = block_exclusive_scan(packed, slot[c & 1], &tot);
+        uint32_t gpre = G + (ex & 0xffffu);
+        uint32_t epre = E + (ex >> 16);
+        if (packed) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (i + q >= L.n) break;
+                uint32_t pos = 0xFFFFFFFFu;
+                if (key[q] > thr) { pos = gpre + min(epre, quota); ++gpre; }
+                else if (key[q] == thr) { if (epre < quota) pos = gpre + epre; ++epre; }
+                if (pos < L.k) {
+                    io[pos] = (uint32_t)(L.offset + i + q);
+                    vo[pos] = rv[q];
+                    if (FUSED) { go[pos] = rv[q]; rl[i + q] = 0.0f; }
+                }
+            }
+        }
+        G += tot & 0xffffu;
+        E += tot >> 16;
     }
 }
 
