@@ -70,6 +70,9 @@ def main():
     ap.add_argument("--route", default="whole_step", choices=["whole_step", "three_calls"],
                     help="whole_step: iwp_step_segmented; three_calls: compress_segmented + gather_sum_at_indices "
                          "+ apply_sparse_update (same results)")
+    ap.add_argument("--no-hint", action="store_true",
+                    help="whole_step only: do not pass the previous step's thresholds as a hint (results are "
+                         "identical either way; the hint saves the second pass over the leaders' layers)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--scale-down", type=int, default=1, help="shrink the many_small / flat workloads (debug)")
     args = ap.parse_args()
@@ -121,7 +124,9 @@ def main():
     idx = torch.empty(ps.K, dtype=torch.int32, device=dev)
     val = torch.empty(ps.K, dtype=torch.float32, device=dev)
     sm = torch.empty(ps.K, dtype=torch.float32, device=dev)
-    thr = torch.zeros(3 * len(ps.layers), dtype=torch.int32, device=dev)
+    thr2 = [torch.zeros(3 * len(ps.layers), dtype=torch.int32, device=dev) for _ in range(2)]   # ping-pong: the
+    thr = thr2[0]                                     # records of step t-1 are the hint of step t
+    use_hint = fused and not args.no_hint
     total = args.warmup + args.steps
     if flat_cfg:
         lead_np = np.zeros((total, 1), np.int32)
@@ -137,7 +142,9 @@ def main():
         else:
             g = [grads[wl.gradient_set_of(ps, p, t, pool)] for p in range(ps.W)]
         if fused:
-            iwp.step_segmented(plan, w, g, r, leaders[t], eps, scale, idx, val, sm, thr, ws, stream)
+            hint = thr2[(t + 1) % 2] if (use_hint and t > 0) else None
+            iwp.step_segmented(plan, w, g, r, leaders[t], eps, scale, idx, val, sm, thr2[t % 2], ws, stream,
+                               thr_hint=hint)
         else:
             iwp.compress_segmented(plan, w, g, r, leaders[t], eps, idx, val, thr, ws, stream)
             iwp.gather_sum_at_indices(r, idx, ps.K, sm, stream)
@@ -189,7 +196,8 @@ def main():
         "config": {"workload": ps.name, "config_id": cfg, "tensors": len(ps.layers), "params": ps.P,
                    "pairs_per_step": ps.K, "workers_accumulating": W_acc, "residual_list": W_list,
                    "keep": "1/64" if cfg in (1, 2) else ("1/58.8" if cfg == 3 else ("U(0.5%,5%)" if cfg == 4 else "0.1%")),
-                   "eps": eps, "gradient_pool": pool, "route": args.route},
+                   "eps": eps, "gradient_pool": pool, "route": args.route,
+                   "threshold_hint": "previous step" if use_hint else "none"},
         "worker_params_per_s": ps.P * W_acc * args.steps / elapsed,
         "step_algorithmic_bytes": algo_bytes,
         "step_algorithmic_GBps": algo_bytes / (ms_per_step * 1e-3) / 1e9,

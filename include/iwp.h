@@ -173,9 +173,16 @@ int compress_segmented(const iwp_plan* plan, const float* w, const float* const*
  * w[idx] += scale * sum and is done.  A worker with g[p] == NULL is not accumulated
  * but still gathered and cleared.  Outputs as in the three separate calls:
  * idx_out / val_out (K pairs), sum_out (K), thr_out (n_layers records or NULL);
- * w and every r[p] are updated in place.  Workspace: iwp_plan_step_workspace_bytes. */
+ * w and every r[p] are updated in place.  Workspace: iwp_plan_step_workspace_bytes.
+ * thr_hint: NULL, or a device array of n_layers threshold records that are
+ * expected to be close to this call's (typically the previous step's thr_out; a
+ * different buffer than thr_out).  The hint never changes any output: it lets the
+ * first pass over a leader's layer already copy out every element from slightly
+ * below the hinted threshold, which makes the second pass over that layer
+ * unnecessary whenever the new threshold is not below that mark; otherwise, and
+ * for records that are wrong or garbage, the layer just takes the two-pass route. */
 int iwp_step_segmented(const iwp_plan* plan, float* w, const float* const* g, float* const* r, uint32_t W,
-                       const uint32_t* leader, float eps, float scale,
+                       const uint32_t* leader, const iwp_threshold* thr_hint, float eps, float scale,
                        uint32_t* idx_out, float* val_out, float* sum_out, iwp_threshold* thr_out,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
 

@@ -91,11 +91,10 @@ struct Sizes {                // everything the workspace layout depends on
 // Carving of a caller-supplied workspace.
 struct Workspace {
     DevLayer* single_table;   // 2 rows, used by the single-layer entry points
-    uint32_t* zeroed;         // start of the region k_init clears: histograms, then states
-    uint64_t zeroed_words;
+    uint64_t hist_words;      // what k_init clears
     uint32_t* hist;           // n_layers * HIST_STRIDE
     LayerState* state;        // n_layers
-    TileStage* stage;         // tiles
+    uint32_t* stage;          // tiles: staged entries per tile, or RAW_TILE
     uint2* tile_counts;       // tiles
     uint2* stile_counts;      // stiles
     uint32_t* tile_out;       // tiles
@@ -114,9 +113,8 @@ Workspace carve(void* base, const Sizes& z) {
     const size_t state_bytes = round256((size_t)z.n_layers * sizeof(LayerState));
     ws.hist = reinterpret_cast<uint32_t*>(take(hist_bytes));
     ws.state = reinterpret_cast<LayerState*>(take(state_bytes));
-    ws.zeroed = ws.hist;
-    ws.zeroed_words = (hist_bytes + state_bytes) / sizeof(uint32_t);
-    ws.stage = reinterpret_cast<TileStage*>(take((size_t)z.tiles * sizeof(TileStage)));
+    ws.hist_words = (uint64_t)z.n_layers * HIST_STRIDE;
+    ws.stage = reinterpret_cast<uint32_t*>(take((size_t)z.tiles * sizeof(uint32_t)));
     ws.tile_counts = reinterpret_cast<uint2*>(take((size_t)z.tiles * sizeof(uint2)));
     ws.stile_counts = reinterpret_cast<uint2*>(take((size_t)z.stiles * sizeof(uint2)));
     ws.tile_out = reinterpret_cast<uint32_t*>(take((size_t)z.tiles * sizeof(uint32_t)));
@@ -137,13 +135,14 @@ struct Table {                // what the launches need to know about a layer ta
 
 int check_eps(float eps) { return (eps >= 0.0f && std::isfinite(eps)) ? IWP_OK : IWP_EINVAL; }
 
-int launch_init(const Workspace& ws, const DevLayer* row, const DevLayer* sentinel, hipStream_t s) {
-    uint32_t grid = (uint32_t)std::min<uint64_t>((ws.zeroed_words + BLOCK - 1) / BLOCK, 4096);
+int launch_init(const Workspace& ws, uint32_t n_layers, const iwp_threshold* hint, const DevLayer* row,
+                const DevLayer* sentinel, hipStream_t s) {
+    uint32_t grid = (uint32_t)std::min<uint64_t>((ws.hist_words + BLOCK - 1) / BLOCK, 4096);
     if (grid == 0) grid = 1;
     DevLayer zero;
     memset(&zero, 0, sizeof zero);
-    IWP_LAUNCH("k_init", k_init, grid, s, ws.zeroed, ws.zeroed_words, row ? ws.single_table : nullptr,
-               row ? *row : zero, sentinel ? *sentinel : zero);
+    IWP_LAUNCH("k_init", k_init, grid, s, ws.hist, ws.hist_words, ws.state, n_layers, hint,
+               row ? ws.single_table : nullptr, row ? *row : zero, sentinel ? *sentinel : zero);
     return IWP_OK;
 }
 
@@ -257,11 +256,12 @@ static int single_common(SingleOp op, const float* w, const float* g, float* r, 
     memset(&sentinel, 0, sizeof sentinel);
     row.n = n; row.k = k; row.slot_cap = slot_cap_of(n, k);
     sentinel.tile_begin = z.tiles; sentinel.stile_begin = z.stiles; sentinel.out_offset = k;
-    int rc = launch_init(ws, &row, &sentinel, s);
+    int rc = launch_init(ws, 1, nullptr, &row, &sentinel, s);
     if (rc) return rc;
     Table T{ws.single_table, 1, z.tiles, z.stiles, k, k > 0};
     if (op == OP_COMPACT) return run_compact_from(T, ws, R, w, eps, from_thr, idx_out, val_out, s);
-    IWP_LAUNCH("k_accumulate_all", k_accumulate_all, z.tiles, s, P, w, T.layers, 1u, z.tiles, nullptr, 1u, eps, ws.hist);
+    IWP_LAUNCH("k_accumulate_all", k_accumulate_all, z.tiles, s, P, w, T.layers, 1u, z.tiles, nullptr, 1u, eps, ws.hist,
+               ws.state, ws.stage, ws.A);
     return run_select(T, ws, R, w, nullptr, 1u, eps, op == OP_SELECT ? STOP_AT_THRESHOLD : FULL, false, idx_out,
                       val_out, thr_out, s);
 }
@@ -435,25 +435,26 @@ int compress_segmented(const iwp_plan* plan, const float* w, const float* const*
     if (rc) return rc;
     if (plan->z.tiles == 0) return IWP_OK;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    rc = launch_init(ws, nullptr, nullptr, s);
+    rc = launch_init(ws, plan->z.n_layers, nullptr, nullptr, nullptr, s);
     if (rc) return rc;
     Table T{plan->dev, plan->z.n_layers, plan->z.tiles, plan->z.stiles, plan->z.pairs, plan->any_k};
     IWP_LAUNCH("k_accumulate_all", k_accumulate_all, W * T.tiles, s, P, w, T.layers, T.n_layers, T.tiles, leader, W, eps,
-               ws.hist);
+               ws.hist, ws.state, ws.stage, ws.A);
     return run_select(T, ws, R, w, leader, W, eps, FULL, false, idx_out, val_out, thr_out, s);
 }
 
 int iwp_step_segmented(const iwp_plan* plan, float* w, const float* const* g, float* const* r, uint32_t W,
-                       const uint32_t* leader, float eps, float scale, uint32_t* idx_out, float* val_out,
-                       float* sum_out, iwp_threshold* thr_out, void* workspace, size_t workspace_bytes,
-                       void* hip_stream) {
+                       const uint32_t* leader, const iwp_threshold* thr_hint, float eps, float scale,
+                       uint32_t* idx_out, float* val_out, float* sum_out, iwp_threshold* thr_out, void* workspace,
+                       size_t workspace_bytes, void* hip_stream) {
     if (!plan) return IWP_EINVAL;
     if (check_eps(eps) || !std::isfinite(scale)) return IWP_EINVAL;
     if (!w) return IWP_EINVAL;
     if (plan->any_k && (!idx_out || !val_out || !sum_out)) return IWP_EINVAL;
     if (!aligned4(w) || !aligned4(idx_out) || !aligned4(val_out) || !aligned4(sum_out) || !aligned4(thr_out) ||
-        !aligned4(leader))
+        !aligned4(leader) || !aligned4(thr_hint))
         return IWP_EALIGN;
+    if (thr_hint && thr_hint == thr_out) return IWP_EINVAL;   // the hint is read while the records are written
     WorkerPtrs P;
     ResidualPtrs R;
     int rc = worker_tables(g, r, W, &P, &R);
@@ -465,11 +466,12 @@ int iwp_step_segmented(const iwp_plan* plan, float* w, const float* const* g, fl
     if (rc) return rc;
     if (z.tiles == 0) return IWP_OK;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    rc = launch_init(ws, nullptr, nullptr, s);
+    rc = launch_init(ws, z.n_layers, thr_hint, nullptr, nullptr, s);
     if (rc) return rc;
     Table T{plan->dev, z.n_layers, z.tiles, z.stiles, z.pairs, plan->any_k};
     if (T.any_k) {
-        IWP_LAUNCH("k_leader_pass", k_leader_pass, T.stiles * (GROUP / LGROUP), s, P, w, T.layers, T.n_layers, leader, W, eps, ws.hist);
+        IWP_LAUNCH("k_leader_pass", k_leader_pass, T.stiles * (GROUP / LGROUP), s, P, w, T.layers, T.n_layers, leader, W, eps,
+                   ws.hist, ws.state, ws.stage, ws.A);
         rc = run_select(T, ws, R, w, leader, W, eps, FULL, true, idx_out, val_out, thr_out, s);
         if (rc) return rc;
     }
@@ -491,7 +493,7 @@ int select_threshold_segmented(const iwp_plan* plan, const float* w, const float
     if (rc) return rc;
     if (plan->z.tiles == 0 || !plan->any_k) return IWP_OK;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    rc = launch_init(ws, nullptr, nullptr, s);
+    rc = launch_init(ws, plan->z.n_layers, nullptr, nullptr, nullptr, s);
     if (rc) return rc;
     WorkerPtrs P;
     memset(&P, 0, sizeof P);
@@ -500,7 +502,8 @@ int select_threshold_segmented(const iwp_plan* plan, const float* w, const float
     memset(&R, 0, sizeof R);
     R.r[0] = const_cast<float*>(r);
     Table T{plan->dev, plan->z.n_layers, plan->z.tiles, plan->z.stiles, plan->z.pairs, plan->any_k};
-    IWP_LAUNCH("k_leader_pass", k_leader_pass, T.stiles * (GROUP / LGROUP), s, P, w, T.layers, T.n_layers, nullptr, 1u, eps, ws.hist);
+    IWP_LAUNCH("k_leader_pass", k_leader_pass, T.stiles * (GROUP / LGROUP), s, P, w, T.layers, T.n_layers, nullptr, 1u, eps,
+               ws.hist, ws.state, ws.stage, ws.A);
     return run_select(T, ws, R, w, nullptr, 1u, eps, STOP_AT_THRESHOLD, false, nullptr, nullptr, thr_out, s);
 }
 

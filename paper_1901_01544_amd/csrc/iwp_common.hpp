@@ -37,7 +37,9 @@ constexpr uint32_t HIST0 = 1u << 12, HIST1 = 1u << 10, HIST2 = 1u << 9;
 constexpr uint32_t HIST_STRIDE = HIST0 + HIST1 + HIST2;    // words per layer; each digit has its own region
 __host__ __device__ constexpr uint32_t hist_base(int level) { return level == 0 ? 0 : (level == 1 ? HIST0 : HIST0 + HIST1); }
 
-constexpr uint32_t RAW_TILE = 0xFFFFFFFFu;     // TileStage.n_sure of a tile whose candidates did not fit its slot
+constexpr uint32_t RAW_TILE = 0xFFFFFFFFu;        // stage count of a tile whose candidates did not fit its slot
+constexpr uint32_t NO_STAGE_BIN = 0xFFFFFFFFu;    // LayerState.stage_bin: look 1 stages nothing for this layer
+constexpr uint32_t NOT_AN_ELEMENT = 0xFFFFFFFFu;  // key slot of a lane position past the layer's end
 
 struct DevLayer {
     uint64_t offset;       // first element in the flat buffers
@@ -55,11 +57,15 @@ struct LayerState {        // selection state of one layer, lives in the workspa
     uint32_t k_rem;        // rank still to be found inside the prefix group (1-based)
     uint32_t n_gt;
     uint32_t n_eq_take;
+    uint32_t stage_bin;    // look 1 copies out every element whose top digit is >= this bin (from a threshold hint)
+    uint32_t prestaged;    // set by the first pick: stage_bin <= threshold bin, so look 1's copies are complete
+    uint32_t pad0, pad1;
 };
 
-struct TileStage {         // what look 2 left in the slot of one tile: n_sure entries whose top digit
-    uint32_t n_sure;       // lies above the threshold bin, then n_maybe entries inside it;
-    uint32_t n_maybe;      // n_sure == RAW_TILE: nothing staged, later passes re-read the tile
+struct StageArrays {       // staged candidates, structure of arrays; tile t of a layer owns entries
+    uint32_t* key;         // [slot_begin + t * slot_cap, + slot_cap), filled in index order
+    uint32_t* idx;         // position inside the layer
+    float* val;
 };
 
 struct WorkerPtrs {        // passed by value as a kernel argument
@@ -217,6 +223,38 @@ __device__ __forceinline__ void bitmap_prefix(const uint32_t* map, uint32_t* pre
 __device__ __forceinline__ uint32_t bitmap_rank(const uint32_t* map, const uint32_t* prefix, uint32_t local) {
     const uint32_t wd = local >> 5, b = local & 31u;
     return prefix[wd] + __popc(map[wd] & ((1u << b) - 1u));
+}
+
+// Copy the elements of one tile whose top key digit is >= bin into the tile's slot,
+// in index order.  key[u][q] / val[u][q]: the lane's element q of chunk u (the
+// lane's elements are consecutive, chunks follow each other), NOT_AN_ELEMENT past
+// the layer's end.  Returns the number of copies, or RAW_TILE if they exceed the
+// slot (then nothing is written).  All 256 threads call it; `slot`: 4 words of LDS.
+__device__ __forceinline__ uint32_t stage_tile(const uint32_t (&key)[CHUNKS_PER_TILE][4],
+                                               const float (&val)[CHUNKS_PER_TILE][4], uint32_t base, uint32_t bin,
+                                               uint32_t cap, uint64_t sb, const StageArrays& A, uint32_t* slot) {
+    uint32_t c = 0;
+#pragma unroll
+    for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            c += (key[u][q] != NOT_AN_ELEMENT && (key[u][q] >> digit_shift(0)) >= bin) ? 1u : 0u;
+    uint32_t tot;
+    uint32_t o = block_exclusive_scan(c, slot, &tot);
+    if (tot > cap) return RAW_TILE;
+    if (c) {
+#pragma unroll
+        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (key[u][q] != NOT_AN_ELEMENT && (key[u][q] >> digit_shift(0)) >= bin) {
+                    A.key[sb + o] = key[u][q];
+                    A.idx[sb + o] = base + u * CHUNK + threadIdx.x * VEC + q;
+                    A.val[sb + o] = val[u][q];
+                    ++o;
+                }
+    }
+    return tot;
 }
 
 }  // namespace iwp

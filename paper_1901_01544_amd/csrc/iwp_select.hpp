@@ -6,10 +6,13 @@
 // (digits of 12 + 10 + 9 bits).  Look 1 (iwp_stream.hpp) histograms the top digit
 // of every element.  k_pick0 finds the bin b1 that holds rank k.  Look 2 (k_stage)
 // reads the leader's residual and weights once more and copies out, per tile, the
-// only elements that can still matter: those above b1 ("sure": all of them are
-// kept) and those inside b1 ("maybe": the threshold lies among them), and
-// histograms the maybes' second digit.  Every tile owns a fixed slot in the staging
-// arrays, so look 2 needs no cross-workgroup coordination at all.  Everything after
+// only elements that can still matter: those whose top digit is >= b1 (above b1 all
+// of them are kept, the threshold lies among those inside b1), and histograms the
+// second digit of those inside b1.  Every tile owns a fixed slot in the staging
+// arrays, so look 2 needs no cross-workgroup coordination at all.  With a threshold
+// hint (say, last step's thresholds) look 1 already copies out everything from a
+// bin slightly below the hinted one; if the new b1 is not below that bin the copies
+// are complete and look 2 only reads the slots, not the layer.  Everything after
 // that works on the staged copies, a few percent of the layer: k_pick1, k_refine2
 // and k_pick2 finish the threshold, k_count / k_scan / k_write place every kept
 // element at its rank in index order.  A tile whose candidates do not fit its slot
@@ -21,24 +24,29 @@
 
 namespace iwp {
 
-struct StageArrays {        // staged candidates, structure of arrays; tile t of a layer owns entries
-    uint32_t* key;          // [slot_begin + t * slot_cap, + slot_cap)
-    uint32_t* idx;          // position inside the layer
-    float* val;
-};
-
-constexpr uint32_t NOT_AN_ELEMENT = 0xFFFFFFFFu;   // key slot of a lane position past the layer's end
 constexpr uint32_t DIRECT_ATOMICS_MAX = 64;        // up to this many histogram updates per tile go straight to global memory
 
 // ---------------------------------------------------------------------------
 // Workspace initialisation with vector stores (a fill kernel rather than a memset
-// node, so the call sequence can be graph-captured): histograms and layer states
-// to zero; for the single-layer entry points also the one-row layer table.
+// node, so the call sequence can be graph-captured): histograms to zero, layer
+// states reset (with the staging bin a threshold hint implies); for the
+// single-layer entry points also the one-row layer table.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(BLOCK) void k_init(uint32_t* __restrict__ words, uint64_t n_words,
+                                                LayerState* __restrict__ state, uint32_t n_layers,
+                                                const iwp_threshold* __restrict__ hint,
                                                 DevLayer* __restrict__ single_table, DevLayer row, DevLayer sentinel) {
     const uint64_t stride = (uint64_t)gridDim.x * BLOCK;
     for (uint64_t i = (uint64_t)blockIdx.x * BLOCK + threadIdx.x; i < n_words; i += stride) words[i] = 0u;
+    for (uint64_t j = (uint64_t)blockIdx.x * BLOCK + threadIdx.x; j < n_layers; j += stride) {
+        LayerState st;
+        st.prefix = 0; st.k_rem = 0; st.n_gt = 0; st.n_eq_take = 0; st.prestaged = 0; st.pad0 = 0; st.pad1 = 0;
+        // one bin of slack below the hinted threshold bin (a bin is 1/16 octave); a hint in bin 0
+        // (threshold among zero scores) or no hint: look 1 stages nothing
+        const uint32_t hb = hint ? ((hint[j].key & 0x7fffffffu) >> digit_shift(0)) : 0u;
+        st.stage_bin = hb >= 2u ? hb - 1u : NO_STAGE_BIN;
+        state[j] = st;
+    }
     if (single_table && blockIdx.x == 0 && threadIdx.x == 0) {
         single_table[0] = row;
         single_table[1] = sentinel;
@@ -63,11 +71,12 @@ __global__ __launch_bounds__(BLOCK) void k_pick(const DevLayer* __restrict__ lay
     uint32_t bin, k_rem;
     block_pick<(1 << digit_bits(LEVEL))>(h, k_in, sh, &bin, &k_rem);
     if (threadIdx.x == 0) {
-        LayerState st;
+        LayerState st = state[j];
         st.prefix = (prefix << digit_bits(LEVEL)) | bin;
         st.k_rem = k_rem;
         st.n_eq_take = k_rem;
         st.n_gt = L.k - k_rem;
+        if (LEVEL == 0) st.prestaged = (st.stage_bin != NO_STAGE_BIN && st.stage_bin <= bin) ? 1u : 0u;
         state[j] = st;
         if (LEVEL == DIGITS - 1 && thr_out) {
             iwp_threshold th;
@@ -85,6 +94,7 @@ __global__ __launch_bounds__(BLOCK) void k_load_thresholds(const DevLayer* __res
     if (j >= n_layers || layers[j].k == 0) return;
     LayerState st;
     st.prefix = thr[j].key; st.k_rem = thr[j].n_eq_take; st.n_gt = thr[j].n_gt; st.n_eq_take = thr[j].n_eq_take;
+    st.stage_bin = NO_STAGE_BIN; st.prestaged = 0; st.pad0 = 0; st.pad1 = 0;
     state[j] = st;
 }
 
@@ -98,31 +108,58 @@ __device__ __forceinline__ void flush_hist(const uint32_t* lh, uint32_t* __restr
 }
 
 // ---------------------------------------------------------------------------
-// Look 2, one workgroup per tile of the leader's residual: copy the sure and maybe
-// elements of the tile into the tile's slot (in index order) and histogram the
-// maybes' second digit.  A tile with more candidates than its slot holds is marked
-// RAW; its second-digit counts still go into the histogram.
+// Look 2, one workgroup per tile of the leader's residual: copy the elements of the
+// tile whose top digit is >= b1 into the tile's slot (in index order) and histogram
+// the second digit of those inside b1.  A tile with more candidates than its slot
+// holds is marked RAW; its second-digit counts still go into the histogram.  If
+// look 1 already filled the slot from a bin <= b1, only the slot is read.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(BLOCK) void k_stage(ResidualPtrs R, const float* __restrict__ w,
                                                  const DevLayer* __restrict__ layers, uint32_t n_layers,
                                                  const uint32_t* __restrict__ leader, uint32_t W, float eps,
                                                  const LayerState* __restrict__ state, uint32_t* __restrict__ hist,
-                                                 TileStage* __restrict__ stage, StageArrays A) {
+                                                 uint32_t* __restrict__ stage_cnt, StageArrays A) {
     __shared__ uint32_t lh[HIST1];
-    __shared__ uint32_t slot[4];
+    __shared__ uint32_t slot[2][4];
     const uint32_t tid = threadIdx.x;
     const uint32_t t = blockIdx.x;
     const uint32_t j = find_layer<false>(layers, n_layers, t);
     const DevLayer L = layers[j];
     if (L.k == 0) return;
-    const uint32_t b1 = state[j].prefix;
+    const LayerState st = state[j];
+    const uint32_t b1 = st.prefix;
     const uint32_t lt = t - L.tile_begin;
     const uint32_t base = lt * TILE;
+    const uint64_t sb = L.slot_begin + (uint64_t)lt * L.slot_cap;
+    uint32_t* h1 = hist + (size_t)j * HIST_STRIDE + hist_base(1);
+
+    if (st.prestaged) {
+        const uint32_t cnt = stage_cnt[t];
+        if (cnt != RAW_TILE) {
+            // the slot already holds everything from a bin <= b1: histogram from it
+            const bool use_lds = cnt > 8 * DIRECT_ATOMICS_MAX;                 // uniform
+            if (use_lds) {
+                for (uint32_t b = tid; b < HIST1; b += BLOCK) lh[b] = 0u;
+                __syncthreads();
+            }
+            for (uint32_t e = tid; e < cnt; e += BLOCK) {
+                const uint32_t key = A.key[sb + e];
+                if ((key >> digit_shift(0)) == b1) {
+                    const uint32_t d1 = (key >> digit_shift(1)) & (HIST1 - 1);
+                    if (use_lds) atomicAdd(&lh[d1], 1u); else atomicAdd(&h1[d1], 1u);
+                }
+            }
+            if (use_lds) {
+                __syncthreads();
+                flush_hist<HIST1>(lh, h1);
+            }
+            return;
+        }
+    }
+
     const float* rl = R.r[leader_of(leader, j, W)] + L.offset;
     const float* wl = w + L.offset;
     const bool vec = is_aligned16(rl) && is_aligned16(wl);
-    uint32_t* h1 = hist + (size_t)j * HIST_STRIDE + hist_base(1);
-
     uint32_t key[CHUNKS_PER_TILE][4];
     float val[CHUNKS_PER_TILE][4];
     float wgt[CHUNKS_PER_TILE][4];
@@ -149,7 +186,7 @@ __global__ __launch_bounds__(BLOCK) void k_stage(ResidualPtrs R, const float* __
             }
         }
     }
-    uint32_t packed = 0;                      // low half: sure count, high half: maybe count (this lane)
+    uint32_t maybes = 0;                      // this lane's elements inside b1
 #pragma unroll
     for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
         const uint32_t i = base + u * CHUNK + tid * VEC;
@@ -157,52 +194,31 @@ __global__ __launch_bounds__(BLOCK) void k_stage(ResidualPtrs R, const float* __
         for (int q = 0; q < 4; ++q) {
             if (full || i + q < L.n) {
                 key[u][q] = score_key(val[u][q], wgt[u][q], eps);
-                const uint32_t d0 = key[u][q] >> digit_shift(0);
-                if (d0 > b1) packed += 1u;
-                else if (d0 == b1) packed += 0x10000u;
+                maybes += (key[u][q] >> digit_shift(0)) == b1 ? 1u : 0u;
             } else {
                 key[u][q] = NOT_AN_ELEMENT;
             }
         }
     }
-    uint32_t tot;
-    const uint32_t ex = block_exclusive_scan(packed, slot, &tot);
-    const uint32_t n_sure = tot & 0xFFFFu, n_maybe = tot >> 16;
-    const bool fits = n_sure + n_maybe <= L.slot_cap;
-    if (tid == 0) {
-        TileStage ts;
-        ts.n_sure = fits ? n_sure : RAW_TILE;
-        ts.n_maybe = fits ? n_maybe : 0u;
-        stage[t] = ts;
-    }
-    if (tot == 0) return;                      // uniform
+    const uint32_t cnt = stage_tile(key, val, base, b1, L.slot_cap, sb, A, slot[0]);
+    if (tid == 0) stage_cnt[t] = cnt;
+    uint32_t n_maybe;
+    (void)block_exclusive_scan(maybes, slot[1], &n_maybe);
+    if (n_maybe == 0) return;                              // uniform
     const bool use_lds = n_maybe > DIRECT_ATOMICS_MAX;     // uniform
     if (use_lds) {
         for (uint32_t b = tid; b < HIST1; b += BLOCK) lh[b] = 0u;
         __syncthreads();
     }
-    if (packed) {
-        const uint64_t sb = L.slot_begin + (uint64_t)lt * L.slot_cap;
-        uint32_t so = ex & 0xFFFFu;                        // sures first ...
-        uint32_t mo = n_sure + (ex >> 16);                 // ... then the maybes
+    if (maybes) {
 #pragma unroll
-        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
-            const uint32_t i = base + u * CHUNK + tid * VEC;
+        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                if (key[u][q] == NOT_AN_ELEMENT) continue;
-                const uint32_t d0 = key[u][q] >> digit_shift(0);
-                if (d0 > b1) {
-                    if (fits) { A.key[sb + so] = key[u][q]; A.idx[sb + so] = i + q; A.val[sb + so] = val[u][q]; }
-                    ++so;
-                } else if (d0 == b1) {
-                    if (fits) { A.key[sb + mo] = key[u][q]; A.idx[sb + mo] = i + q; A.val[sb + mo] = val[u][q]; }
-                    ++mo;
+            for (int q = 0; q < 4; ++q)
+                if (key[u][q] != NOT_AN_ELEMENT && (key[u][q] >> digit_shift(0)) == b1) {
                     const uint32_t d1 = (key[u][q] >> digit_shift(1)) & (HIST1 - 1);
                     if (use_lds) atomicAdd(&lh[d1], 1u); else atomicAdd(&h1[d1], 1u);
                 }
-            }
-        }
     }
     if (use_lds) {
         __syncthreads();
@@ -219,7 +235,7 @@ __global__ __launch_bounds__(BLOCK) void k_refine2(ResidualPtrs R, const float* 
                                                    const DevLayer* __restrict__ layers, uint32_t n_layers,
                                                    const uint32_t* __restrict__ leader, uint32_t W, float eps,
                                                    const LayerState* __restrict__ state,
-                                                   const TileStage* __restrict__ stage, StageArrays A,
+                                                   const uint32_t* __restrict__ stage_cnt, StageArrays A,
                                                    uint32_t* __restrict__ hist) {
     __shared__ uint32_t lh[HIST2];
     const uint32_t tid = threadIdx.x;
@@ -237,10 +253,10 @@ __global__ __launch_bounds__(BLOCK) void k_refine2(ResidualPtrs R, const float* 
     for (uint32_t b = tid; b < HIST2; b += BLOCK) lh[b] = 0u;
     __syncthreads();
     for (uint32_t tl = 0; tl < nt; ++tl) {
-        const TileStage ts = stage[L.tile_begin + lt0 + tl];
-        if (ts.n_sure != RAW_TILE) {
-            const uint64_t sb = L.slot_begin + (uint64_t)(lt0 + tl) * L.slot_cap + ts.n_sure;
-            for (uint32_t e = tid; e < ts.n_maybe; e += BLOCK) {
+        const uint32_t cnt = stage_cnt[L.tile_begin + lt0 + tl];
+        if (cnt != RAW_TILE) {
+            const uint64_t sb = L.slot_begin + (uint64_t)(lt0 + tl) * L.slot_cap;
+            for (uint32_t e = tid; e < cnt; e += BLOCK) {
                 const uint32_t key = A.key[sb + e];
                 if ((key >> digit_shift(1)) == prefix) atomicAdd(&lh[key & (HIST2 - 1)], 1u);
             }
@@ -273,7 +289,7 @@ __global__ __launch_bounds__(BLOCK) void k_count(ResidualPtrs R, const float* __
                                                  const DevLayer* __restrict__ layers, uint32_t n_layers,
                                                  const uint32_t* __restrict__ leader, uint32_t W, float eps,
                                                  const LayerState* __restrict__ state,
-                                                 const TileStage* __restrict__ stage, StageArrays A, bool all_raw,
+                                                 const uint32_t* __restrict__ stage_cnt, StageArrays A, bool all_raw,
                                                  uint2* __restrict__ tile_counts, uint2* __restrict__ stile_counts) {
     __shared__ uint32_t cg[GROUP], ce[GROUP];
     const uint32_t tid = threadIdx.x;
@@ -291,14 +307,11 @@ __global__ __launch_bounds__(BLOCK) void k_count(ResidualPtrs R, const float* __
     if (tid < GROUP) { cg[tid] = 0u; ce[tid] = 0u; }
     __syncthreads();
     for (uint32_t tl = 0; tl < nt; ++tl) {
-        TileStage ts;
-        ts.n_sure = RAW_TILE; ts.n_maybe = 0;
-        if (!all_raw) ts = stage[L.tile_begin + lt0 + tl];
+        const uint32_t cnt = all_raw ? RAW_TILE : stage_cnt[L.tile_begin + lt0 + tl];
         uint32_t gt = 0, eq = 0;
-        if (ts.n_sure != RAW_TILE) {
-            if (tid == 0) gt = ts.n_sure;
-            const uint64_t sb = L.slot_begin + (uint64_t)(lt0 + tl) * L.slot_cap + ts.n_sure;
-            for (uint32_t e = tid; e < ts.n_maybe; e += BLOCK) {
+        if (cnt != RAW_TILE) {
+            const uint64_t sb = L.slot_begin + (uint64_t)(lt0 + tl) * L.slot_cap;
+            for (uint32_t e = tid; e < cnt; e += BLOCK) {
                 const uint32_t key = A.key[sb + e];
                 gt += key > thr ? 1u : 0u;
                 eq += key == thr ? 1u : 0u;
@@ -368,7 +381,7 @@ __global__ __launch_bounds__(BLOCK) void k_write(ResidualPtrs R, const float* __
                                                  const DevLayer* __restrict__ layers, uint32_t n_layers,
                                                  const uint32_t* __restrict__ leader, uint32_t W, float eps,
                                                  const LayerState* __restrict__ state,
-                                                 const TileStage* __restrict__ stage, StageArrays A, bool all_raw,
+                                                 const uint32_t* __restrict__ stage_cnt, StageArrays A, bool all_raw,
                                                  const uint2* __restrict__ tile_counts,
                                                  const uint2* __restrict__ stile_counts,
                                                  uint32_t* __restrict__ tile_out,
@@ -395,17 +408,14 @@ __global__ __launch_bounds__(BLOCK) void k_write(ResidualPtrs R, const float* __
     float* vo = val_out + L.out_offset;
     float* go = FUSED ? gathered + (size_t)lead * K + L.out_offset : nullptr;
     if (tid == 0) tile_out[t] = out_base;
-    TileStage ts;
-    ts.n_sure = RAW_TILE; ts.n_maybe = 0;
-    if (!all_raw) ts = stage[t];
+    const uint32_t cnt = all_raw ? RAW_TILE : stage_cnt[t];
 
-    if (ts.n_sure != RAW_TILE) {
-        const uint32_t cnt = ts.n_sure + ts.n_maybe;
+    if (cnt != RAW_TILE) {
         if (cnt == 0) return;                                            // uniform
         const uint64_t sb = L.slot_begin + (uint64_t)lt * L.slot_cap;
         if (tid < TILE_WORDS) { eqmap[tid] = 0u; selmap[tid] = 0u; }
         __syncthreads();
-        for (uint32_t e = ts.n_sure + tid; e < cnt; e += BLOCK) {
+        for (uint32_t e = tid; e < cnt; e += BLOCK) {
             if (A.key[sb + e] == thr) {
                 const uint32_t loc = (A.idx[sb + e] - tile_first) & (TILE - 1);
                 atomicOr(&eqmap[loc >> 5], 1u << (loc & 31u));
@@ -414,12 +424,9 @@ __global__ __launch_bounds__(BLOCK) void k_write(ResidualPtrs R, const float* __
         __syncthreads();
         bitmap_prefix(eqmap, eqpre, slot[0]);
         for (uint32_t e = tid; e < cnt; e += BLOCK) {
+            const uint32_t key = A.key[sb + e];
             const uint32_t loc = (A.idx[sb + e] - tile_first) & (TILE - 1);
-            bool sel = true;                                             // a sure entry
-            if (e >= ts.n_sure) {
-                const uint32_t key = A.key[sb + e];
-                sel = key > thr || (key == thr && Et + bitmap_rank(eqmap, eqpre, loc) < quota);
-            }
+            const bool sel = key > thr || (key == thr && Et + bitmap_rank(eqmap, eqpre, loc) < quota);
             if (sel) atomicOr(&selmap[loc >> 5], 1u << (loc & 31u));
         }
         __syncthreads();

@@ -17,23 +17,64 @@
 
 namespace iwp {
 
-__device__ __forceinline__ void hist_add4(uint32_t* lh, v4f r, v4f w, float eps) {
-    atomicAdd(&lh[score_key(r.x, w.x, eps) >> digit_shift(0)], 1u);
-    atomicAdd(&lh[score_key(r.y, w.y, eps) >> digit_shift(0)], 1u);
-    atomicAdd(&lh[score_key(r.z, w.z, eps) >> digit_shift(0)], 1u);
-    atomicAdd(&lh[score_key(r.w, w.w, eps) >> digit_shift(0)], 1u);
+// What a leader's workgroup needs besides the data: its LDS histogram, and, when a
+// threshold hint makes look 1 copy candidates out, where they go.
+struct LeadCtx {
+    uint32_t* lh;           // LDS, HIST0 bins
+    uint32_t* slot;         // LDS, 2 x 4 words for the scans
+    uint32_t stage_bin;     // NO_STAGE_BIN: no staging in look 1
+    uint32_t cap;           // slot entries per tile
+    uint64_t slot_begin;    // the layer's first slot
+    uint32_t* stage_cnt;    // the layer's first tile count
+    StageArrays A;
+};
+
+// One tile of a plain worker: r <- r + g, streaming (non-temporal) accesses.
+__device__ __forceinline__ void stream_tile(const float* __restrict__ gl, float* __restrict__ rl, uint32_t n,
+                                            uint32_t base, bool vec) {
+    const uint32_t tid = threadIdx.x;
+    if (vec && base + TILE <= n) {
+        v4f rr[CHUNKS_PER_TILE], gg[CHUNKS_PER_TILE];
+#pragma unroll
+        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+            const uint32_t i = base + u * CHUNK + tid * VEC;
+            rr[u] = load_v4<true>(rl + i);
+            gg[u] = load_v4<true>(gl + i);
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+            const uint32_t i = base + u * CHUNK + tid * VEC;
+            store_v4<true>(rl + i, rr[u] + gg[u]);
+        }
+    } else {
+        // ragged tail of a layer, or a layer whose base is not 16-byte aligned
+        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+            const uint32_t i = base + u * CHUNK + tid * VEC;
+            if (i >= n) break;
+            float rv[4], gv[4];
+            load_quad(rl, i, n, vec, rv);
+            load_quad(gl, i, n, vec, gv);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) rv[q] = rv[q] + gv[q];
+            store_quad(rl, i, n, vec, rv);
+        }
+    }
 }
 
-// One tile of one worker.  ACC: add the gradient.  LEAD: score and histogram.
-// Everything streams with non-temporal accesses, the leader's residual included:
-// the second look comes after the whole first look, far too late for any cache
-// (the counters show it fetching every byte from HBM either way), and the
+// One tile of a layer's leader: accumulate (ACC), score every element, histogram
+// the top key digit, and with a staging bin copy the candidates into the tile's
+// slot.  Everything streams with non-temporal accesses, the leader's residual
+// included: the second look comes after the whole first look, far too late for any
+// cache (the counters show it fetching every byte from HBM either way), and the
 // non-temporal form measured about 10 % faster here.
-template <bool ACC, bool LEAD>
-__device__ __forceinline__ void stream_tile(const float* __restrict__ gl, float* __restrict__ rl,
-                                            const float* __restrict__ wl, uint32_t n, uint32_t base, bool vec,
-                                            float eps, uint32_t* lh) {
+template <bool ACC>
+__device__ __forceinline__ void lead_tile(const float* __restrict__ gl, float* __restrict__ rl,
+                                          const float* __restrict__ wl, uint32_t n, uint32_t lt, bool vec,
+                                          float eps, const LeadCtx& C) {
     const uint32_t tid = threadIdx.x;
+    const uint32_t base = lt * TILE;
+    uint32_t key[CHUNKS_PER_TILE][4];
+    float val[CHUNKS_PER_TILE][4];
     if (vec && base + TILE <= n) {
         v4f rr[CHUNKS_PER_TILE], gg[CHUNKS_PER_TILE], ww[CHUNKS_PER_TILE];
 #pragma unroll
@@ -41,7 +82,7 @@ __device__ __forceinline__ void stream_tile(const float* __restrict__ gl, float*
             const uint32_t i = base + u * CHUNK + tid * VEC;
             rr[u] = load_v4<true>(rl + i);
             if (ACC) gg[u] = load_v4<true>(gl + i);
-            if (LEAD) ww[u] = load_v4<true>(wl + i);
+            ww[u] = load_v4<true>(wl + i);
         }
 #pragma unroll
         for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
@@ -50,37 +91,50 @@ __device__ __forceinline__ void stream_tile(const float* __restrict__ gl, float*
                 rr[u] = rr[u] + gg[u];
                 store_v4<true>(rl + i, rr[u]);
             }
-            if (LEAD) hist_add4(lh, rr[u], ww[u], eps);
+            val[u][0] = rr[u].x; val[u][1] = rr[u].y; val[u][2] = rr[u].z; val[u][3] = rr[u].w;
+            key[u][0] = score_key(rr[u].x, ww[u].x, eps);
+            key[u][1] = score_key(rr[u].y, ww[u].y, eps);
+            key[u][2] = score_key(rr[u].z, ww[u].z, eps);
+            key[u][3] = score_key(rr[u].w, ww[u].w, eps);
         }
     } else {
         // ragged tail of a layer, or a layer whose base is not 16-byte aligned
+#pragma unroll
         for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
             const uint32_t i = base + u * CHUNK + tid * VEC;
-            if (i >= n) break;
-            float rv[4], gv[4], wv[4];
-            load_quad(rl, i, n, vec, rv);
-            if (ACC) {
-                load_quad(gl, i, n, vec, gv);
+            float gv[4], wv[4];
+            if (i < n) {
+                load_quad(rl, i, n, vec, val[u]);
+                if (ACC) {
+                    load_quad(gl, i, n, vec, gv);
 #pragma unroll
-                for (int q = 0; q < 4; ++q) rv[q] = rv[q] + gv[q];
-                store_quad(rl, i, n, vec, rv);
+                    for (int q = 0; q < 4; ++q) val[u][q] = val[u][q] + gv[q];
+                    store_quad(rl, i, n, vec, val[u]);
+                }
+                load_quad(wl, i, n, vec, wv, 1.0f);
             }
-            if (LEAD) {
-                load_quad(wl, i, n, vec, wv);
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    if (i + q < n) atomicAdd(&lh[score_key(rv[q], wv[q], eps) >> digit_shift(0)], 1u);
-            }
+            for (int q = 0; q < 4; ++q) key[u][q] = (i + q < n) ? score_key(val[u][q], wv[q], eps) : NOT_AN_ELEMENT;
         }
+    }
+#pragma unroll
+    for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (key[u][q] != NOT_AN_ELEMENT) atomicAdd(&C.lh[key[u][q] >> digit_shift(0)], 1u);
+    if (C.stage_bin != NO_STAGE_BIN) {                      // uniform
+        const uint32_t cnt = stage_tile(key, val, base, C.stage_bin, C.cap, C.slot_begin + (uint64_t)lt * C.cap, C.A,
+                                        C.slot + (lt & 1u) * 4u);
+        if (tid == 0) C.stage_cnt[lt] = cnt;
     }
 }
 
 // The leader's share of one group (up to LGROUP tiles of the same layer):
 // one LDS histogram of the top digit for the whole group, flushed once.
 __device__ __forceinline__ void leader_group(const float* gp, float* rp, const float* __restrict__ w, const DevLayer& L,
-                                             uint32_t first_tile /*in layer*/, float eps, uint32_t* lh,
+                                             uint32_t first_tile /*in layer*/, float eps, LeadCtx& C,
                                              uint32_t* __restrict__ ghist) {
-    for (uint32_t b = threadIdx.x; b < HIST0; b += BLOCK) lh[b] = 0u;
+    for (uint32_t b = threadIdx.x; b < HIST0; b += BLOCK) C.lh[b] = 0u;
     __syncthreads();
     float* rl = rp + L.offset;
     const float* gl = gp ? gp + L.offset : nullptr;
@@ -89,14 +143,27 @@ __device__ __forceinline__ void leader_group(const float* gp, float* rp, const f
     const uint32_t ntiles = (L.n + TILE - 1) / TILE;
     const uint32_t last = min(first_tile + LGROUP, ntiles);
     for (uint32_t t = first_tile; t < last; ++t) {
-        if (gp) stream_tile<true, true>(gl, rl, wl, L.n, t * TILE, vec, eps, lh);
-        else stream_tile<false, true>(gl, rl, wl, L.n, t * TILE, vec, eps, lh);
+        if (gp) lead_tile<true>(gl, rl, wl, L.n, t, vec, eps, C);
+        else lead_tile<false>(gl, rl, wl, L.n, t, vec, eps, C);
     }
     __syncthreads();
     for (uint32_t b = threadIdx.x; b < HIST0; b += BLOCK) {
-        const uint32_t v = lh[b];
+        const uint32_t v = C.lh[b];
         if (v) atomicAdd(&ghist[b], v);
     }
+}
+
+__device__ __forceinline__ LeadCtx lead_ctx(uint32_t* lh, uint32_t* slot, const DevLayer& L, const LayerState* state,
+                                            uint32_t j, uint32_t* stage_cnt, const StageArrays& A) {
+    LeadCtx C;
+    C.lh = lh;
+    C.slot = slot;
+    C.stage_bin = state[j].stage_bin;
+    C.cap = L.slot_cap;
+    C.slot_begin = L.slot_begin;
+    C.stage_cnt = stage_cnt + L.tile_begin;
+    C.A = A;
+    return C;
 }
 
 // Every worker, every layer, one launch: W * tiles workgroups, worker-major.
@@ -106,8 +173,11 @@ __device__ __forceinline__ void leader_group(const float* gp, float* rp, const f
 __global__ __launch_bounds__(BLOCK) void k_accumulate_all(WorkerPtrs P, const float* __restrict__ w,
                                                           const DevLayer* __restrict__ layers, uint32_t n_layers,
                                                           uint32_t tiles, const uint32_t* __restrict__ leader,
-                                                          uint32_t W, float eps, uint32_t* __restrict__ hist) {
+                                                          uint32_t W, float eps, uint32_t* __restrict__ hist,
+                                                          const LayerState* __restrict__ state,
+                                                          uint32_t* __restrict__ stage_cnt, StageArrays A) {
     __shared__ uint32_t lh[HIST0];
+    __shared__ uint32_t slot[8];
     const uint32_t p = blockIdx.x / tiles;
     const uint32_t t = blockIdx.x - p * tiles;
     const uint32_t j = find_layer<false>(layers, n_layers, t);
@@ -117,21 +187,25 @@ __global__ __launch_bounds__(BLOCK) void k_accumulate_all(WorkerPtrs P, const fl
     float* rp = P.r[p];
     if (L.k > 0 && leader_of(leader, j, W) == p) {
         if (lt % LGROUP) return;
-        leader_group(gp, rp, w, L, lt, eps, lh, hist + (size_t)j * HIST_STRIDE);
+        LeadCtx C = lead_ctx(lh, slot, L, state, j, stage_cnt, A);
+        leader_group(gp, rp, w, L, lt, eps, C, hist + (size_t)j * HIST_STRIDE);
         return;
     }
     if (!gp) return;
     float* rl = rp + L.offset;
     const float* gl = gp + L.offset;
-    stream_tile<true, false>(gl, rl, nullptr, L.n, lt * TILE, is_aligned16(rl) && is_aligned16(gl), eps, lh);
+    stream_tile(gl, rl, L.n, lt * TILE, is_aligned16(rl) && is_aligned16(gl));
 }
 
 // Leaders only: one workgroup per group of LGROUP tiles of every layer with k > 0.
 __global__ __launch_bounds__(BLOCK) void k_leader_pass(WorkerPtrs P, const float* __restrict__ w,
                                                        const DevLayer* __restrict__ layers, uint32_t n_layers,
                                                        const uint32_t* __restrict__ leader, uint32_t W, float eps,
-                                                       uint32_t* __restrict__ hist) {
+                                                       uint32_t* __restrict__ hist,
+                                                       const LayerState* __restrict__ state,
+                                                       uint32_t* __restrict__ stage_cnt, StageArrays A) {
     __shared__ uint32_t lh[HIST0];
+    __shared__ uint32_t slot[8];
     constexpr uint32_t SUB = GROUP / LGROUP;                 // workgroups per super-tile
     const uint32_t s = blockIdx.x / SUB;
     const uint32_t j = find_layer<true>(layers, n_layers, s);
@@ -140,7 +214,8 @@ __global__ __launch_bounds__(BLOCK) void k_leader_pass(WorkerPtrs P, const float
     const uint32_t first = (s - L.stile_begin) * GROUP + (blockIdx.x % SUB) * LGROUP;
     if (first * TILE >= L.n) return;
     const uint32_t p = leader_of(leader, j, W);
-    leader_group(P.g[p], P.r[p], w, L, first, eps, lh, hist + (size_t)j * HIST_STRIDE);
+    LeadCtx C = lead_ctx(lh, slot, L, state, j, stage_cnt, A);
+    leader_group(P.g[p], P.r[p], w, L, first, eps, C, hist + (size_t)j * HIST_STRIDE);
 }
 
 // The other workers, after the leader's pairs are known: accumulate, and where the
@@ -187,7 +262,7 @@ __global__ __launch_bounds__(BLOCK) void k_follow_gather(WorkerPtrs P, const Dev
     const float* gl = gp + L.offset;
     const bool vec = is_aligned16(rl) && is_aligned16(gl);
     if (cnt == 0) {
-        stream_tile<true, false>(gl, rl, nullptr, L.n, base, vec, 0.0f, nullptr);
+        stream_tile(gl, rl, L.n, base, vec);
         return;
     }
     if (tid < TILE_WORDS) map[tid] = 0u;

@@ -58,8 +58,8 @@ def load() -> C.CDLL:
     L.iwp_plan_workspace_bytes.restype = C.c_size_t
     L.iwp_plan_step_workspace_bytes.argtypes = [_vp, C.c_uint32]
     L.iwp_plan_step_workspace_bytes.restype = C.c_size_t
-    L.iwp_step_segmented.argtypes = [_vp, _vp, C.POINTER(_vp), C.POINTER(_vp), C.c_uint32, _vp, C.c_float, C.c_float,
-                                     _vp, _vp, _vp, _vp, _vp, C.c_size_t, _vp]
+    L.iwp_step_segmented.argtypes = [_vp, _vp, C.POINTER(_vp), C.POINTER(_vp), C.c_uint32, _vp, _vp, C.c_float,
+                                     C.c_float, _vp, _vp, _vp, _vp, _vp, C.c_size_t, _vp]
     L.iwp_step_segmented.restype = C.c_int
     L.iwp_plan_total_pairs.argtypes = [_vp]
     L.iwp_plan_total_pairs.restype = C.c_uint64
@@ -197,10 +197,11 @@ def compress_segmented(plan: Plan, w, g: Sequence, r: Sequence, leader, eps: flo
 
 
 def step_segmented(plan: Plan, w, g: Sequence, r: Sequence, leader, eps: float, scale: float, idx_out, val_out,
-                   sum_out, thr_out, workspace, stream=None):
+                   sum_out, thr_out, workspace, stream=None, thr_hint=None):
     assert len(g) == len(r)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(load().iwp_step_segmented(plan._h, _ptr(w), _ptr_table(g), _ptr_table(r), len(r), _ptr(leader), eps, scale,
+    _check(load().iwp_step_segmented(plan._h, _ptr(w), _ptr_table(g), _ptr_table(r), len(r), _ptr(leader),
+                                     _ptr(thr_hint), eps, scale,
                                      _ptr(idx_out), _ptr(val_out), _ptr(sum_out), _ptr(thr_out), _ptr(workspace),
                                      ws_bytes, _stream(stream)), "iwp_step_segmented")
 

@@ -16,7 +16,7 @@ class GpuSet:
     three separate calls (compress_segmented, gather_sum_at_indices,
     apply_sparse_update) or, with fused=True, the whole-step entry point."""
 
-    def __init__(self, iwp, ps, w_np, grads_np, r_np=None, W=None, fused=False):
+    def __init__(self, iwp, ps, w_np, grads_np, r_np=None, W=None, fused=False, hint="none"):
         import torch
         self.torch = torch
         self.iwp = iwp
@@ -32,6 +32,10 @@ class GpuSet:
         self.plan = iwp.Plan(ps.rows())
         assert self.plan.total_pairs == ps.K
         self.fused = fused
+        # hint: "none" | "previous" (last step's thresholds, the intended use) | "garbage" | "high" | "low"
+        self.hint_mode = hint
+        self.hint = torch.zeros(len(ps.layers) * 3, dtype=torch.int32, device=dev)
+        self.steps_done = 0
         ws_bytes = self.plan.step_workspace_bytes(self.W) if fused else self.plan.workspace_bytes
         self.ws = torch.empty(max(1, ws_bytes), dtype=torch.uint8, device=dev)
         K = max(1, ps.K)
@@ -51,9 +55,24 @@ class GpuSet:
         sc = float(ps.scale if scale is None else scale)
         if self.fused:
             self.sum.fill_(float("nan"))
+            hint = None
+            if self.hint_mode == "previous" and self.steps_done > 0:
+                self.hint.copy_(self.thr)
+                hint = self.hint
+            elif self.hint_mode == "garbage":
+                self.hint.copy_(self.torch.randint(-2 ** 31, 2 ** 31 - 1, (self.hint.numel(),), dtype=self.torch.int64,
+                                                   device=self.hint.device).to(self.torch.int32))
+                hint = self.hint
+            elif self.hint_mode in ("high", "low") and self.steps_done > 0:
+                # last step's keys moved up / down by a few top-digit bins
+                key = self.thr.view(-1, 3)[:, 0].to(self.torch.int64)
+                key = key + (5 << 19) if self.hint_mode == "high" else self.torch.clamp(key - (5 << 19), min=0)
+                self.hint.view(-1, 3)[:, 0] = key.clamp(max=2 ** 31 - 1).to(self.torch.int32)
+                hint = self.hint
             iwp.step_segmented(self.plan, self.w, g, self.r, self.leader, float(ps.eps), sc, self.idx, self.val,
-                               self.sum, self.thr, self.ws)
+                               self.sum, self.thr, self.ws, thr_hint=hint)
             self.torch.cuda.synchronize()
+            self.steps_done += 1
             return
         iwp.compress_segmented(self.plan, self.w, g, self.r, self.leader, float(ps.eps), self.idx, self.val,
                                self.thr, self.ws)

@@ -225,7 +225,7 @@ def _run_steps(iwp, ps, steps, pool, W=None, r0=None, g_ids_fn=None, leader_fn=N
     w = wl.gen_weights(ps)
     sets = [wl.gen_gradient(ps, s) for s in range(pool)]
     r_ref = [np.zeros(ps.flat, np.float32) for _ in range(W)] if r0 is None else [x.copy() for x in r0]
-    gs = GpuSet(iwp, ps, w, sets, r_np=r0, W=W, fused=fused)
+    gs = GpuSet(iwp, ps, w, sets, r_np=r0, W=W, fused=bool(fused), hint=fused or "none")
     w_ref = w.copy()
     for t in range(steps):
         lead = wl.leaders(ps, t, n_candidates=W) if leader_fn is None else leader_fn(t)
@@ -240,7 +240,10 @@ def _run_steps(iwp, ps, steps, pool, W=None, r0=None, g_ids_fn=None, leader_fn=N
     return gs
 
 
-ROUTES = pytest.mark.parametrize("fused", [False, True], ids=["three_calls", "whole_step"])
+# fused: False = the three separate calls; otherwise the whole-step entry point with the named kind of
+# threshold hint ("previous" = last step's records, the intended use; the others must not change a bit either)
+ROUTES = pytest.mark.parametrize("fused", [False, "none", "previous"], ids=["three_calls", "whole_step", "whole_step_hinted"])
+HINTS = pytest.mark.parametrize("fused", ["garbage", "high", "low"], ids=["hint_garbage", "hint_high", "hint_low"])
 
 
 @ROUTES
@@ -271,7 +274,7 @@ def test_leader_table_out_of_range_reads_as_worker_zero(gpu_lib, fused):
     bad = np.array([7, 0xFFFFFFFF], np.uint32)
     w = wl.gen_weights(ps)
     sets = [wl.gen_gradient(ps, s) for s in range(2)]
-    gs = GpuSet(gpu_lib, ps, w, sets, fused=fused)
+    gs = GpuSet(gpu_lib, ps, w, sets, fused=bool(fused), hint=fused or "none")
     gs.step([0, 1], bad)
     r_ref = [np.zeros(ps.flat, np.float32) for _ in range(2)]
     ref = oracle.step(w, sets, r_ref, ps.rows(), np.zeros(2, np.uint32), float(ps.eps), float(ps.scale))
@@ -338,15 +341,34 @@ def test_staging_overflow_takes_the_raw_route(gpu_lib, fused):
     w[L0.offset:L0.offset + n] = 1.0
     w[L1.offset:L1.offset + n] = 1.0
     sets = [g0, g1]
-    gs = GpuSet(gpu_lib, ps, w, sets, fused=fused)
+    gs = GpuSet(gpu_lib, ps, w, sets, fused=bool(fused), hint=fused or "none")
     w_ref = w.copy()
     r_ref = [np.zeros(ps.flat, np.float32) for _ in range(2)]
-    for t in range(2):
+    for t in range(3):
         lead = wl.leaders(ps, t)
         ref = oracle.step(w_ref, sets, r_ref, ps.rows(), lead, 0.0, float(ps.scale))
         ps.eps = 0.0
         gs.step([0, 1], lead)
         assert_step_equal(gs.download(), w_ref, r_ref, *ref, ps.layers, tag="raw route step %d" % t)
+
+
+@HINTS
+def test_wrong_hints_change_nothing(gpu_lib, fused):
+    """A threshold hint is only a shortcut: random records, records far above and far
+    below the true thresholds all give the oracle's bytes (config 1 and a ragged set)."""
+    ps = wl.make_config(1)
+    _run_steps(gpu_lib, ps, 5, pool=4, tag="cfg1 " + fused, fused=fused)
+    sizes = [(300, 5), (0, 0), (1, 1), (TILE, 256), (64, 64), (1000, 0), (TILE + 1, 1), (777, 13),
+             (2 * TILE - 1, 2 * TILE - 1), (5, 0), (40000, 625), (STILE + 3, 600), (3 * STILE, 3 * STILE - 1)]
+    ps = wl.custom_set(sizes, W=3, seed=97, align=1, start=1, zero_frac=0.01)
+    _run_steps(gpu_lib, ps, 4, pool=3, tag="edge " + fused, fused=fused)
+
+
+@HINTS
+@pytest.mark.timeout(600)
+def test_wrong_hints_config3(gpu_lib, fused):
+    ps = wl.make_config(3)
+    _run_steps(gpu_lib, ps, 3, pool=4, tag="cfg3 " + fused, fused=fused)
 
 
 def test_determinism_run_to_run(gpu_lib):
