@@ -98,15 +98,9 @@ def main():
     t0 = time.time()
     if flat_cfg:
         # 1e9-element buffers are drawn on the device (seeded); same laws as the host generator
-        gen = torch.Generator(device=dev)
-        gen.manual_seed(ps.seed)
-        w = torch.empty(ps.flat, device=dev).normal_(0.0, ps.weight_std, generator=gen)
-
-        def laplace():
-            u = torch.empty(ps.flat, device=dev).uniform_(-0.5, 0.5, generator=gen)
-            return -ps.grad_b * torch.sign(u) * torch.log1p(-2.0 * u.abs())
-        grads = [laplace() for _ in range(pool)]
-        r = [torch.zeros(ps.flat, device=dev)] + [laplace() for _ in range(8)]
+        w = wl.gen_weights_device(ps, dev)
+        grads = [wl.gen_laplace_device(ps, 1 + s, dev) for s in range(pool)]
+        r = [torch.zeros(ps.flat, device=dev)] + [wl.gen_laplace_device(ps, 100 + p, dev) for p in range(8)]
         w_np = grads_np = None
     else:
         w_np = wl.gen_weights(ps)

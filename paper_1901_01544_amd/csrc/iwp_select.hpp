@@ -293,6 +293,7 @@ __global__ __launch_bounds__(BLOCK) void k_count(ResidualPtrs R, const float* __
                                                  uint2* __restrict__ tile_counts, uint2* __restrict__ stile_counts) {
     __shared__ uint32_t cg[GROUP], ce[GROUP];
     const uint32_t tid = threadIdx.x;
+    const uint32_t lane = tid & (WAVE - 1), wave = tid >> 6;
     const uint32_t s = blockIdx.x;
     const uint32_t j = find_layer<true>(layers, n_layers, s);
     const DevLayer L = layers[j];
@@ -303,37 +304,32 @@ __global__ __launch_bounds__(BLOCK) void k_count(ResidualPtrs R, const float* __
     const uint32_t nt = min(GROUP, ntiles - lt0);
     const float* rl = R.r[leader_of(leader, j, W)] + L.offset;
     const float* wl = w + L.offset;
-    const bool vec = is_aligned16(rl) && is_aligned16(wl);
-    if (tid < GROUP) { cg[tid] = 0u; ce[tid] = 0u; }
-    __syncthreads();
-    for (uint32_t tl = 0; tl < nt; ++tl) {
+    // each wavefront takes tiles of its own (no workgroup-wide step until the end)
+    for (uint32_t tl = wave; tl < nt; tl += BLOCK / WAVE) {
         const uint32_t cnt = all_raw ? RAW_TILE : stage_cnt[L.tile_begin + lt0 + tl];
         uint32_t gt = 0, eq = 0;
         if (cnt != RAW_TILE) {
             const uint64_t sb = L.slot_begin + (uint64_t)(lt0 + tl) * L.slot_cap;
-            for (uint32_t e = tid; e < cnt; e += BLOCK) {
+            for (uint32_t e = lane; e < cnt; e += WAVE) {
                 const uint32_t key = A.key[sb + e];
                 gt += key > thr ? 1u : 0u;
                 eq += key == thr ? 1u : 0u;
             }
         } else {
-            for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
-                const uint32_t i = (lt0 + tl) * TILE + u * CHUNK + tid * VEC;
-                if (i >= L.n) break;
-                float rv[4], wv[4];
-                load_quad(rl, i, L.n, vec, rv);
-                load_quad(wl, i, L.n, vec, wv, 1.0f);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const uint32_t key = score_key(rv[q], wv[q], eps);
-                    const bool valid = i + q < L.n;
-                    gt += (valid && key > thr) ? 1u : 0u;
-                    eq += (valid && key == thr) ? 1u : 0u;
-                }
+            const uint32_t first = (lt0 + tl) * TILE;
+            const uint32_t end = min(L.n, first + TILE);
+            for (uint32_t i = first + lane; i < end; i += WAVE) {
+                const uint32_t key = score_key(rl[i], wl[i], eps);
+                gt += key > thr ? 1u : 0u;
+                eq += key == thr ? 1u : 0u;
             }
         }
-        if (gt) atomicAdd(&cg[tl], gt);
-        if (eq) atomicAdd(&ce[tl], eq);
+#pragma unroll
+        for (int d = WAVE / 2; d > 0; d >>= 1) {
+            gt += __shfl_xor(gt, d, WAVE);
+            eq += __shfl_xor(eq, d, WAVE);
+        }
+        if (lane == 0) { cg[tl] = gt; ce[tl] = eq; }
     }
     __syncthreads();
     if (tid == 0) {

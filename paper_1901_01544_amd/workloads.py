@@ -327,3 +327,33 @@ def leaders(ps: ParamSet, step: int, n_candidates: Optional[int] = None) -> np.n
     W = ps.W if n_candidates is None else n_candidates
     L = len(ps.layers)
     return np.array([_splitmix64(ps.seed ^ (step * L + j)) % W for j in range(L)], np.uint32)
+
+
+# --------------------------------------------------------------------------
+# device-side generation for the 1e9-element config (host generation of eleven
+# 4 GB buffers would take minutes); same laws, torch's seeded generator
+# --------------------------------------------------------------------------
+
+def device_generator(ps: ParamSet, stream_id: int, device="cuda:0"):
+    """A torch generator on ``device`` seeded from (set seed, stream_id)."""
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(int(ps.seed) * 1000003 + int(stream_id))
+    return gen
+
+
+def gen_weights_device(ps: ParamSet, device="cuda:0"):
+    """Flat fp32 weights N(0, weight_std) drawn on the device (config 5)."""
+    import torch
+    assert ps.weight_std is not None
+    return torch.empty(ps.flat, device=device).normal_(0.0, ps.weight_std, generator=device_generator(ps, 0, device))
+
+
+def gen_laplace_device(ps: ParamSet, stream_id: int, device="cuda:0"):
+    """Flat fp32 Laplace(0, grad_b) buffer drawn on the device by inverse CDF:
+    stream_id 1.. = gradient sets, 100.. = peer residuals."""
+    import torch
+    u = torch.empty(ps.flat, device=device).uniform_(-0.5, 0.5, generator=device_generator(ps, stream_id, device))
+    x = torch.log1p(-2.0 * u.abs())
+    x.mul_(torch.sign(u)).mul_(-ps.grad_b)
+    return x
