@@ -167,10 +167,10 @@ int run_select(const Table& T, const Workspace& ws, const ResidualPtrs& R, const
                false, ws.tile_counts, ws.stile_counts);
     IWP_LAUNCH("k_scan", k_scan, T.n_layers, s, T.layers, ws.stile_counts);
     if (fused)
-        IWP_LAUNCH("k_write", k_write<true>, T.tiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.stage,
+        IWP_LAUNCH("k_write", k_write<true>, (T.tiles + 3) / 4, s, R, w, T.layers, T.n_layers, T.tiles, leader, W, eps, ws.state, ws.stage,
                    ws.A, false, ws.tile_counts, ws.stile_counts, ws.tile_out, idx_out, val_out, ws.gathered, T.pairs);
     else
-        IWP_LAUNCH("k_write", k_write<false>, T.tiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.stage,
+        IWP_LAUNCH("k_write", k_write<false>, (T.tiles + 3) / 4, s, R, w, T.layers, T.n_layers, T.tiles, leader, W, eps, ws.state, ws.stage,
                    ws.A, false, ws.tile_counts, ws.stile_counts, ws.tile_out, idx_out, val_out, nullptr, T.pairs);
     return IWP_OK;
 }
@@ -184,7 +184,7 @@ int run_compact_from(const Table& T, const Workspace& ws, const ResidualPtrs& R,
     IWP_LAUNCH("k_count", k_count, T.stiles, s, R, w, T.layers, T.n_layers, nullptr, 1u, eps, ws.state, ws.stage, ws.A,
                true, ws.tile_counts, ws.stile_counts);
     IWP_LAUNCH("k_scan", k_scan, T.n_layers, s, T.layers, ws.stile_counts);
-    IWP_LAUNCH("k_write", k_write<false>, T.tiles, s, R, w, T.layers, T.n_layers, nullptr, 1u, eps, ws.state, ws.stage,
+    IWP_LAUNCH("k_write", k_write<false>, (T.tiles + 3) / 4, s, R, w, T.layers, T.n_layers, T.tiles, nullptr, 1u, eps, ws.state, ws.stage,
                ws.A, true, ws.tile_counts, ws.stile_counts, ws.tile_out, idx_out, val_out, nullptr, T.pairs);
     return IWP_OK;
 }
@@ -475,8 +475,24 @@ int iwp_step_segmented(const iwp_plan* plan, float* w, const float* const* g, fl
         rc = run_select(T, ws, R, w, leader, W, eps, FULL, true, idx_out, val_out, thr_out, s);
         if (rc) return rc;
     }
-    IWP_LAUNCH("k_follow_gather", k_follow_gather, W * T.tiles, s, P, T.layers, T.n_layers, T.tiles, leader, W, idx_out,
-               ws.tile_out, ws.gathered, T.pairs);
+    WorkerList acc, stat;                       // workers with / without a gradient
+    memset(&acc, 0, sizeof acc);
+    memset(&stat, 0, sizeof stat);
+    for (uint32_t p = 0; p < W; ++p) {
+        if (g[p]) acc.id[acc.n++] = (uint8_t)p; else stat.id[stat.n++] = (uint8_t)p;
+    }
+    if (acc.n)
+        IWP_LAUNCH("k_follow_gather", k_follow_gather, acc.n * T.tiles, s, P, acc, T.layers, T.n_layers, T.tiles, leader,
+                   W, idx_out, ws.tile_out, ws.gathered, T.pairs);
+    if (stat.n && T.any_k) {
+        TimedLaunch tl_("k_gather_static", s);
+        k_gather_static<<<dim3((uint32_t)((T.pairs + BLOCK - 1) / BLOCK), stat.n), BLOCK, 0, s>>>(
+            R, stat, T.layers, T.n_layers, leader, W, idx_out, ws.gathered, T.pairs);
+    }
+    {
+        hipError_t e_ = hipGetLastError();
+        if (e_ != hipSuccess) return hip_fail(e_, "k_gather_static");
+    }
     if (T.any_k)
         IWP_LAUNCH("k_reduce_update", k_reduce_update, (uint32_t)((T.pairs + BLOCK - 1) / BLOCK), s, ws.gathered, W,
                    T.pairs, idx_out, w, scale, sum_out);

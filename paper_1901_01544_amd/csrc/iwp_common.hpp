@@ -77,6 +77,11 @@ struct ResidualPtrs {
     float* r[IWP_MAX_WORKERS];
 };
 
+struct WorkerList {        // a subset of the workers, by index
+    uint32_t n;
+    uint8_t id[IWP_MAX_WORKERS];
+};
+
 // Importance of one element as an order-preserving integer (Alg. 1 mask line:
 // |grad / w|, with eps added to |w| in fp32 before the correctly rounded divide).
 __device__ __forceinline__ uint32_t score_key(float r, float w, float eps) {
@@ -206,6 +211,23 @@ __device__ __forceinline__ void block_pick(const uint32_t* hist, uint32_t k_rem,
     __syncthreads();
     *bin_out = sh[BLOCK];
     *k_rem_out = sh[BLOCK + 1];
+}
+
+// Orders LDS traffic inside one wavefront (the lanes run in lockstep; this makes
+// earlier LDS writes and atomics of the wave visible to its later reads).
+__device__ __forceinline__ void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Wavefront-private version of bitmap_prefix: each lane owns two of the 128 words.
+__device__ __forceinline__ void wave_bitmap_prefix(const uint32_t* map, uint32_t* prefix) {
+    const uint32_t lane = threadIdx.x & (WAVE - 1);
+    const uint32_t c0 = __popc(map[2 * lane]), c1 = __popc(map[2 * lane + 1]);
+    const uint32_t ex = wave_inclusive_scan(c0 + c1) - (c0 + c1);
+    prefix[2 * lane] = ex;
+    prefix[2 * lane + 1] = ex + c0;
+    wave_sync();
 }
 
 // One bit per element of a tile.  prefix[w] = number of set bits in words < w.

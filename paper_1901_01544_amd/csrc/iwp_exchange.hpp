@@ -29,6 +29,29 @@ __global__ __launch_bounds__(BLOCK) void k_apply_update(float* __restrict__ w, c
     for (uint32_t p = 0; p < W; ++p) R.r[p][i] = 0.0f;
 }
 
+// Whole-step route, workers that do not accumulate (no gradient: their residual is
+// static): nothing streams, so their values at the sent positions are fetched and
+// cleared pair by pair.  Grid: (pairs / 256, stat.n).  The leader of a pair's layer
+// is skipped (its row and its clearing are the pair writer's).
+__global__ __launch_bounds__(BLOCK) void k_gather_static(ResidualPtrs R, WorkerList stat,
+                                                         const DevLayer* __restrict__ layers, uint32_t n_layers,
+                                                         const uint32_t* __restrict__ leader, uint32_t W,
+                                                         const uint32_t* __restrict__ idx, float* __restrict__ gathered,
+                                                         uint64_t K) {
+    const uint64_t j = (uint64_t)blockIdx.x * BLOCK + threadIdx.x;
+    if (j >= K) return;
+    const uint32_t p = stat.id[blockIdx.y];
+    uint32_t lo = 0, hi = n_layers;              // layer of pair j: last row with out_offset <= j
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (layers[mid].out_offset <= j) lo = mid; else hi = mid;
+    }
+    if (leader_of(leader, lo, W) == p) return;
+    const uint32_t i = idx[j];
+    gathered[(size_t)p * K + j] = R.r[p][i];
+    R.r[p][i] = 0.0f;
+}
+
 // Whole-step route: the residuals were already gathered into `gathered`
 // (row p = worker p's values at the K pairs, leader's row included) and cleared
 // while they streamed by, so what is left is the ordered sum over the workers and

@@ -344,20 +344,34 @@ __global__ __launch_bounds__(BLOCK) void k_count(ResidualPtrs R, const float* __
 }
 
 // Part 2: exclusive prefix of the super-tile totals inside each layer, in order.
+// One workgroup per layer, eight consecutive super-tiles per lane and round.
 __global__ __launch_bounds__(BLOCK) void k_scan(const DevLayer* __restrict__ layers, uint2* __restrict__ stile_counts) {
+    constexpr uint32_t PER = 8;
     __shared__ uint32_t slot_g[4], slot_e[4];
     const uint32_t j = blockIdx.x;
     if (layers[j].k == 0) return;
     const uint32_t sb = layers[j].stile_begin;
     const uint32_t se = sb + (layers[j].n + STILE - 1) / STILE;
     uint32_t G = 0, E = 0;
-    for (uint32_t b = sb; b < se; b += BLOCK) {
-        const uint32_t s = b + threadIdx.x;
-        const uint2 v = (s < se) ? stile_counts[s] : make_uint2(0u, 0u);
+    for (uint32_t b = sb; b < se; b += BLOCK * PER) {
+        const uint32_t s0 = b + threadIdx.x * PER;
+        uint2 v[PER];
+        uint32_t lg = 0, le = 0;
+#pragma unroll
+        for (uint32_t q = 0; q < PER; ++q) {
+            v[q] = (s0 + q < se) ? stile_counts[s0 + q] : make_uint2(0u, 0u);
+            lg += v[q].x;
+            le += v[q].y;
+        }
         uint32_t tot_g, tot_e;
-        const uint32_t ex_g = block_exclusive_scan(v.x, slot_g, &tot_g);
-        const uint32_t ex_e = block_exclusive_scan(v.y, slot_e, &tot_e);
-        if (s < se) stile_counts[s] = make_uint2(G + ex_g, E + ex_e);
+        uint32_t pg = G + block_exclusive_scan(lg, slot_g, &tot_g);
+        uint32_t pe = E + block_exclusive_scan(le, slot_e, &tot_e);
+#pragma unroll
+        for (uint32_t q = 0; q < PER; ++q) {
+            if (s0 + q < se) stile_counts[s0 + q] = make_uint2(pg, pe);
+            pg += v[q].x;
+            pe += v[q].y;
+        }
         G += tot_g;
         E += tot_e;
         __syncthreads();
@@ -371,10 +385,11 @@ __global__ __launch_bounds__(BLOCK) void k_scan(const DevLayer* __restrict__ lay
 // residual itself).  tile_out[t] receives the position of the tile's first pair.
 // FUSED (whole-step entry point): the value also goes into the leader's row of the
 // gather matrix and the leader's residual is cleared at the sent position.
-// One workgroup per tile.
+// One wavefront per tile (four tiles per workgroup, nothing workgroup-wide).
 template <bool FUSED>
 __global__ __launch_bounds__(BLOCK) void k_write(ResidualPtrs R, const float* __restrict__ w,
                                                  const DevLayer* __restrict__ layers, uint32_t n_layers,
+                                                 uint32_t tiles_total,
                                                  const uint32_t* __restrict__ leader, uint32_t W, float eps,
                                                  const LayerState* __restrict__ state,
                                                  const uint32_t* __restrict__ stage_cnt, StageArrays A, bool all_raw,
@@ -383,10 +398,10 @@ __global__ __launch_bounds__(BLOCK) void k_write(ResidualPtrs R, const float* __
                                                  uint32_t* __restrict__ tile_out,
                                                  uint32_t* __restrict__ idx_out, float* __restrict__ val_out,
                                                  float* __restrict__ gathered, uint64_t K) {
-    __shared__ uint32_t eqmap[TILE_WORDS], eqpre[TILE_WORDS], selmap[TILE_WORDS], selpre[TILE_WORDS];
-    __shared__ uint32_t slot[2][4];
-    const uint32_t tid = threadIdx.x;
-    const uint32_t t = blockIdx.x;
+    __shared__ uint32_t maps[BLOCK / WAVE][4][TILE_WORDS];
+    const uint32_t lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x >> 6;
+    const uint32_t t = blockIdx.x * (BLOCK / WAVE) + wave;
+    if (t >= tiles_total) return;
     const uint32_t j = find_layer<false>(layers, n_layers, t);
     const DevLayer L = layers[j];
     if (L.k == 0) return;
@@ -403,31 +418,36 @@ __global__ __launch_bounds__(BLOCK) void k_write(ResidualPtrs R, const float* __
     uint32_t* io = idx_out + L.out_offset;
     float* vo = val_out + L.out_offset;
     float* go = FUSED ? gathered + (size_t)lead * K + L.out_offset : nullptr;
-    if (tid == 0) tile_out[t] = out_base;
+    if (lane == 0) tile_out[t] = out_base;
     const uint32_t cnt = all_raw ? RAW_TILE : stage_cnt[t];
 
     if (cnt != RAW_TILE) {
-        if (cnt == 0) return;                                            // uniform
+        if (cnt == 0) return;
+        uint32_t* eqmap = maps[wave][0];
+        uint32_t* eqpre = maps[wave][1];
+        uint32_t* selmap = maps[wave][2];
+        uint32_t* selpre = maps[wave][3];
         const uint64_t sb = L.slot_begin + (uint64_t)lt * L.slot_cap;
-        if (tid < TILE_WORDS) { eqmap[tid] = 0u; selmap[tid] = 0u; }
-        __syncthreads();
-        for (uint32_t e = tid; e < cnt; e += BLOCK) {
+        eqmap[2 * lane] = 0u; eqmap[2 * lane + 1] = 0u;
+        selmap[2 * lane] = 0u; selmap[2 * lane + 1] = 0u;
+        wave_sync();
+        for (uint32_t e = lane; e < cnt; e += WAVE) {
             if (A.key[sb + e] == thr) {
                 const uint32_t loc = (A.idx[sb + e] - tile_first) & (TILE - 1);
                 atomicOr(&eqmap[loc >> 5], 1u << (loc & 31u));
             }
         }
-        __syncthreads();
-        bitmap_prefix(eqmap, eqpre, slot[0]);
-        for (uint32_t e = tid; e < cnt; e += BLOCK) {
+        wave_sync();
+        wave_bitmap_prefix(eqmap, eqpre);
+        for (uint32_t e = lane; e < cnt; e += WAVE) {
             const uint32_t key = A.key[sb + e];
             const uint32_t loc = (A.idx[sb + e] - tile_first) & (TILE - 1);
             const bool sel = key > thr || (key == thr && Et + bitmap_rank(eqmap, eqpre, loc) < quota);
             if (sel) atomicOr(&selmap[loc >> 5], 1u << (loc & 31u));
         }
-        __syncthreads();
-        bitmap_prefix(selmap, selpre, slot[1]);
-        for (uint32_t e = tid; e < cnt; e += BLOCK) {
+        wave_sync();
+        wave_bitmap_prefix(selmap, selpre);
+        for (uint32_t e = lane; e < cnt; e += WAVE) {
             const uint32_t li = A.idx[sb + e];
             const uint32_t loc = (li - tile_first) & (TILE - 1);
             if ((selmap[loc >> 5] >> (loc & 31u)) & 1u) {
@@ -443,14 +463,14 @@ __global__ __launch_bounds__(BLOCK) void k_write(ResidualPtrs R, const float* __
         return;
     }
 
-    // RAW tile: every element is scored again, chunk by chunk
+    // RAW tile: every element is scored again, 256 at a time
     const float* wl = w + L.offset;
     const bool vec = is_aligned16(rl) && is_aligned16(wl);
     uint32_t G = Gt, E = Et;
-    for (uint32_t c = 0; c < CHUNKS_PER_TILE; ++c) {
-        const uint32_t cbase = tile_first + c * CHUNK;
-        if (cbase >= L.n) break;                                            // uniform
-        const uint32_t i = cbase + tid * VEC;
+    for (uint32_t c = 0; c < TILE / (WAVE * VEC); ++c) {
+        const uint32_t cbase = tile_first + c * (WAVE * VEC);
+        if (cbase >= L.n) break;
+        const uint32_t i = cbase + lane * VEC;
         float rv[4] = {0.f, 0.f, 0.f, 0.f}, wv[4] = {1.f, 1.f, 1.f, 1.f};
         if (i < L.n) {
             load_quad(rl, i, L.n, vec, rv);
@@ -465,8 +485,9 @@ __global__ __launch_bounds__(BLOCK) void k_write(ResidualPtrs R, const float* __
             packed += (valid && key[q] > thr) ? 1u : 0u;
             packed += (valid && key[q] == thr) ? 0x10000u : 0u;
         }
-        uint32_t tot;
-        const uint32_t ex = block_exclusive_scan(packed, slot[c & 1], &tot);
+        const uint32_t inc = wave_inclusive_scan(packed);
+        const uint32_t tot = __shfl(inc, WAVE - 1, WAVE);
+        const uint32_t ex = inc - packed;
         uint32_t gpre = G + (ex & 0xffffu);
         uint32_t epre = E + (ex >> 16);
         if (packed) {

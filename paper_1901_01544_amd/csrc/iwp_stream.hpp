@@ -222,9 +222,9 @@ __global__ __launch_bounds__(BLOCK) void k_leader_pass(WorkerPtrs P, const float
 // tile holds sent positions, copy the accumulated value into the worker's row of
 // the gather matrix and leave +0 behind.  tile_out[t] = position (inside the
 // layer's pairs) of the first pair that falls into tile t; the pairs are ascending,
-// so a tile's pairs are contiguous.  A worker without a gradient pointer is only
-// gathered and cleared at the sent positions.
-__global__ __launch_bounds__(BLOCK) void k_follow_gather(WorkerPtrs P, const DevLayer* __restrict__ layers,
+// so a tile's pairs are contiguous.  `acc`: the workers that accumulate (have a
+// gradient); the grid is acc.n * tiles.
+__global__ __launch_bounds__(BLOCK) void k_follow_gather(WorkerPtrs P, WorkerList acc, const DevLayer* __restrict__ layers,
                                                          uint32_t n_layers, uint32_t tiles,
                                                          const uint32_t* __restrict__ leader, uint32_t W,
                                                          const uint32_t* __restrict__ idx,
@@ -232,8 +232,9 @@ __global__ __launch_bounds__(BLOCK) void k_follow_gather(WorkerPtrs P, const Dev
                                                          float* __restrict__ gathered, uint64_t K) {
     __shared__ uint32_t map[TILE_WORDS], pre[TILE_WORDS], slot[4];
     const uint32_t tid = threadIdx.x;
-    const uint32_t p = blockIdx.x / tiles;
-    const uint32_t t = blockIdx.x - p * tiles;
+    const uint32_t a = blockIdx.x / tiles;
+    const uint32_t t = blockIdx.x - a * tiles;
+    const uint32_t p = acc.id[a];
     const uint32_t j = find_layer<false>(layers, n_layers, t);
     const DevLayer L = layers[j];
     const bool has_sel = L.k > 0;
@@ -252,40 +253,35 @@ __global__ __launch_bounds__(BLOCK) void k_follow_gather(WorkerPtrs P, const Dev
     const uint32_t* ix = idx + L.out_offset + lo;
     float* go = gathered + (size_t)p * K + L.out_offset + lo;
     const uint32_t first = (uint32_t)L.offset + base;           // flat position of the tile's first element
-    if (!gp) {
-        for (uint32_t e = tid; e < cnt; e += BLOCK) {
-            const uint32_t loc = ix[e] - first;
-            if (loc < TILE && base + loc < L.n) { go[e] = rl[base + loc]; rl[base + loc] = 0.0f; }
-        }
-        return;
-    }
     const float* gl = gp + L.offset;
     const bool vec = is_aligned16(rl) && is_aligned16(gl);
-    if (cnt == 0) {
-        stream_tile(gl, rl, L.n, base, vec);
-        return;
-    }
-    if (tid < TILE_WORDS) map[tid] = 0u;
-    __syncthreads();
-    for (uint32_t e = tid; e < cnt; e += BLOCK) {
-        const uint32_t loc = ix[e] - first;
-        if (loc < TILE) atomicOr(&map[loc >> 5], 1u << (loc & 31u));
-    }
-    __syncthreads();
-    bitmap_prefix(map, pre, slot);
-    if (vec && base + TILE <= L.n) {
-        v4f rr[CHUNKS_PER_TILE], gg[CHUNKS_PER_TILE];
+    const bool full = vec && base + TILE <= L.n;
+    // the tile's loads go out first; the bitmap of sent positions is built while they are in flight
+    v4f rr[CHUNKS_PER_TILE], gg[CHUNKS_PER_TILE];
+    if (full) {
 #pragma unroll
         for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
             const uint32_t i = base + u * CHUNK + tid * VEC;
             rr[u] = load_v4<true>(rl + i);
             gg[u] = load_v4<true>(gl + i);
         }
+    }
+    if (cnt) {                                                   // uniform
+        if (tid < TILE_WORDS) map[tid] = 0u;
+        __syncthreads();
+        for (uint32_t e = tid; e < cnt; e += BLOCK) {
+            const uint32_t loc = ix[e] - first;
+            if (loc < TILE) atomicOr(&map[loc >> 5], 1u << (loc & 31u));
+        }
+        __syncthreads();
+        bitmap_prefix(map, pre, slot);
+    }
+    if (full) {
 #pragma unroll
         for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
             const uint32_t loc = u * CHUNK + tid * VEC;
             rr[u] = rr[u] + gg[u];
-            const uint32_t nib = (map[loc >> 5] >> (loc & 31u)) & 0xFu;
+            const uint32_t nib = cnt ? (map[loc >> 5] >> (loc & 31u)) & 0xFu : 0u;
             if (nib) {
                 uint32_t rank = bitmap_rank(map, pre, loc);
                 if (nib & 1u) { go[rank++] = rr[u].x; rr[u].x = 0.0f; }
@@ -296,6 +292,7 @@ __global__ __launch_bounds__(BLOCK) void k_follow_gather(WorkerPtrs P, const Dev
             store_v4<true>(rl + base + loc, rr[u]);
         }
     } else {
+        // ragged tail of a layer, or a layer whose base is not 16-byte aligned
         for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
             const uint32_t loc = u * CHUNK + tid * VEC;
             const uint32_t i = base + loc;
@@ -303,7 +300,7 @@ __global__ __launch_bounds__(BLOCK) void k_follow_gather(WorkerPtrs P, const Dev
             float rv[4], gv[4];
             load_quad(rl, i, L.n, vec, rv);
             load_quad(gl, i, L.n, vec, gv);
-            const uint32_t nib = (map[loc >> 5] >> (loc & 31u)) & 0xFu;
+            const uint32_t nib = cnt ? (map[loc >> 5] >> (loc & 31u)) & 0xFu : 0u;
             uint32_t rank = nib ? bitmap_rank(map, pre, loc) : 0u;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
