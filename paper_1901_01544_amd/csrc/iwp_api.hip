@@ -195,6 +195,7 @@ struct iwp_plan {
     std::vector<iwp_layer> rows;
     DevLayer* dev = nullptr;      // n_layers + 1 rows
     Sizes z{};
+    uint64_t flat_end = 0;        // one past the last element any layer covers
     bool any_k = false;
 };
 
@@ -370,6 +371,7 @@ int iwp_plan_create(const iwp_layer* layers, uint32_t n_layers, iwp_plan** plan_
     plan->rows.assign(layers, layers + n_layers);
     plan->z = Sizes{n_layers, (uint32_t)tiles, (uint32_t)stiles, pairs, slots, 0};
     plan->any_k = any_k;
+    plan->flat_end = end;
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&plan->dev), dev.size() * sizeof(DevLayer));
     if (e == hipSuccess) e = hipMemcpy(plan->dev, dev.data(), dev.size() * sizeof(DevLayer), hipMemcpyHostToDevice);
     if (e != hipSuccess) {
@@ -487,7 +489,7 @@ int iwp_step_segmented(const iwp_plan* plan, float* w, const float* const* g, fl
     if (stat.n && T.any_k) {
         TimedLaunch tl_("k_gather_static", s);
         k_gather_static<<<dim3((uint32_t)((T.pairs + BLOCK - 1) / BLOCK), stat.n), BLOCK, 0, s>>>(
-            R, stat, T.layers, T.n_layers, leader, W, idx_out, ws.gathered, T.pairs);
+            R, stat, T.layers, T.n_layers, leader, W, idx_out, ws.gathered, T.pairs, plan->flat_end);
     }
     {
         hipError_t e_ = hipGetLastError();
@@ -495,7 +497,7 @@ int iwp_step_segmented(const iwp_plan* plan, float* w, const float* const* g, fl
     }
     if (T.any_k)
         IWP_LAUNCH("k_reduce_update", k_reduce_update, (uint32_t)((T.pairs + BLOCK - 1) / BLOCK), s, ws.gathered, W,
-                   T.pairs, idx_out, w, scale, sum_out);
+                   T.pairs, idx_out, w, scale, sum_out, plan->flat_end);
     return IWP_OK;
 }
 

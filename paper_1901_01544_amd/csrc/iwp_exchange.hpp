@@ -37,7 +37,7 @@ __global__ __launch_bounds__(BLOCK) void k_gather_static(ResidualPtrs R, WorkerL
                                                          const DevLayer* __restrict__ layers, uint32_t n_layers,
                                                          const uint32_t* __restrict__ leader, uint32_t W,
                                                          const uint32_t* __restrict__ idx, float* __restrict__ gathered,
-                                                         uint64_t K) {
+                                                         uint64_t K, uint64_t flat_end) {
     const uint64_t j = (uint64_t)blockIdx.x * BLOCK + threadIdx.x;
     if (j >= K) return;
     const uint32_t p = stat.id[blockIdx.y];
@@ -48,6 +48,7 @@ __global__ __launch_bounds__(BLOCK) void k_gather_static(ResidualPtrs R, WorkerL
     }
     if (leader_of(leader, lo, W) == p) return;
     const uint32_t i = idx[j];
+    if (i >= flat_end) return;                   // cannot happen for pairs this library wrote
     gathered[(size_t)p * K + j] = R.r[p][i];
     R.r[p][i] = 0.0f;
 }
@@ -58,13 +59,14 @@ __global__ __launch_bounds__(BLOCK) void k_gather_static(ResidualPtrs R, WorkerL
 // the weight update.
 __global__ __launch_bounds__(BLOCK) void k_reduce_update(const float* __restrict__ gathered, uint32_t W, uint64_t K,
                                                          const uint32_t* __restrict__ idx, float* __restrict__ w,
-                                                         float scale, float* __restrict__ sum_out) {
+                                                         float scale, float* __restrict__ sum_out, uint64_t flat_end) {
     const uint64_t j = (uint64_t)blockIdx.x * BLOCK + threadIdx.x;
     if (j >= K) return;
     float acc = gathered[j];
     for (uint32_t p = 1; p < W; ++p) acc = acc + gathered[(size_t)p * K + j];
     sum_out[j] = acc;
     const uint32_t i = idx[j];
+    if (i >= flat_end) return;                   // cannot happen for pairs this library wrote
     const float t = scale * acc;
     w[i] = w[i] + t;
 }

@@ -246,8 +246,9 @@ __global__ __launch_bounds__(BLOCK) void k_follow_gather(WorkerPtrs P, WorkerLis
     uint32_t lo = 0, cnt = 0;
     if (has_sel) {
         const uint32_t ntiles = (L.n + TILE - 1) / TILE;
-        lo = tile_out[t];
-        const uint32_t hi = (lt + 1 < ntiles) ? tile_out[t + 1] : L.k;
+        // positions are clamped to the layer's k pairs: never index outside idx / the gather row
+        lo = min(tile_out[t], L.k);
+        const uint32_t hi = (lt + 1 < ntiles) ? min(tile_out[t + 1], L.k) : L.k;
         cnt = hi > lo ? min(hi - lo, TILE) : 0u;
     }
     const uint32_t* ix = idx + L.out_offset + lo;
