@@ -73,6 +73,7 @@ def main():
     ap.add_argument("--no-hint", action="store_true",
                     help="whole_step only: do not pass the previous step's thresholds as a hint (results are "
                          "identical either way; the hint saves the second pass over the leaders' layers)")
+    ap.add_argument("--no-parts", action="store_true", help="skip the stand-alone compress / exchange timings")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--scale-down", type=int, default=1, help="shrink the many_small / flat workloads (debug)")
     args = ap.parse_args()
@@ -140,7 +141,7 @@ def main():
             iwp.step_segmented(plan, w, g, r, leaders[t], eps, scale, idx, val, sm, thr2[t % 2], ws, stream,
                                thr_hint=hint)
         else:
-            iwp.compress_segmented(plan, w, g, r, leaders[t], eps, idx, val, thr, ws, stream)
+            iwp.compress_segmented(plan, w, g, r, leaders[t], eps, idx, val, thr2[t % 2], ws, stream)
             iwp.gather_sum_at_indices(r, idx, ps.K, sm, stream)
             iwp.apply_sparse_update(w, idx, sm, ps.K, scale, r, stream)
 
@@ -167,6 +168,44 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     k_ms, k_cnt = iwp.timing_collect()
+
+    # the parts on their own, after the timed region (they change r and w further, which no longer matters):
+    # (i) compression of one worker (accumulate + score + select + compact, every layer leads itself),
+    # (ii) the exchange as the two separate calls over the K pairs the last step produced
+    parts = {}
+    if not args.no_parts:
+        ws1 = torch.empty(max(1, plan.workspace_bytes), dtype=torch.uint8, device=dev)
+        reps = 5
+        def timed(fn):
+            for _ in range(2):
+                fn()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t1) / reps
+        tc = timed(lambda: iwp.compress_segmented(plan, w, [grads[0]], [r[0]], None, eps, idx, val, thr2[0], ws1, stream))
+        flip = [0]
+        def hinted():                                      # hint: the records the previous call wrote
+            flip[0] ^= 1
+            iwp.compress_segmented(plan, w, [grads[0]], [r[0]], None, eps, idx, val, thr2[flip[0]], ws1, stream,
+                                   thr_hint=thr2[flip[0] ^ 1])
+        th = timed(hinted)
+        tg = timed(lambda: iwp.gather_sum_at_indices(r, idx, ps.K, sm, stream))
+        tu = timed(lambda: iwp.apply_sparse_update(w, idx, sm, ps.K, scale, r, stream))
+        cb = 16 * ps.P + 8 * ps.K
+        xb = (12 + 8 * W_list + 8) * ps.K
+        parts = {
+            "compress_one_worker": {"ms": tc * 1e3, "params_per_s": ps.P / tc, "algorithmic_GBps": cb / tc / 1e9,
+                                    "frac_of_hbm_peak": cb / tc / 1e9 / HBM_PEAK_GBPS},
+            "compress_one_worker_hinted": {"ms": th * 1e3, "params_per_s": ps.P / th,
+                                           "algorithmic_GBps": cb / th / 1e9,
+                                           "frac_of_hbm_peak": cb / th / 1e9 / HBM_PEAK_GBPS},
+            "exchange_two_calls": {"ms": (tg + tu) * 1e3, "pairs_per_s": ps.K / (tg + tu),
+                                   "algorithmic_GBps": xb / (tg + tu) / 1e9, "gather_ms": tg * 1e3, "update_ms": tu * 1e3},
+        }
+        del ws1
 
     ms_per_step = elapsed * 1e3 / args.steps
     params_per_s = ps.P * args.steps / elapsed
@@ -197,6 +236,7 @@ def main():
         "step_algorithmic_GBps": algo_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "copy_kernel_GBps": copy_gbps,
+        "parts": parts,
         "input_generation_s": gen_s,
         "roofline": {
             "bound": "hbm",

@@ -156,9 +156,10 @@ uint64_t iwp_plan_total_pairs(const iwp_plan* plan);
  * positions in the flat buffers (offset + position in layer), ascending within a
  * layer, layers in table order starting at out_offset; val_out alike.
  * thr_out: device array of n_layers records, or NULL.  w: flat weights; g, r:
- * host arrays of W device pointers to flat buffers with w's layout. */
+ * host arrays of W device pointers to flat buffers with w's layout.
+ * thr_hint: NULL or expected thresholds (see iwp_step_segmented); a pure shortcut. */
 int compress_segmented(const iwp_plan* plan, const float* w, const float* const* g, float* const* r,
-                       uint32_t W, const uint32_t* leader, float eps,
+                       uint32_t W, const uint32_t* leader, const iwp_threshold* thr_hint, float eps,
                        uint32_t* idx_out, float* val_out, iwp_threshold* thr_out,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
 

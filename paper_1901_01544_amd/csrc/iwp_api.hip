@@ -421,13 +421,16 @@ static int worker_tables(const float* const* g, float* const* r, uint32_t W, Wor
 }
 
 int compress_segmented(const iwp_plan* plan, const float* w, const float* const* g, float* const* r, uint32_t W,
-                       const uint32_t* leader, float eps, uint32_t* idx_out, float* val_out, iwp_threshold* thr_out,
-                       void* workspace, size_t workspace_bytes, void* hip_stream) {
+                       const uint32_t* leader, const iwp_threshold* thr_hint, float eps, uint32_t* idx_out,
+                       float* val_out, iwp_threshold* thr_out, void* workspace, size_t workspace_bytes,
+                       void* hip_stream) {
     if (!plan) return IWP_EINVAL;
     if (check_eps(eps)) return IWP_EINVAL;
     if (plan->any_k && (!w || !idx_out || !val_out)) return IWP_EINVAL;
-    if (!aligned4(w) || !aligned4(idx_out) || !aligned4(val_out) || !aligned4(thr_out) || !aligned4(leader))
+    if (!aligned4(w) || !aligned4(idx_out) || !aligned4(val_out) || !aligned4(thr_out) || !aligned4(leader) ||
+        !aligned4(thr_hint))
         return IWP_EALIGN;
+    if (thr_hint && thr_hint == thr_out) return IWP_EINVAL;   // the hint is read while the records are written
     WorkerPtrs P;
     ResidualPtrs R;
     int rc = worker_tables(g, r, W, &P, &R);
@@ -437,7 +440,7 @@ int compress_segmented(const iwp_plan* plan, const float* w, const float* const*
     if (rc) return rc;
     if (plan->z.tiles == 0) return IWP_OK;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    rc = launch_init(ws, plan->z.n_layers, nullptr, nullptr, nullptr, s);
+    rc = launch_init(ws, plan->z.n_layers, thr_hint, nullptr, nullptr, s);
     if (rc) return rc;
     Table T{plan->dev, plan->z.n_layers, plan->z.tiles, plan->z.stiles, plan->z.pairs, plan->any_k};
     IWP_LAUNCH("k_accumulate_all", k_accumulate_all, W * T.tiles, s, P, w, T.layers, T.n_layers, T.tiles, leader, W, eps,

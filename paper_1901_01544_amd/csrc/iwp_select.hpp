@@ -430,33 +430,61 @@ __global__ __launch_bounds__(BLOCK) void k_write(ResidualPtrs R, const float* __
         const uint64_t sb = L.slot_begin + (uint64_t)lt * L.slot_cap;
         eqmap[2 * lane] = 0u; eqmap[2 * lane + 1] = 0u;
         selmap[2 * lane] = 0u; selmap[2 * lane + 1] = 0u;
-        wave_sync();
-        for (uint32_t e = lane; e < cnt; e += WAVE) {
-            if (A.key[sb + e] == thr) {
-                const uint32_t loc = (A.idx[sb + e] - tile_first) & (TILE - 1);
-                atomicOr(&eqmap[loc >> 5], 1u << (loc & 31u));
+        // a lane keeps up to PER of the tile's entries in registers (enough for the usual tile); the
+        // rare fuller slot takes more rounds of the same three passes
+        constexpr uint32_t PER = 2;
+        for (uint32_t e0 = 0; e0 < cnt; e0 += PER * WAVE) {
+            uint32_t key[PER], loc[PER];
+            float val[PER];
+            bool have[PER];
+#pragma unroll
+            for (uint32_t q = 0; q < PER; ++q) {
+                const uint32_t e = e0 + q * WAVE + lane;
+                have[q] = e < cnt;
+                key[q] = have[q] ? A.key[sb + e] : 0u;
+                loc[q] = have[q] ? (A.idx[sb + e] - tile_first) & (TILE - 1) : 0u;
+                val[q] = have[q] ? A.val[sb + e] : 0.0f;
             }
-        }
-        wave_sync();
-        wave_bitmap_prefix(eqmap, eqpre);
-        for (uint32_t e = lane; e < cnt; e += WAVE) {
-            const uint32_t key = A.key[sb + e];
-            const uint32_t loc = (A.idx[sb + e] - tile_first) & (TILE - 1);
-            const bool sel = key > thr || (key == thr && Et + bitmap_rank(eqmap, eqpre, loc) < quota);
-            if (sel) atomicOr(&selmap[loc >> 5], 1u << (loc & 31u));
-        }
-        wave_sync();
-        wave_bitmap_prefix(selmap, selpre);
-        for (uint32_t e = lane; e < cnt; e += WAVE) {
-            const uint32_t li = A.idx[sb + e];
-            const uint32_t loc = (li - tile_first) & (TILE - 1);
-            if ((selmap[loc >> 5] >> (loc & 31u)) & 1u) {
-                const uint32_t pos = out_base + bitmap_rank(selmap, selpre, loc);
-                if (pos < L.k && li < L.n) {
-                    const float v = A.val[sb + e];
-                    io[pos] = (uint32_t)(L.offset + li);
-                    vo[pos] = v;
-                    if (FUSED) { go[pos] = v; rl[li] = 0.0f; }
+            if (e0 == 0) {
+                // ties first: all of the slot's entries equal to the threshold, in index order
+                wave_sync();
+                for (uint32_t e = lane; e < cnt; e += WAVE) {
+                    if (e < PER * WAVE) continue;                         // those are in registers (below)
+                    if (A.key[sb + e] == thr) {
+                        const uint32_t l2 = (A.idx[sb + e] - tile_first) & (TILE - 1);
+                        atomicOr(&eqmap[l2 >> 5], 1u << (l2 & 31u));
+                    }
+                }
+#pragma unroll
+                for (uint32_t q = 0; q < PER; ++q)
+                    if (have[q] && key[q] == thr) atomicOr(&eqmap[loc[q] >> 5], 1u << (loc[q] & 31u));
+                wave_sync();
+                wave_bitmap_prefix(eqmap, eqpre);
+                // then everything that is kept
+                for (uint32_t e = lane; e < cnt; e += WAVE) {
+                    if (e < PER * WAVE) continue;
+                    const uint32_t k2 = A.key[sb + e];
+                    const uint32_t l2 = (A.idx[sb + e] - tile_first) & (TILE - 1);
+                    if (k2 > thr || (k2 == thr && Et + bitmap_rank(eqmap, eqpre, l2) < quota))
+                        atomicOr(&selmap[l2 >> 5], 1u << (l2 & 31u));
+                }
+#pragma unroll
+                for (uint32_t q = 0; q < PER; ++q)
+                    if (have[q] && (key[q] > thr || (key[q] == thr && Et + bitmap_rank(eqmap, eqpre, loc[q]) < quota)))
+                        atomicOr(&selmap[loc[q] >> 5], 1u << (loc[q] & 31u));
+                wave_sync();
+                wave_bitmap_prefix(selmap, selpre);
+            }
+#pragma unroll
+            for (uint32_t q = 0; q < PER; ++q) {
+                if (have[q] && ((selmap[loc[q] >> 5] >> (loc[q] & 31u)) & 1u)) {
+                    const uint32_t pos = out_base + bitmap_rank(selmap, selpre, loc[q]);
+                    const uint32_t li = tile_first + loc[q];
+                    if (pos < L.k && li < L.n) {
+                        io[pos] = (uint32_t)(L.offset + li);
+                        vo[pos] = val[q];
+                        if (FUSED) { go[pos] = val[q]; rl[li] = 0.0f; }
+                    }
                 }
             }
         }

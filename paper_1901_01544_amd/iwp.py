@@ -63,7 +63,7 @@ def load() -> C.CDLL:
     L.iwp_step_segmented.restype = C.c_int
     L.iwp_plan_total_pairs.argtypes = [_vp]
     L.iwp_plan_total_pairs.restype = C.c_uint64
-    L.compress_segmented.argtypes = [_vp, _vp, C.POINTER(_vp), C.POINTER(_vp), C.c_uint32, _vp, C.c_float,
+    L.compress_segmented.argtypes = [_vp, _vp, C.POINTER(_vp), C.POINTER(_vp), C.c_uint32, _vp, _vp, C.c_float,
                                      _vp, _vp, _vp, _vp, C.c_size_t, _vp]
     L.select_threshold_segmented.argtypes = [_vp, _vp, _vp, C.c_float, _vp, _vp, C.c_size_t, _vp]
     L.compact_pairs_segmented.argtypes = [_vp, _vp, _vp, C.c_float, _vp, _vp, _vp, _vp, C.c_size_t, _vp]
@@ -188,10 +188,11 @@ class Plan:
 
 
 def compress_segmented(plan: Plan, w, g: Sequence, r: Sequence, leader, eps: float, idx_out, val_out, thr_out,
-                       workspace, stream=None):
+                       workspace, stream=None, thr_hint=None):
     assert len(g) == len(r)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(load().compress_segmented(plan._h, _ptr(w), _ptr_table(g), _ptr_table(r), len(r), _ptr(leader), eps,
+    _check(load().compress_segmented(plan._h, _ptr(w), _ptr_table(g), _ptr_table(r), len(r), _ptr(leader),
+                                     _ptr(thr_hint), eps,
                                      _ptr(idx_out), _ptr(val_out), _ptr(thr_out), _ptr(workspace), ws_bytes,
                                      _stream(stream)), "compress_segmented")
 

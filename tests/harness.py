@@ -53,29 +53,29 @@ class GpuSet:
         self.leader.copy_(self.torch.from_numpy(leader_np.astype(np.int32)))
         g = [None if i is None else self.grads[i] for i in g_ids]
         sc = float(ps.scale if scale is None else scale)
+        hint = None
+        if self.hint_mode == "previous" and self.steps_done > 0:
+            self.hint.copy_(self.thr)
+            hint = self.hint
+        elif self.hint_mode == "garbage":
+            self.hint.copy_(self.torch.randint(-2 ** 31, 2 ** 31 - 1, (self.hint.numel(),), dtype=self.torch.int64,
+                                               device=self.hint.device).to(self.torch.int32))
+            hint = self.hint
+        elif self.hint_mode in ("high", "low") and self.steps_done > 0:
+            # last step's keys moved up / down by a few top-digit bins
+            key = self.thr.view(-1, 3)[:, 0].to(self.torch.int64)
+            key = key + (5 << 19) if self.hint_mode == "high" else self.torch.clamp(key - (5 << 19), min=0)
+            self.hint.view(-1, 3)[:, 0] = key.clamp(max=2 ** 31 - 1).to(self.torch.int32)
+            hint = self.hint
+        self.steps_done += 1
         if self.fused:
             self.sum.fill_(float("nan"))
-            hint = None
-            if self.hint_mode == "previous" and self.steps_done > 0:
-                self.hint.copy_(self.thr)
-                hint = self.hint
-            elif self.hint_mode == "garbage":
-                self.hint.copy_(self.torch.randint(-2 ** 31, 2 ** 31 - 1, (self.hint.numel(),), dtype=self.torch.int64,
-                                                   device=self.hint.device).to(self.torch.int32))
-                hint = self.hint
-            elif self.hint_mode in ("high", "low") and self.steps_done > 0:
-                # last step's keys moved up / down by a few top-digit bins
-                key = self.thr.view(-1, 3)[:, 0].to(self.torch.int64)
-                key = key + (5 << 19) if self.hint_mode == "high" else self.torch.clamp(key - (5 << 19), min=0)
-                self.hint.view(-1, 3)[:, 0] = key.clamp(max=2 ** 31 - 1).to(self.torch.int32)
-                hint = self.hint
             iwp.step_segmented(self.plan, self.w, g, self.r, self.leader, float(ps.eps), sc, self.idx, self.val,
                                self.sum, self.thr, self.ws, thr_hint=hint)
             self.torch.cuda.synchronize()
-            self.steps_done += 1
             return
         iwp.compress_segmented(self.plan, self.w, g, self.r, self.leader, float(ps.eps), self.idx, self.val,
-                               self.thr, self.ws)
+                               self.thr, self.ws, thr_hint=hint)
         iwp.gather_sum_at_indices(self.r, self.idx, ps.K, self.sum)
         iwp.apply_sparse_update(self.w, self.idx, self.sum, ps.K, sc, self.r)
         self.torch.cuda.synchronize()

@@ -220,12 +220,21 @@ def test_exchange_kernels(gpu_lib):
 
 # ---------------------------------------------------------------- whole steps on parameter sets
 
+def _route(fused):
+    """Test parameter -> GpuSet arguments: False / "3:<hint>" = the three separate calls."""
+    if not fused:
+        return dict(fused=False, hint="none")
+    if fused.startswith("3:"):
+        return dict(fused=False, hint=fused[2:])
+    return dict(fused=True, hint=fused)
+
+
 def _run_steps(iwp, ps, steps, pool, W=None, r0=None, g_ids_fn=None, leader_fn=None, tag="", fused=False):
     W = ps.W if W is None else W
     w = wl.gen_weights(ps)
     sets = [wl.gen_gradient(ps, s) for s in range(pool)]
     r_ref = [np.zeros(ps.flat, np.float32) for _ in range(W)] if r0 is None else [x.copy() for x in r0]
-    gs = GpuSet(iwp, ps, w, sets, r_np=r0, W=W, fused=bool(fused), hint=fused or "none")
+    gs = GpuSet(iwp, ps, w, sets, r_np=r0, W=W, **_route(fused))
     w_ref = w.copy()
     for t in range(steps):
         lead = wl.leaders(ps, t, n_candidates=W) if leader_fn is None else leader_fn(t)
@@ -242,7 +251,8 @@ def _run_steps(iwp, ps, steps, pool, W=None, r0=None, g_ids_fn=None, leader_fn=N
 
 # fused: False = the three separate calls; otherwise the whole-step entry point with the named kind of
 # threshold hint ("previous" = last step's records, the intended use; the others must not change a bit either)
-ROUTES = pytest.mark.parametrize("fused", [False, "none", "previous"], ids=["three_calls", "whole_step", "whole_step_hinted"])
+ROUTES = pytest.mark.parametrize("fused", [False, "3:previous", "none", "previous"],
+                                 ids=["three_calls", "three_calls_hinted", "whole_step", "whole_step_hinted"])
 HINTS = pytest.mark.parametrize("fused", ["garbage", "high", "low"], ids=["hint_garbage", "hint_high", "hint_low"])
 
 
@@ -274,7 +284,7 @@ def test_leader_table_out_of_range_reads_as_worker_zero(gpu_lib, fused):
     bad = np.array([7, 0xFFFFFFFF], np.uint32)
     w = wl.gen_weights(ps)
     sets = [wl.gen_gradient(ps, s) for s in range(2)]
-    gs = GpuSet(gpu_lib, ps, w, sets, fused=bool(fused), hint=fused or "none")
+    gs = GpuSet(gpu_lib, ps, w, sets, **_route(fused))
     gs.step([0, 1], bad)
     r_ref = [np.zeros(ps.flat, np.float32) for _ in range(2)]
     ref = oracle.step(w, sets, r_ref, ps.rows(), np.zeros(2, np.uint32), float(ps.eps), float(ps.scale))
@@ -341,7 +351,7 @@ def test_staging_overflow_takes_the_raw_route(gpu_lib, fused):
     w[L0.offset:L0.offset + n] = 1.0
     w[L1.offset:L1.offset + n] = 1.0
     sets = [g0, g1]
-    gs = GpuSet(gpu_lib, ps, w, sets, fused=bool(fused), hint=fused or "none")
+    gs = GpuSet(gpu_lib, ps, w, sets, **_route(fused))
     w_ref = w.copy()
     r_ref = [np.zeros(ps.flat, np.float32) for _ in range(2)]
     for t in range(3):
