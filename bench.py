@@ -12,7 +12,9 @@ are resident in HBM before the timed region.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload alexnet|resnet50|many_small|tiny|flat]
 
-Prints ONE JSON line (see the design doc for the fields).  The default workload is the
+Prints ONE JSON line: metric / value / unit, ms_per_step, the roofline of the
+dominant kernel, stand-alone part timings and the oracle timed on the host
+(cpu_baseline).  The default workload is the
 AlexNet-shaped set the headline metric is quoted on.
 """
 from __future__ import annotations
@@ -79,7 +81,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU; --gpus N with N > 1 is not supported "
-              "(the path shards by worker, see DESIGN.md)", file=sys.stderr)
+              "(the path would shard by worker: one GPU per data-parallel worker)", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
