@@ -78,6 +78,20 @@ def lib():
                                   C.c_uint32, C.POINTER(Layer), _u32p, C.c_uint32, C.c_float, C.c_float,
                                   _u32p, _f32p, _f32p, C.POINTER(Threshold)]
         L.oracle_step.restype = C.c_int
+        _u8p = C.POINTER(C.c_uint8)
+        L.oracle_mask_bytes.argtypes = [C.c_uint64]
+        L.oracle_mask_bytes.restype = C.c_uint64
+        L.oracle_mask_threshold.argtypes = [_f32p, _f32p, C.c_uint64, C.c_float, C.c_float, _u8p]
+        L.oracle_mask_threshold.restype = None
+        L.oracle_mask_or.argtypes = [_u8p, _u8p, C.c_uint64]
+        L.oracle_mask_or.restype = None
+        L.oracle_mask_indices.argtypes = [_u8p, C.c_uint64, _u32p]
+        L.oracle_mask_indices.restype = C.c_uint64
+        L.oracle_step_threshold.argtypes = [_f32p, C.POINTER(_f32p), C.POINTER(_f32p), _u8p, C.c_uint32,
+                                            C.POINTER(Layer), _u32p, C.c_uint32, _f32p, C.c_uint32, C.c_float,
+                                            C.c_float, _u8p, _u32p, _u32p, _f32p, C.c_uint64,
+                                            C.POINTER(C.c_uint64)]
+        L.oracle_step_threshold.restype = C.c_int
     return _lib
 
 
@@ -195,3 +209,59 @@ def step(w: np.ndarray, g: Sequence[np.ndarray], r: Sequence[np.ndarray], rows, 
         raise ValueError("oracle_step: rc=%d" % rc)
     thr_np = np.array([(t.key, t.n_gt, t.n_eq_take) for t in thr], np.uint32).reshape(len(rows), 3)
     return idx, val, sm, thr_np
+
+
+# ------------------------------------------------------------------ threshold mode
+
+def _u8(a: np.ndarray):
+    assert a.dtype == np.uint8 and a.flags.c_contiguous, "uint8 C-contiguous array required"
+    return a.ctypes.data_as(C.POINTER(C.c_uint8))
+
+
+def mask_bytes(n: int) -> int:
+    return int(lib().oracle_mask_bytes(n))
+
+
+def mask_threshold(w: np.ndarray, r: np.ndarray, eps: float, thr: float) -> np.ndarray:
+    """Encoded mask (uint8, LSB first, padded to whole 32-bit words) of score > thr."""
+    m = np.empty(mask_bytes(r.size), np.uint8)
+    lib().oracle_mask_threshold(_f32(w), _f32(r), r.size, C.c_float(eps), C.c_float(thr), _u8(m))
+    return m
+
+
+def mask_or(acc: np.ndarray, m: np.ndarray) -> None:
+    assert acc.size == m.size
+    lib().oracle_mask_or(_u8(acc), _u8(m), acc.size)
+
+
+def mask_indices(mask: np.ndarray, n: int) -> np.ndarray:
+    idx = np.empty(n, np.uint32)
+    c = int(lib().oracle_mask_indices(_u8(mask), n, _u32(idx)))
+    return idx[:c].copy()
+
+
+def step_threshold(w: np.ndarray, g: Sequence[np.ndarray], r: Sequence[np.ndarray], rows, leaders: np.ndarray,
+                   thr: np.ndarray, eps: float, scale: float, max_pairs: int,
+                   accumulate_mask: Sequence[int] | None = None):
+    """One whole threshold-mode step on flat host buffers; w and every r[p] are updated
+    in place.  leaders: (n_layers, n_lead) uint32; thr: (n_layers,) float32.
+    -> (mask bytes of all layers back to back, counts[n_layers], idx[total], sum[total])."""
+    rows = list(rows)
+    tab = layer_table(rows)
+    W = len(r)
+    leaders = np.ascontiguousarray(leaders, np.uint32).reshape(len(rows), -1)
+    thr = np.ascontiguousarray(thr, np.float32)
+    mask = np.zeros(sum(mask_bytes(int(n)) for (_, n, _, _) in rows), np.uint8)
+    counts = np.zeros(len(rows), np.uint32)
+    idx = np.empty(max_pairs, np.uint32)
+    sm = np.empty(max_pairs, np.float32)
+    total = C.c_uint64(0)
+    acc = None
+    if accumulate_mask is not None:
+        acc = (C.c_uint8 * W)(*[1 if a else 0 for a in accumulate_mask])
+    rc = lib().oracle_step_threshold(_f32(w), _ptr_array(g), _ptr_array(r), acc, W, tab, _u32(leaders),
+                                     leaders.shape[1], _f32(thr), len(rows), C.c_float(eps), C.c_float(scale),
+                                     _u8(mask), _u32(counts), _u32(idx), _f32(sm), max_pairs, C.byref(total))
+    if rc:
+        raise ValueError("oracle_step_threshold: rc=%d" % rc)
+    return mask, counts, idx[:total.value].copy(), sm[:total.value].copy()

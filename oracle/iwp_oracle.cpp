@@ -29,6 +29,16 @@
 // Arithmetic is IEEE-754 binary32, round to nearest even, denormals kept, no
 // contraction (build with -ffp-contract=off, never -ffast-math).
 //
+// Threshold mode, the front end exactly as Algorithm 1 prints it (fixed thresholds
+// of Section 4.1 instead of a k-th largest score):
+//   T1  mask of one chosen node    m[i] = (s[i] > thr), strict           (Alg. 1, mask line)
+//   T2  encoding                   bit i%8 of byte i/8, LSB first; one layer's mask is a
+//       whole number of 32-bit words                                     (Alg. 1, encode_uint8 -- the paper
+//       does not give the format; this is the build's reading)
+//   T3  union over the chosen nodes  Mask = OR_i m_{r_i}                 (Alg. 1, OR line)
+//   T4  split on EVERY node        sent: R_p[i] for Mask[i], kept: the rest   (Alg. 1, G~ / G lines)
+//   then O5..O7 over the masked positions.
+//
 // Pins (tests/test_oracle_pins.py): brute-force rank count on tiny layers,
 // cardinality, exact conservation, the paper's 64x / 58.8x ratios as keep
 // fractions, numpy lexsort cross-check, threshold-mask equivalence with the
@@ -57,6 +67,7 @@ typedef struct {
     uint32_t out_offset;  // first pair of the layer in idx/val
     uint32_t pad;
 } oracle_layer;
+
 
 }  // extern "C"
 
@@ -223,6 +234,79 @@ int oracle_step(float* w, const float* const* g, float* const* r, const uint8_t*
     std::vector<const float*> rc_ptrs(r, r + W);
     oracle_gather_sum(rc_ptrs.data(), W, idx_out, pairs_total, sum_out);
     oracle_apply_sparse_update(w, idx_out, sum_out, pairs_total, scale, r, W);
+    return 0;
+}
+
+
+// ------------------------------------------------------------------ threshold mode
+
+// Bytes of one layer's encoded mask: whole 32-bit words.
+uint64_t oracle_mask_bytes(uint64_t n) { return ((n + 31) / 32) * 4; }
+
+// T1 + T2 for one chosen node: scores above thr, strictly; bit i%8 of byte i/8.
+void oracle_mask_threshold(const float* w, const float* r, uint64_t n, float eps, float thr, uint8_t* mask) {
+    std::memset(mask, 0, oracle_mask_bytes(n));
+    for (uint64_t i = 0; i < n; ++i) {
+        float denom = std::fabs(w[i]) + eps;
+        float s = std::fabs(r[i]) / denom;
+        if (s > thr) mask[i >> 3] = (uint8_t)(mask[i >> 3] | (1u << (i & 7)));
+    }
+}
+
+// T3: acc |= m, byte by byte.
+void oracle_mask_or(uint8_t* acc, const uint8_t* m, uint64_t nbytes) {
+    for (uint64_t b = 0; b < nbytes; ++b) acc[b] = (uint8_t)(acc[b] | m[b]);
+}
+
+// The masked positions of a layer in ascending order; returns how many.
+uint64_t oracle_mask_indices(const uint8_t* mask, uint64_t n, uint32_t* idx_out) {
+    uint64_t c = 0;
+    for (uint64_t i = 0; i < n; ++i)
+        if ((mask[i >> 3] >> (i & 7)) & 1u) idx_out[c++] = (uint32_t)i;
+    return c;
+}
+
+// One whole iteration of Algorithm 1 in threshold mode on a flat parameter set.
+// leaders: n_layers x n_lead chosen nodes per layer (row-major); thr: one threshold
+// per layer; mask_out: the layers' encoded masks back to back (oracle_mask_bytes(n)
+// each); count_out[j]: masked positions of layer j; idx_out / sum_out: the masked
+// flat positions of all layers packed in table order and the reduced values, at most
+// max_pairs (returns -4 if there are more).  Every worker with accumulate[p] != 0
+// adds its gradient first; every worker is cleared at the masked positions.
+int oracle_step_threshold(float* w, const float* const* g, float* const* r, const uint8_t* accumulate, uint32_t W,
+                          const oracle_layer* layers, const uint32_t* leaders, uint32_t n_lead,
+                          const float* thr, uint32_t n_layers, float eps, float scale, uint8_t* mask_out,
+                          uint32_t* count_out, uint32_t* idx_out, float* sum_out, uint64_t max_pairs,
+                          uint64_t* total_out) {
+    uint64_t total = 0, mask_off = 0;
+    for (uint32_t j = 0; j < n_layers; ++j) {
+        const oracle_layer& L = layers[j];
+        for (uint32_t p = 0; p < W; ++p) {
+            if (accumulate && !accumulate[p]) continue;
+            oracle_accumulate(r[p] + L.offset, g[p] + L.offset, L.n);
+        }
+        const uint64_t nbytes = oracle_mask_bytes(L.n);
+        uint8_t* mask = mask_out + mask_off;
+        std::memset(mask, 0, nbytes);
+        std::vector<uint8_t> one(nbytes);
+        for (uint32_t q = 0; q < n_lead; ++q) {
+            const uint32_t lead = leaders[(size_t)j * n_lead + q];
+            if (lead >= W) return -2;
+            oracle_mask_threshold(w + L.offset, r[lead] + L.offset, L.n, eps, thr[j], one.data());
+            oracle_mask_or(mask, one.data(), nbytes);
+        }
+        std::vector<uint32_t> local(L.n);
+        const uint64_t c = oracle_mask_indices(mask, L.n, local.data());
+        count_out[j] = (uint32_t)c;
+        if (total + c > max_pairs) return -4;
+        for (uint64_t q = 0; q < c; ++q) idx_out[total + q] = (uint32_t)(L.offset + local[q]);
+        total += c;
+        mask_off += nbytes;
+    }
+    if (total_out) *total_out = total;
+    std::vector<const float*> rc_ptrs(r, r + W);
+    oracle_gather_sum(rc_ptrs.data(), W, idx_out, total, sum_out);
+    oracle_apply_sparse_update(w, idx_out, sum_out, total, scale, r, W);
     return 0;
 }
 
