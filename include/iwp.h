@@ -199,6 +199,34 @@ int compact_pairs_segmented(const iwp_plan* plan, const float* w, const float* r
                             const iwp_threshold* thr, uint32_t* idx_out, float* val_out,
                             void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ------------------------------------------------------------------ threshold mode */
+
+/* Bytes of the encoded masks of all layers of the plan: layer j's mask takes
+ * 4 * ceil(n_j / 32) bytes, the layers follow each other in table order. */
+size_t iwp_plan_mask_bytes(const iwp_plan* plan);
+size_t iwp_plan_threshold_workspace_bytes(const iwp_plan* plan, uint32_t W, uint32_t n_lead, uint32_t max_pairs);
+
+/* One whole iteration of Algorithm 1 with the front end exactly as printed: a fixed
+ * threshold per layer (Section 4.1 uses 0.005 ... 0.1) instead of a k-th largest
+ * importance.  For every layer j of the plan (the rows' k and out_offset are not
+ * used): every worker with g[p] != NULL accumulates; each of the n_lead chosen nodes
+ * leaders[j * n_lead + q] (device array; entries >= W read as 0; a node listed twice
+ * counts once) marks the elements with |r| / (|w| + eps) strictly above thr[j]
+ * (device array of n_layers floats); the masks are encoded one bit per element
+ * (encode_uint8 of Algorithm 1: bit i % 8 of byte i / 8) and OR-ed into mask_out;
+ * every worker's residual at the masked positions is summed in worker order,
+ * w[i] += scale * sum, and the residuals are cleared there.
+ * Outputs: mask_out (iwp_plan_mask_bytes, 4-byte aligned); count_out[0..n_layers) =
+ * sent elements per layer, count_out[n_layers] = their total, count_out[n_layers + 1]
+ * = 1 if the total exceeds max_pairs -- then the workers are accumulated and the
+ * mask and counts are valid, but nothing is exchanged, updated or cleared;
+ * idx_out / sum_out (capacity max_pairs): ascending flat positions, layers packed
+ * in table order, and the reduced values.  n_lead <= 8 and <= W. */
+int iwp_step_threshold_segmented(const iwp_plan* plan, float* w, const float* const* g, float* const* r, uint32_t W,
+                                 const uint32_t* leaders, uint32_t n_lead, const float* thr, float eps, float scale,
+                                 uint8_t* mask_out, uint32_t* count_out, uint32_t* idx_out, float* sum_out,
+                                 uint32_t max_pairs, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* ------------------------------------------------------------------ helpers */
 
 /* The importance keys exactly as the kernels compute them: key_out[i] = bit

@@ -15,6 +15,7 @@
 #include "iwp_exchange.hpp"
 #include "iwp_select.hpp"
 #include "iwp_stream.hpp"
+#include "iwp_threshold.hpp"
 
 using namespace iwp;
 
@@ -85,6 +86,7 @@ inline uint32_t slot_cap_of(uint32_t n, uint32_t k) {
 struct Sizes {                // everything the workspace layout depends on
     uint32_t n_layers, tiles, stiles;
     uint64_t pairs, slots;    // slots: staging entries over all tiles
+    uint64_t mask_words;      // 32-bit words of all layers' encoded masks (threshold mode)
     uint32_t W_gather;        // rows of the gather matrix (whole-step entry point), else 0
 };
 
@@ -165,7 +167,7 @@ int run_select(const Table& T, const Workspace& ws, const ResidualPtrs& R, const
     if (stop == STOP_AT_THRESHOLD) return IWP_OK;
     IWP_LAUNCH("k_count", k_count, T.stiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.stage, ws.A,
                false, ws.tile_counts, ws.stile_counts);
-    IWP_LAUNCH("k_scan", k_scan, T.n_layers, s, T.layers, ws.stile_counts);
+    IWP_LAUNCH("k_scan", k_scan, T.n_layers, s, T.layers, ws.stile_counts, false, nullptr);
     if (fused)
         IWP_LAUNCH("k_write", k_write<true>, (T.tiles + 3) / 4, s, R, w, T.layers, T.n_layers, T.tiles, leader, W, eps, ws.state, ws.stage,
                    ws.A, false, ws.tile_counts, ws.stile_counts, ws.tile_out, idx_out, val_out, ws.gathered, T.pairs);
@@ -183,7 +185,7 @@ int run_compact_from(const Table& T, const Workspace& ws, const ResidualPtrs& R,
                ws.state);
     IWP_LAUNCH("k_count", k_count, T.stiles, s, R, w, T.layers, T.n_layers, nullptr, 1u, eps, ws.state, ws.stage, ws.A,
                true, ws.tile_counts, ws.stile_counts);
-    IWP_LAUNCH("k_scan", k_scan, T.n_layers, s, T.layers, ws.stile_counts);
+    IWP_LAUNCH("k_scan", k_scan, T.n_layers, s, T.layers, ws.stile_counts, false, nullptr);
     IWP_LAUNCH("k_write", k_write<false>, (T.tiles + 3) / 4, s, R, w, T.layers, T.n_layers, T.tiles, nullptr, 1u, eps, ws.state, ws.stage,
                ws.A, true, ws.tile_counts, ws.stile_counts, ws.tile_out, idx_out, val_out, nullptr, T.pairs);
     return IWP_OK;
@@ -220,7 +222,8 @@ const char* iwp_last_hip_error(void) { return g_hip_error; }
 static Sizes single_sizes(uint32_t n, uint32_t k) {
     Sizes z;
     z.n_layers = 1; z.tiles = tiles_of(n); z.stiles = stiles_of(n);
-    z.pairs = k; z.slots = (uint64_t)z.tiles * slot_cap_of(n, k); z.W_gather = 0;
+    z.pairs = k; z.slots = (uint64_t)z.tiles * slot_cap_of(n, k); z.mask_words = ((uint64_t)n + 31) / 32;
+    z.W_gather = 0;
     return z;
 }
 
@@ -334,7 +337,7 @@ int iwp_plan_create(const iwp_layer* layers, uint32_t n_layers, iwp_plan** plan_
     *plan_out = nullptr;
     if (!layers || n_layers == 0) return IWP_EINVAL;
     std::vector<DevLayer> dev(n_layers + 1);
-    uint64_t pairs = 0, slots = 0, tiles = 0, stiles = 0, end = 0;
+    uint64_t pairs = 0, slots = 0, tiles = 0, stiles = 0, end = 0, mask_words = 0;
     bool any_k = false;
     for (uint32_t j = 0; j < n_layers; ++j) {
         const iwp_layer& L = layers[j];
@@ -352,11 +355,13 @@ int iwp_plan_create(const iwp_layer* layers, uint32_t n_layers, iwp_plan** plan_
         D.tile_begin = (uint32_t)tiles;
         D.stile_begin = (uint32_t)stiles;
         D.slot_cap = slot_cap_of(L.n, L.k);
+        D.mask_begin = (uint32_t)mask_words;
         end = (uint64_t)L.offset + L.n;
         pairs += L.k;
         slots += (uint64_t)tiles_of(L.n) * D.slot_cap;
         tiles += tiles_of(L.n);
         stiles += stiles_of(L.n);
+        mask_words += ((uint64_t)L.n + 31) / 32;
         any_k = any_k || L.k > 0;
         if (pairs > 0xFFFFFFFFull || tiles > 0x7FFFFFFFull / IWP_MAX_WORKERS) return IWP_ERANGE;
     }
@@ -369,7 +374,7 @@ int iwp_plan_create(const iwp_layer* layers, uint32_t n_layers, iwp_plan** plan_
     iwp_plan* plan = new (std::nothrow) iwp_plan;
     if (!plan) return IWP_EINVAL;
     plan->rows.assign(layers, layers + n_layers);
-    plan->z = Sizes{n_layers, (uint32_t)tiles, (uint32_t)stiles, pairs, slots, 0};
+    plan->z = Sizes{n_layers, (uint32_t)tiles, (uint32_t)stiles, pairs, slots, mask_words, 0};
     plan->any_k = any_k;
     plan->flat_end = end;
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&plan->dev), dev.size() * sizeof(DevLayer));
@@ -545,6 +550,95 @@ int compact_pairs_segmented(const iwp_plan* plan, const float* w, const float* r
     R.r[0] = const_cast<float*>(r);
     Table T{plan->dev, plan->z.n_layers, plan->z.tiles, plan->z.stiles, plan->z.pairs, plan->any_k};
     return run_compact_from(T, ws, R, w, eps, thr, idx_out, val_out, s);
+}
+
+// ----------------------------------------------------------------- threshold mode
+
+namespace {
+
+struct ThresholdWorkspace {
+    uint32_t* lmask;          // n_lead * mask_words
+    uint2* tile_counts;       // tiles
+    uint2* stile_counts;      // stiles
+    uint32_t* tile_out;       // tiles
+    uint32_t* layer_total;    // n_layers
+    uint32_t* lay_out;        // n_layers + 1
+    float* gathered;          // W * max_pairs
+    size_t bytes;
+};
+
+ThresholdWorkspace carve_threshold(void* base, const Sizes& z, uint32_t W, uint32_t n_lead, uint32_t max_pairs) {
+    ThresholdWorkspace ws;
+    const uintptr_t b = reinterpret_cast<uintptr_t>(base);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { uintptr_t p = b + off; off += round256(bytes); return p; };
+    ws.lmask = reinterpret_cast<uint32_t*>(take((size_t)n_lead * z.mask_words * sizeof(uint32_t)));
+    ws.tile_counts = reinterpret_cast<uint2*>(take((size_t)z.tiles * sizeof(uint2)));
+    ws.stile_counts = reinterpret_cast<uint2*>(take((size_t)z.stiles * sizeof(uint2)));
+    ws.tile_out = reinterpret_cast<uint32_t*>(take((size_t)z.tiles * sizeof(uint32_t)));
+    ws.layer_total = reinterpret_cast<uint32_t*>(take((size_t)z.n_layers * sizeof(uint32_t)));
+    ws.lay_out = reinterpret_cast<uint32_t*>(take(((size_t)z.n_layers + 1) * sizeof(uint32_t)));
+    ws.gathered = reinterpret_cast<float*>(take((size_t)W * max_pairs * sizeof(float)));
+    ws.bytes = off;
+    return ws;
+}
+
+}  // namespace
+
+size_t iwp_plan_mask_bytes(const iwp_plan* plan) { return plan ? (size_t)plan->z.mask_words * 4 : 0; }
+
+size_t iwp_plan_threshold_workspace_bytes(const iwp_plan* plan, uint32_t W, uint32_t n_lead, uint32_t max_pairs) {
+    return plan ? carve_threshold(nullptr, plan->z, W, n_lead, max_pairs).bytes : 0;
+}
+
+int iwp_step_threshold_segmented(const iwp_plan* plan, float* w, const float* const* g, float* const* r, uint32_t W,
+                                 const uint32_t* leaders, uint32_t n_lead, const float* thr, float eps, float scale,
+                                 uint8_t* mask_out, uint32_t* count_out, uint32_t* idx_out, float* sum_out,
+                                 uint32_t max_pairs, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!plan || !w || !leaders || !thr || !mask_out || !count_out || !idx_out || !sum_out) return IWP_EINVAL;
+    if (n_lead == 0 || n_lead > MAX_LEAD || n_lead > W || max_pairs == 0) return IWP_EINVAL;
+    if (check_eps(eps) || !std::isfinite(scale)) return IWP_EINVAL;
+    if (!aligned4(w) || !aligned4(leaders) || !aligned4(thr) || !aligned4(mask_out) || !aligned4(count_out) ||
+        !aligned4(idx_out) || !aligned4(sum_out))
+        return IWP_EALIGN;
+    WorkerPtrs P;
+    ResidualPtrs R;
+    int rc = worker_tables(g, r, W, &P, &R);
+    if (rc) return rc;
+    const Sizes& z = plan->z;
+    ThresholdWorkspace ws = carve_threshold(workspace, z, W, n_lead, max_pairs);
+    rc = check_ws(ws.bytes, workspace, workspace_bytes);
+    if (rc) return rc;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    uint32_t* mask32 = reinterpret_cast<uint32_t*>(mask_out);
+    const DevLayer* layers = plan->dev;
+    if (z.tiles) {
+        IWP_LAUNCH("k_leader_mask", k_leader_mask, n_lead * z.tiles, s, P, w, layers, z.n_layers, z.tiles, leaders, n_lead, W,
+                   thr, eps, ws.lmask, z.mask_words);
+        IWP_LAUNCH("k_mask_or_count", k_mask_or_count, z.stiles, s, layers, z.n_layers, leaders, n_lead, W, ws.lmask,
+                   z.mask_words, mask32, ws.tile_counts, ws.stile_counts);
+    }
+    IWP_LAUNCH("k_scan", k_scan, z.n_layers, s, layers, ws.stile_counts, true, ws.layer_total);
+    IWP_LAUNCH("k_layer_offsets", k_layer_offsets, 1u, s, ws.layer_total, z.n_layers, max_pairs, ws.lay_out, count_out);
+    if (z.tiles == 0) return IWP_OK;
+    IWP_LAUNCH("k_mask_emit", k_mask_emit, (z.tiles + 3) / 4, s, layers, z.n_layers, z.tiles, mask32, ws.tile_counts,
+               ws.stile_counts, ws.lay_out, count_out, max_pairs, ws.tile_out, idx_out);
+    IWP_LAUNCH("k_follow_mask", k_follow_mask, W * z.tiles, s, P, layers, z.n_layers, z.tiles, leaders, n_lead, W, mask32,
+               ws.tile_out, ws.lay_out, count_out, max_pairs, ws.gathered);
+    const uint32_t pair_blocks = (max_pairs + BLOCK - 1) / BLOCK;
+    {
+        TimedLaunch tl_("k_gather_pairs", s);
+        k_gather_pairs<<<dim3(pair_blocks, W), BLOCK, 0, s>>>(P, layers, z.n_layers, leaders, n_lead, W, ws.lay_out,
+                                                              count_out, max_pairs, idx_out, ws.gathered,
+                                                              plan->flat_end);
+    }
+    {
+        hipError_t e_ = hipGetLastError();
+        if (e_ != hipSuccess) return hip_fail(e_, "k_gather_pairs");
+    }
+    IWP_LAUNCH("k_reduce_update_counted", k_reduce_update_counted, pair_blocks, s, ws.gathered, W, max_pairs, count_out,
+               z.n_layers, idx_out, w, scale, sum_out, plan->flat_end);
+    return IWP_OK;
 }
 
 // ----------------------------------------------------------------- helpers

@@ -50,6 +50,8 @@ struct DevLayer {
     uint32_t tile_begin;   // first TILE of the layer in the per-worker tile numbering
     uint32_t stile_begin;  // first STILE of the layer
     uint32_t slot_cap;     // staging entries per tile of this layer
+    uint32_t mask_begin;   // first 32-bit word of the layer's encoded mask (threshold mode)
+    uint32_t pad;
 };
 
 struct LayerState {        // selection state of one layer, lives in the workspace

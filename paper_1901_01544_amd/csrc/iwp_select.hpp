@@ -345,11 +345,14 @@ __global__ __launch_bounds__(BLOCK) void k_count(ResidualPtrs R, const float* __
 
 // Part 2: exclusive prefix of the super-tile totals inside each layer, in order.
 // One workgroup per layer, eight consecutive super-tiles per lane and round.
-__global__ __launch_bounds__(BLOCK) void k_scan(const DevLayer* __restrict__ layers, uint2* __restrict__ stile_counts) {
+// every_layer: also layers with k == 0 (threshold mode has no k); layer_total (may be
+// NULL) receives the layer's first sum.
+__global__ __launch_bounds__(BLOCK) void k_scan(const DevLayer* __restrict__ layers, uint2* __restrict__ stile_counts,
+                                                bool every_layer, uint32_t* __restrict__ layer_total) {
     constexpr uint32_t PER = 8;
     __shared__ uint32_t slot_g[4], slot_e[4];
     const uint32_t j = blockIdx.x;
-    if (layers[j].k == 0) return;
+    if (layers[j].k == 0 && !every_layer) return;
     const uint32_t sb = layers[j].stile_begin;
     const uint32_t se = sb + (layers[j].n + STILE - 1) / STILE;
     uint32_t G = 0, E = 0;
@@ -376,6 +379,7 @@ __global__ __launch_bounds__(BLOCK) void k_scan(const DevLayer* __restrict__ lay
         E += tot_e;
         __syncthreads();
     }
+    if (layer_total && threadIdx.x == 0) layer_total[j] = G;
 }
 
 // Part 3: write the pairs.  An element above the threshold goes to position

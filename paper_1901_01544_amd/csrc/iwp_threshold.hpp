@@ -1,0 +1,374 @@
+// Threshold mode: the front end exactly as Algorithm 1 prints it.  Each of the
+// n_lead randomly chosen nodes of a layer marks the elements whose importance is
+// strictly above the layer's threshold (mask line; fixed thresholds, Section 4.1),
+// the masks are encoded one bit per element (encode_uint8: bit i%8 of byte i/8,
+// i.e. bit i%32 of little-endian word i/32; a layer's mask is a whole number of
+// words) and OR-ed, and every node splits its accumulated gradient by the common
+// mask (G~ / G lines).  The number of sent elements is data dependent, so the
+// layers' pairs are packed by a scan over device-resident counts.
+//
+// One look per chosen node (16 B/element), no selection at all; the other nodes
+// stream once and hand over / clear their masked values on the way, with the
+// 4096-bit tile mask taken straight from the encoded mask.
+#pragma once
+
+#include "iwp_common.hpp"
+
+namespace iwp {
+
+constexpr uint32_t MAX_LEAD = 8;                 // chosen nodes per layer
+
+// The node in slot q of layer j (out-of-range entries read as node 0).
+__device__ __forceinline__ uint32_t chosen_at(const uint32_t* __restrict__ leaders, uint32_t n_lead, uint32_t j,
+                                              uint32_t q, uint32_t W) {
+    const uint32_t l = leaders[(size_t)j * n_lead + q];
+    return l < W ? l : 0u;
+}
+
+// Is node p among the first `upto` chosen nodes of layer j?
+__device__ __forceinline__ bool chosen_before(const uint32_t* __restrict__ leaders, uint32_t n_lead, uint32_t j,
+                                              uint32_t upto, uint32_t W, uint32_t p) {
+    for (uint32_t q = 0; q < upto; ++q)
+        if (chosen_at(leaders, n_lead, j, q, W) == p) return true;
+    return false;
+}
+
+// Status words at the end of count_out: [n_layers] = total pairs, [n_layers + 1] = 1 if
+// the total exceeds the caller's capacity (then nothing is exchanged).
+__device__ __forceinline__ bool overflowed(const uint32_t* __restrict__ count_out, uint32_t n_layers) {
+    return count_out[n_layers + 1] != 0u;
+}
+
+// ---------------------------------------------------------------------------
+// Chosen nodes: accumulate, score, compare, encode.  Grid: n_lead * tiles.  A node
+// that appears in an earlier slot of the same layer is skipped (same mask).
+// lmask: n_lead masks of mask_words words each, laid out like the final mask.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(BLOCK) void k_leader_mask(WorkerPtrs P, const float* __restrict__ w,
+                                                       const DevLayer* __restrict__ layers, uint32_t n_layers,
+                                                       uint32_t tiles, const uint32_t* __restrict__ leaders,
+                                                       uint32_t n_lead, uint32_t W, const float* __restrict__ thr,
+                                                       float eps, uint32_t* __restrict__ lmask, uint64_t mask_words) {
+    const uint32_t tid = threadIdx.x, lane = tid & (WAVE - 1);
+    const uint32_t q = blockIdx.x / tiles;
+    const uint32_t t = blockIdx.x - q * tiles;
+    const uint32_t j = find_layer<false>(layers, n_layers, t);
+    const DevLayer L = layers[j];
+    const uint32_t p = chosen_at(leaders, n_lead, j, q, W);
+    if (chosen_before(leaders, n_lead, j, q, W, p)) return;
+    const uint32_t lt = t - L.tile_begin;
+    const uint32_t base = lt * TILE;
+    const float* gp = P.g[p];
+    float* rl = P.r[p] + L.offset;
+    const float* gl = gp ? gp + L.offset : nullptr;
+    const float* wl = w + L.offset;
+    const bool vec = is_aligned16(rl) && is_aligned16(wl) && (!gp || is_aligned16(gl));
+    const float th = thr[j];
+    const uint32_t nwords = (L.n + 31) / 32;
+    uint32_t* mw = lmask + (size_t)q * mask_words + L.mask_begin;
+    float rv[CHUNKS_PER_TILE][4], wv[CHUNKS_PER_TILE][4];
+    if (vec && base + TILE <= L.n) {
+        v4f rr[CHUNKS_PER_TILE], gg[CHUNKS_PER_TILE], ww[CHUNKS_PER_TILE];
+#pragma unroll
+        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+            const uint32_t i = base + u * CHUNK + tid * VEC;
+            rr[u] = load_v4<true>(rl + i);
+            if (gp) gg[u] = load_v4<true>(gl + i);
+            ww[u] = load_v4<true>(wl + i);
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+            const uint32_t i = base + u * CHUNK + tid * VEC;
+            if (gp) {
+                rr[u] = rr[u] + gg[u];
+                store_v4<true>(rl + i, rr[u]);
+            }
+            rv[u][0] = rr[u].x; rv[u][1] = rr[u].y; rv[u][2] = rr[u].z; rv[u][3] = rr[u].w;
+            wv[u][0] = ww[u].x; wv[u][1] = ww[u].y; wv[u][2] = ww[u].z; wv[u][3] = ww[u].w;
+        }
+    } else {
+#pragma unroll
+        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+            const uint32_t i = base + u * CHUNK + tid * VEC;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) { rv[u][c] = 0.0f; wv[u][c] = 1.0f; }
+            if (i < L.n) {
+                load_quad(rl, i, L.n, vec, rv[u]);
+                if (gp) {
+                    float gv[4];
+                    load_quad(gl, i, L.n, vec, gv);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) rv[u][c] = rv[u][c] + gv[c];
+                    store_quad(rl, i, L.n, vec, rv[u]);
+                }
+                load_quad(wl, i, L.n, vec, wv[u], 1.0f);
+            }
+        }
+    }
+#pragma unroll
+    for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+        const uint32_t i = base + u * CHUNK + tid * VEC;
+        uint32_t nib = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const float s = fabsf(rv[u][c]) / (fabsf(wv[u][c]) + eps);
+            if (i + c < L.n && s > th) nib |= 1u << c;
+        }
+        // eight lanes (32 consecutive elements) make one word of the encoded mask
+        uint32_t word = nib << (4u * (lane & 7u));
+        word |= __shfl_xor(word, 1, WAVE);
+        word |= __shfl_xor(word, 2, WAVE);
+        word |= __shfl_xor(word, 4, WAVE);
+        const uint32_t widx = lt * TILE_WORDS + u * (CHUNK / 32) + (tid >> 3);
+        if ((lane & 7u) == 0u && widx < nwords) mw[widx] = word;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// OR of the chosen nodes' masks -> the layer's mask (an output), and how many bits
+// each tile holds.  One workgroup per super-tile, one wavefront per tile.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(BLOCK) void k_mask_or_count(const DevLayer* __restrict__ layers, uint32_t n_layers,
+                                                         const uint32_t* __restrict__ leaders, uint32_t n_lead,
+                                                         uint32_t W, const uint32_t* __restrict__ lmask,
+                                                         uint64_t mask_words, uint32_t* __restrict__ mask_out,
+                                                         uint2* __restrict__ tile_counts,
+                                                         uint2* __restrict__ stile_counts) {
+    __shared__ uint32_t cg[GROUP];
+    const uint32_t tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid >> 6;
+    const uint32_t s = blockIdx.x;
+    const uint32_t j = find_layer<true>(layers, n_layers, s);
+    const DevLayer L = layers[j];
+    const uint32_t ntiles = (L.n + TILE - 1) / TILE;
+    const uint32_t nwords = (L.n + 31) / 32;
+    const uint32_t lt0 = (s - L.stile_begin) * GROUP;
+    const uint32_t nt = min(GROUP, ntiles - lt0);
+    for (uint32_t tl = wave; tl < nt; tl += BLOCK / WAVE) {
+        uint32_t c = 0;
+#pragma unroll
+        for (uint32_t h = 0; h < 2; ++h) {
+            const uint32_t widx = (lt0 + tl) * TILE_WORDS + 2 * lane + h;
+            if (widx < nwords) {
+                uint32_t wd = 0;
+                for (uint32_t q = 0; q < n_lead; ++q) {
+                    const uint32_t p = chosen_at(leaders, n_lead, j, q, W);
+                    if (!chosen_before(leaders, n_lead, j, q, W, p)) wd |= lmask[(size_t)q * mask_words + L.mask_begin + widx];
+                }
+                mask_out[L.mask_begin + widx] = wd;
+                c += __popc(wd);
+            }
+        }
+#pragma unroll
+        for (int d = WAVE / 2; d > 0; d >>= 1) c += __shfl_xor(c, d, WAVE);
+        if (lane == 0) cg[tl] = c;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t G = 0;
+        for (uint32_t tl = 0; tl < nt; ++tl) {
+            tile_counts[L.tile_begin + lt0 + tl] = make_uint2(G, 0u);
+            G += cg[tl];
+        }
+        stile_counts[s] = make_uint2(G, 0u);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Layer totals -> where each layer's pairs start in the packed outputs, the counts
+// the caller sees, and the capacity check.  One workgroup.
+// lay_out[j] = first pair of layer j, lay_out[n_layers] = total.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(BLOCK) void k_layer_offsets(const uint32_t* __restrict__ layer_total, uint32_t n_layers,
+                                                         uint32_t max_pairs, uint32_t* __restrict__ lay_out,
+                                                         uint32_t* __restrict__ count_out) {
+    __shared__ uint32_t slot[4];
+    uint32_t carry = 0;
+    for (uint32_t b = 0; b < n_layers; b += BLOCK) {
+        const uint32_t j = b + threadIdx.x;
+        const uint32_t v = j < n_layers ? layer_total[j] : 0u;
+        uint32_t tot;
+        const uint32_t ex = block_exclusive_scan(v, slot, &tot);
+        if (j < n_layers) {
+            lay_out[j] = carry + ex;
+            count_out[j] = v;
+        }
+        carry += tot;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        lay_out[n_layers] = carry;
+        count_out[n_layers] = carry;
+        count_out[n_layers + 1] = carry > max_pairs ? 1u : 0u;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// The masked positions as ascending flat indices, layers packed in table order.
+// One wavefront per tile; tile_out[t] = first pair of the tile inside its layer.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(BLOCK) void k_mask_emit(const DevLayer* __restrict__ layers, uint32_t n_layers,
+                                                     uint32_t tiles_total, const uint32_t* __restrict__ mask,
+                                                     const uint2* __restrict__ tile_counts,
+                                                     const uint2* __restrict__ stile_counts,
+                                                     const uint32_t* __restrict__ lay_out,
+                                                     const uint32_t* __restrict__ count_out, uint32_t max_pairs,
+                                                     uint32_t* __restrict__ tile_out, uint32_t* __restrict__ idx_out) {
+    const uint32_t lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x >> 6;
+    const uint32_t t = blockIdx.x * (BLOCK / WAVE) + wave;
+    if (t >= tiles_total) return;
+    const uint32_t j = find_layer<false>(layers, n_layers, t);
+    const DevLayer L = layers[j];
+    const uint32_t lt = t - L.tile_begin;
+    const uint32_t in_layer = stile_counts[L.stile_begin + lt / GROUP].x + tile_counts[t].x;
+    if (lane == 0) tile_out[t] = in_layer;
+    if (overflowed(count_out, n_layers)) return;
+    const uint32_t nwords = (L.n + 31) / 32;
+    uint32_t wd[2];
+#pragma unroll
+    for (uint32_t h = 0; h < 2; ++h) {
+        const uint32_t widx = lt * TILE_WORDS + 2 * lane + h;
+        wd[h] = widx < nwords ? mask[L.mask_begin + widx] : 0u;
+    }
+    const uint32_t c = __popc(wd[0]) + __popc(wd[1]);
+    uint32_t pos = lay_out[j] + in_layer + wave_inclusive_scan(c) - c;
+    const uint32_t first = (uint32_t)L.offset + lt * TILE + 2 * lane * 32;
+#pragma unroll
+    for (uint32_t h = 0; h < 2; ++h) {
+        uint32_t m = wd[h];
+        while (m) {
+            const uint32_t b = __ffs(m) - 1;
+            if (pos < max_pairs) idx_out[pos] = first + h * 32 + b;
+            ++pos;
+            m &= m - 1;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Every node that is not chosen for the layer and has a gradient: accumulate, and
+// where the tile's mask has bits, copy the accumulated value into the node's gather
+// row and leave +0 behind.  Grid: W * tiles.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(BLOCK) void k_follow_mask(WorkerPtrs P, const DevLayer* __restrict__ layers,
+                                                       uint32_t n_layers, uint32_t tiles,
+                                                       const uint32_t* __restrict__ leaders, uint32_t n_lead, uint32_t W,
+                                                       const uint32_t* __restrict__ mask,
+                                                       const uint32_t* __restrict__ tile_out,
+                                                       const uint32_t* __restrict__ lay_out,
+                                                       const uint32_t* __restrict__ count_out, uint32_t max_pairs,
+                                                       float* __restrict__ gathered) {
+    __shared__ uint32_t map[TILE_WORDS], pre[TILE_WORDS], slot[4];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t p = blockIdx.x / tiles;
+    const uint32_t t = blockIdx.x - p * tiles;
+    const uint32_t j = find_layer<false>(layers, n_layers, t);
+    const DevLayer L = layers[j];
+    const float* gp = P.g[p];
+    if (!gp || chosen_before(leaders, n_lead, j, n_lead, W, p)) return;   // chosen / static nodes: pair by pair later
+    const uint32_t lt = t - L.tile_begin;
+    const uint32_t base = lt * TILE;
+    float* rl = P.r[p] + L.offset;
+    const float* gl = gp + L.offset;
+    const bool vec = is_aligned16(rl) && is_aligned16(gl);
+    const bool full = vec && base + TILE <= L.n;
+    v4f rr[CHUNKS_PER_TILE], gg[CHUNKS_PER_TILE];
+    if (full) {
+#pragma unroll
+        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+            const uint32_t i = base + u * CHUNK + tid * VEC;
+            rr[u] = load_v4<true>(rl + i);
+            gg[u] = load_v4<true>(gl + i);
+        }
+    }
+    const bool exchange = !overflowed(count_out, n_layers);
+    const uint32_t nwords = (L.n + 31) / 32;
+    if (tid < TILE_WORDS) {
+        const uint32_t widx = lt * TILE_WORDS + tid;
+        map[tid] = (exchange && widx < nwords) ? mask[L.mask_begin + widx] : 0u;
+    }
+    __syncthreads();
+    bitmap_prefix(map, pre, slot);
+    const uint64_t row = (uint64_t)lay_out[j] + tile_out[t];
+    float* go = gathered + (size_t)p * max_pairs + min(row, (uint64_t)max_pairs);
+    const uint32_t room = (uint32_t)((uint64_t)max_pairs - min(row, (uint64_t)max_pairs));
+    if (full) {
+#pragma unroll
+        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+            const uint32_t loc = u * CHUNK + tid * VEC;
+            rr[u] = rr[u] + gg[u];
+            const uint32_t nib = (map[loc >> 5] >> (loc & 31u)) & 0xFu;
+            if (nib) {
+                uint32_t rank = bitmap_rank(map, pre, loc);
+                if (nib & 1u) { if (rank < room) go[rank] = rr[u].x; ++rank; rr[u].x = 0.0f; }
+                if (nib & 2u) { if (rank < room) go[rank] = rr[u].y; ++rank; rr[u].y = 0.0f; }
+                if (nib & 4u) { if (rank < room) go[rank] = rr[u].z; ++rank; rr[u].z = 0.0f; }
+                if (nib & 8u) { if (rank < room) go[rank] = rr[u].w; ++rank; rr[u].w = 0.0f; }
+            }
+            store_v4<true>(rl + base + loc, rr[u]);
+        }
+    } else {
+        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+            const uint32_t loc = u * CHUNK + tid * VEC;
+            const uint32_t i = base + loc;
+            if (i >= L.n) break;
+            float rv[4], gv[4];
+            load_quad(rl, i, L.n, vec, rv);
+            load_quad(gl, i, L.n, vec, gv);
+            const uint32_t nib = (map[loc >> 5] >> (loc & 31u)) & 0xFu;
+            uint32_t rank = nib ? bitmap_rank(map, pre, loc) : 0u;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                rv[q] = rv[q] + gv[q];
+                if ((nib >> q) & 1u) { if (rank < room) go[rank] = rv[q]; ++rank; rv[q] = 0.0f; }
+            }
+            store_quad(rl, i, L.n, vec, rv);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// The nodes the streaming pass left out (chosen for the pair's layer, or without a
+// gradient): value fetched and cleared pair by pair.  Grid: (max_pairs / 256, W).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(BLOCK) void k_gather_pairs(WorkerPtrs P, const DevLayer* __restrict__ layers,
+                                                        uint32_t n_layers, const uint32_t* __restrict__ leaders,
+                                                        uint32_t n_lead, uint32_t W,
+                                                        const uint32_t* __restrict__ lay_out,
+                                                        const uint32_t* __restrict__ count_out, uint32_t max_pairs,
+                                                        const uint32_t* __restrict__ idx, float* __restrict__ gathered,
+                                                        uint64_t flat_end) {
+    const uint32_t jj = blockIdx.x * BLOCK + threadIdx.x;
+    if (overflowed(count_out, n_layers) || jj >= count_out[n_layers]) return;
+    const uint32_t p = blockIdx.y;
+    uint32_t lo = 0, hi = n_layers;              // layer of pair jj: last layer with lay_out <= jj
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (lay_out[mid] <= jj) lo = mid; else hi = mid;
+    }
+    if (P.g[p] && !chosen_before(leaders, n_lead, lo, n_lead, W, p)) return;   // done while streaming
+    const uint32_t i = idx[jj];
+    if (i >= flat_end) return;
+    gathered[(size_t)p * max_pairs + jj] = P.r[p][i];
+    P.r[p][i] = 0.0f;
+}
+
+// Ordered sum over the W gather rows and the weight update, for a pair count that
+// lives on the device.
+__global__ __launch_bounds__(BLOCK) void k_reduce_update_counted(const float* __restrict__ gathered, uint32_t W,
+                                                                 uint32_t max_pairs,
+                                                                 const uint32_t* __restrict__ count_out,
+                                                                 uint32_t n_layers, const uint32_t* __restrict__ idx,
+                                                                 float* __restrict__ w, float scale,
+                                                                 float* __restrict__ sum_out, uint64_t flat_end) {
+    const uint32_t jj = blockIdx.x * BLOCK + threadIdx.x;
+    if (overflowed(count_out, n_layers) || jj >= count_out[n_layers]) return;
+    float acc = gathered[jj];
+    for (uint32_t p = 1; p < W; ++p) acc = acc + gathered[(size_t)p * max_pairs + jj];
+    sum_out[jj] = acc;
+    const uint32_t i = idx[jj];
+    if (i >= flat_end) return;
+    const float t = scale * acc;
+    w[i] = w[i] + t;
+}
+
+}  // namespace iwp

@@ -61,6 +61,14 @@ def load() -> C.CDLL:
     L.iwp_step_segmented.argtypes = [_vp, _vp, C.POINTER(_vp), C.POINTER(_vp), C.c_uint32, _vp, _vp, C.c_float,
                                      C.c_float, _vp, _vp, _vp, _vp, _vp, C.c_size_t, _vp]
     L.iwp_step_segmented.restype = C.c_int
+    L.iwp_plan_mask_bytes.argtypes = [_vp]
+    L.iwp_plan_mask_bytes.restype = C.c_size_t
+    L.iwp_plan_threshold_workspace_bytes.argtypes = [_vp, C.c_uint32, C.c_uint32, C.c_uint32]
+    L.iwp_plan_threshold_workspace_bytes.restype = C.c_size_t
+    L.iwp_step_threshold_segmented.argtypes = [_vp, _vp, C.POINTER(_vp), C.POINTER(_vp), C.c_uint32, _vp, C.c_uint32,
+                                               _vp, C.c_float, C.c_float, _vp, _vp, _vp, _vp, C.c_uint32, _vp,
+                                               C.c_size_t, _vp]
+    L.iwp_step_threshold_segmented.restype = C.c_int
     L.iwp_plan_total_pairs.argtypes = [_vp]
     L.iwp_plan_total_pairs.restype = C.c_uint64
     L.compress_segmented.argtypes = [_vp, _vp, C.POINTER(_vp), C.POINTER(_vp), C.c_uint32, _vp, _vp, C.c_float,
@@ -175,6 +183,13 @@ class Plan:
     def step_workspace_bytes(self, W: int) -> int:
         return int(load().iwp_plan_step_workspace_bytes(self._h, W))
 
+    @property
+    def mask_bytes(self) -> int:
+        return int(load().iwp_plan_mask_bytes(self._h))
+
+    def threshold_workspace_bytes(self, W: int, n_lead: int, max_pairs: int) -> int:
+        return int(load().iwp_plan_threshold_workspace_bytes(self._h, W, n_lead, max_pairs))
+
     def close(self):
         if getattr(self, "_h", None):
             load().iwp_plan_destroy(self._h)
@@ -205,6 +220,17 @@ def step_segmented(plan: Plan, w, g: Sequence, r: Sequence, leader, eps: float, 
                                      _ptr(thr_hint), eps, scale,
                                      _ptr(idx_out), _ptr(val_out), _ptr(sum_out), _ptr(thr_out), _ptr(workspace),
                                      ws_bytes, _stream(stream)), "iwp_step_segmented")
+
+
+def step_threshold_segmented(plan: Plan, w, g: Sequence, r: Sequence, leaders, n_lead: int, thr, eps: float,
+                             scale: float, mask_out, count_out, idx_out, sum_out, max_pairs: int, workspace,
+                             stream=None):
+    assert len(g) == len(r)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().iwp_step_threshold_segmented(plan._h, _ptr(w), _ptr_table(g), _ptr_table(r), len(r), _ptr(leaders),
+                                               n_lead, _ptr(thr), eps, scale, _ptr(mask_out), _ptr(count_out),
+                                               _ptr(idx_out), _ptr(sum_out), max_pairs, _ptr(workspace), ws_bytes,
+                                               _stream(stream)), "iwp_step_threshold_segmented")
 
 
 def select_threshold_segmented(plan: Plan, w, r, eps: float, thr_out, workspace, stream=None):

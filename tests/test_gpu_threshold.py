@@ -1,0 +1,253 @@
+"""GPU parity of the threshold mode (the front end as Algorithm 1 prints it: fixed
+per-layer threshold, strict compare, bit-per-element masks OR-ed over the chosen
+nodes) against the CPU oracle, through the C ABI, bit for bit: encoded mask,
+per-layer counts, index list, sums, weights and every residual buffer."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1901_01544_amd import workloads as wl
+from harness import bits
+
+pytestmark = pytest.mark.gpu
+EPS = 1e-8
+
+
+class ThresholdSet:
+    def __init__(self, iwp, ps, w_np, grads_np, r_np, n_lead, max_pairs):
+        import torch
+        self.torch, self.iwp, self.ps = torch, iwp, ps
+        dev = "cuda:0"
+        self.W = len(r_np)
+        self.w = torch.from_numpy(w_np).to(dev)
+        self.grads = [torch.from_numpy(g).to(dev) for g in grads_np]
+        self.r = [torch.from_numpy(x).to(dev) for x in r_np]
+        self.plan = iwp.Plan(ps.rows())
+        self.n_lead, self.max_pairs = n_lead, max_pairs
+        nl = len(ps.layers)
+        self.mask = torch.full((max(4, self.plan.mask_bytes),), 0xAA, dtype=torch.uint8, device=dev)
+        self.count = torch.full((nl + 2,), -1, dtype=torch.int32, device=dev)
+        self.idx = torch.full((max_pairs + 8,), -1, dtype=torch.int32, device=dev)
+        self.sum = torch.full((max_pairs + 8,), float("nan"), dtype=torch.float32, device=dev)
+        self.ws = torch.empty(max(1, self.plan.threshold_workspace_bytes(self.W, n_lead, max_pairs)),
+                              dtype=torch.uint8, device=dev)
+        self.leaders = torch.zeros(nl * n_lead, dtype=torch.int32, device=dev)
+        self.thr = torch.zeros(nl, dtype=torch.float32, device=dev)
+
+    def step(self, g_ids, leaders_np, thr_np, scale):
+        t = self.torch
+        self.idx.fill_(-1)
+        self.sum.fill_(float("nan"))
+        self.leaders.copy_(t.from_numpy(np.ascontiguousarray(leaders_np, np.uint32).view(np.int32).ravel()))
+        self.thr.copy_(t.from_numpy(np.ascontiguousarray(thr_np, np.float32)))
+        g = [None if i is None else self.grads[i] for i in g_ids]
+        self.iwp.step_threshold_segmented(self.plan, self.w, g, self.r, self.leaders, self.n_lead, self.thr, EPS,
+                                          float(scale), self.mask, self.count, self.idx, self.sum, self.max_pairs,
+                                          self.ws)
+        t.cuda.synchronize()
+
+    def download(self):
+        nl = len(self.ps.layers)
+        return dict(mask=self.mask.cpu().numpy()[:self.plan.mask_bytes],
+                    count=self.count.cpu().numpy().view(np.uint32),
+                    idx=self.idx.cpu().numpy().view(np.uint32), sum=self.sum.cpu().numpy(),
+                    w=self.w.cpu().numpy(), r=[x.cpu().numpy() for x in self.r], nl=nl)
+
+
+def _leaders(rng, n_layers, n_lead, W, wild=False):
+    L = rng.integers(0, W, size=(n_layers, n_lead)).astype(np.uint32)
+    if wild and n_layers:
+        L[rng.integers(0, n_layers)] = L[0, 0]                  # a node listed several times
+        L[rng.integers(0, n_layers), rng.integers(0, n_lead)] = W + 5   # out of range: reads as node 0
+    return L
+
+
+def _thr_for(w, r_list, g_list, ps, density, rng):
+    """Per-layer thresholds near the requested density of worker 0's accumulated scores,
+    with some layers at exactly a score value (strictness), at 0 and above everything."""
+    thr = np.zeros(len(ps.layers), np.float32)
+    for j, L in enumerate(ps.layers):
+        if L.n == 0:
+            continue
+        sl = slice(L.offset, L.offset + L.n)
+        s = np.abs(r_list[0][sl] + (g_list[0][sl] if g_list[0] is not None else 0)).astype(np.float32) / \
+            (np.abs(w[sl]) + np.float32(EPS))
+        srt = np.sort(s)[::-1]
+        kk = min(L.n - 1, max(0, int(round(density * L.n))))
+        thr[j] = srt[kk]                                        # exactly a score: that element is NOT sent
+        mode = rng.integers(0, 8)
+        if mode == 0:
+            thr[j] = 0.0                                        # every non-zero residual
+        elif mode == 1:
+            thr[j] = np.float32(3e38)                           # nothing
+    return thr
+
+
+def _run_case(iwp, ps, W, n_lead, steps, density, seed, static=(), slack=8, wild=True, align_msg=""):
+    rng = np.random.default_rng(seed)
+    w = wl.gen_weights(ps)
+    pool = [wl.gen_gradient(ps, s) for s in range(3)]
+    r0 = [(rng.standard_t(3, ps.flat) * 1e-3).astype(np.float32) for _ in range(W)]
+    for p in range(W):
+        r0[p][rng.random(ps.flat) < 0.05] = 0.0
+    w_ref, r_ref = w.copy(), [x.copy() for x in r0]
+    # capacity: generous, the oracle tells the real totals
+    max_pairs = max(16, int(ps.flat) + slack)
+    ts = ThresholdSet(iwp, ps, w, pool, r0, n_lead, max_pairs)
+    rows = ps.rows()
+    for t in range(steps):
+        g_ids = [None if p in static else (p + t) % len(pool) for p in range(W)]
+        g_np = [None if i is None else pool[i] for i in g_ids]
+        leaders = _leaders(rng, len(ps.layers), n_lead, W, wild)
+        thr = _thr_for(w_ref, r_ref, g_np, ps, density, rng)
+        scale = np.float32(-0.01 / W)
+        zero = np.zeros(1, np.float32)
+        mask_ref, cnt_ref, idx_ref, sum_ref = oracle.step_threshold(
+            w_ref, [g if g is not None else zero for g in g_np], r_ref, rows, np.where(leaders >= W, 0, leaders), thr,
+            EPS, float(scale),
+            max_pairs, accumulate_mask=[g is not None for g in g_np])
+        ts.step(g_ids, leaders, thr, scale)
+        got = ts.download()
+        tag = "%s step %d" % (align_msg, t)
+        nl = got["nl"]
+        total = int(cnt_ref.sum())
+        assert np.array_equal(got["count"][:nl], cnt_ref), "%s counts %s vs %s" % (tag, got["count"][:nl], cnt_ref)
+        assert got["count"][nl] == total and got["count"][nl + 1] == 0, tag
+        assert np.array_equal(got["mask"], mask_ref), tag + " mask"
+        assert np.array_equal(got["idx"][:total], idx_ref), tag + " idx"
+        assert np.all(got["idx"][total:] == 0xFFFFFFFF), tag + " idx tail written"
+        assert np.array_equal(bits(got["sum"][:total]), bits(sum_ref)), tag + " sum"
+        assert np.all(np.isnan(got["sum"][total:])), tag + " sum tail written"
+        assert np.array_equal(bits(got["w"]), bits(w_ref)), tag + " w"
+        for p in range(W):
+            assert np.array_equal(bits(got["r"][p]), bits(r_ref[p])), "%s residual of worker %d" % (tag, p)
+    return ts, w_ref, r_ref
+
+
+RAGGED = [(1, 0), (31, 0), (32, 0), (33, 0), (0, 0), (4095, 0), (4096, 0), (4097, 0), (8 * 4096 + 5, 0),
+          (100_003, 0), (3 * 32768, 0), (7, 0)]
+
+
+@pytest.mark.parametrize("n_lead", [1, 2, 3])
+@pytest.mark.parametrize("align", [1, 64])
+def test_threshold_step_ragged_layers(gpu_lib, n_lead, align):
+    ps = wl.custom_set(RAGGED, W=4, seed=10 + n_lead, align=align, start=3 if align == 1 else 0, zero_frac=0.01)
+    _run_case(gpu_lib, ps, 4, n_lead, steps=3, density=0.01, seed=100 + n_lead, align_msg="align %d" % align)
+
+
+@pytest.mark.parametrize("density", [0.0005, 0.05, 0.6])
+def test_threshold_step_densities(gpu_lib, density):
+    ps = wl.custom_set([(300_000, 0), (50_000, 0), (1234, 0)], W=5, seed=3, align=64)
+    _run_case(gpu_lib, ps, 5, 2, steps=2, density=density, seed=7)
+
+
+def test_threshold_step_static_workers(gpu_lib):
+    """Workers without a gradient this step (chosen or not) take part in the exchange."""
+    ps = wl.custom_set([(70_000, 0), (9000, 0), (40_000, 0)], W=6, seed=4, align=64)
+    _run_case(gpu_lib, ps, 6, 3, steps=3, density=0.02, seed=8, static=(1, 4))
+
+
+def test_threshold_step_single_worker(gpu_lib):
+    ps = wl.custom_set([(20_000, 0), (5, 0)], W=1, seed=5, align=64)
+    _run_case(gpu_lib, ps, 1, 1, steps=2, density=0.03, seed=9, wild=False)
+
+
+def test_threshold_step_config1(gpu_lib):
+    """The small configuration of the benchmark table with the thresholds Section 4.1 names."""
+    ps = wl.make_config(1)
+    W = ps.W
+    rng = np.random.default_rng(21)
+    w = wl.gen_weights(ps)
+    pool = [wl.gen_gradient(ps, s) for s in range(2)]
+    r0 = [np.zeros(ps.flat, np.float32) for _ in range(W)]
+    w_ref, r_ref = w.copy(), [x.copy() for x in r0]
+    max_pairs = ps.flat
+    ts = ThresholdSet(gpu_lib, ps, w, pool, r0, 2, max_pairs)
+    rows = ps.rows()
+    choices = np.array([0.005, 0.01, 0.05, 0.1], np.float32)
+    for t in range(3):
+        g_ids = [(p + t) % 2 for p in range(W)]
+        leaders = _leaders(rng, len(ps.layers), 2, W)
+        thr = choices[rng.integers(0, 4, len(ps.layers))]
+        mask_ref, cnt_ref, idx_ref, sum_ref = oracle.step_threshold(
+            w_ref, [pool[i] for i in g_ids], r_ref, rows, leaders, thr, EPS, float(ps.scale), max_pairs)
+        ts.step(g_ids, leaders, thr, ps.scale)
+        got = ts.download()
+        total = int(cnt_ref.sum())
+        assert np.array_equal(got["count"][:got["nl"]], cnt_ref)
+        assert np.array_equal(got["mask"], mask_ref)
+        assert np.array_equal(got["idx"][:total], idx_ref)
+        assert np.array_equal(bits(got["sum"][:total]), bits(sum_ref))
+        assert np.array_equal(bits(got["w"]), bits(w_ref))
+        for p in range(W):
+            assert np.array_equal(bits(got["r"][p]), bits(r_ref[p]))
+
+
+def test_threshold_step_capacity(gpu_lib):
+    """Capacity exactly the total: exchanged.  One less: flag set, workers accumulated,
+    mask and counts valid, nothing exchanged, updated or cleared."""
+    ps = wl.custom_set([(50_000, 0), (4097, 0), (20_000, 0)], W=3, seed=6, align=64)
+    rng = np.random.default_rng(11)
+    w = wl.gen_weights(ps)
+    pool = [wl.gen_gradient(ps, s) for s in range(3)]
+    r0 = [(rng.standard_t(3, ps.flat) * 1e-3).astype(np.float32) for _ in range(3)]
+    leaders = _leaders(rng, 3, 2, 3)
+    thr = _thr_for(w, r0, pool, ps, 0.02, np.random.default_rng(2))
+    thr[thr == 0] = 1.0
+    thr[thr > 1e30] = 1.0
+    rows = ps.rows()
+    w_ref, r_ref = w.copy(), [x.copy() for x in r0]
+    mask_ref, cnt_ref, idx_ref, sum_ref = oracle.step_threshold(w_ref, pool, r_ref, rows, leaders, thr, EPS, -0.01,
+                                                                ps.flat)
+    total = int(cnt_ref.sum())
+    assert total > 100
+    # exact fit
+    ts = ThresholdSet(gpu_lib, ps, w, pool, r0, 2, total)
+    ts.step([0, 1, 2], leaders, thr, -0.01)
+    got = ts.download()
+    assert got["count"][3] == total and got["count"][4] == 0
+    assert np.array_equal(got["idx"][:total], idx_ref) and np.all(got["idx"][total:] == 0xFFFFFFFF)
+    assert np.array_equal(bits(got["sum"][:total]), bits(sum_ref))
+    assert np.array_equal(bits(got["w"]), bits(w_ref))
+    for p in range(3):
+        assert np.array_equal(bits(got["r"][p]), bits(r_ref[p]))
+    # one short
+    ts = ThresholdSet(gpu_lib, ps, w, pool, r0, 2, total - 1)
+    ts.step([0, 1, 2], leaders, thr, -0.01)
+    got = ts.download()
+    assert got["count"][3] == total and got["count"][4] == 1
+    assert np.array_equal(got["count"][:3], cnt_ref)
+    assert np.array_equal(got["mask"], mask_ref)
+    assert np.all(got["idx"] == 0xFFFFFFFF) and np.all(np.isnan(got["sum"]))
+    assert np.array_equal(bits(got["w"]), bits(w))
+    for p in range(3):
+        acc = r0[p].copy()
+        oracle.accumulate(acc, pool[p])
+        assert np.array_equal(bits(got["r"][p]), bits(acc))
+
+
+def test_threshold_argument_checks(gpu_lib):
+    import torch
+    iwp = gpu_lib
+    ps = wl.custom_set([(1000, 0)], W=2, seed=1, align=64)
+    plan = iwp.Plan(ps.rows())
+    d = "cuda:0"
+    w = torch.zeros(ps.flat, device=d)
+    r = [torch.zeros(ps.flat, device=d) for _ in range(2)]
+    leaders = torch.zeros(9, dtype=torch.int32, device=d)
+    thr = torch.zeros(1, device=d)
+    mask = torch.zeros(plan.mask_bytes, dtype=torch.uint8, device=d)
+    cnt = torch.zeros(3, dtype=torch.int32, device=d)
+    idx = torch.zeros(16, dtype=torch.int32, device=d)
+    sm = torch.zeros(16, device=d)
+    ws = torch.empty(plan.threshold_workspace_bytes(2, 1, 16), dtype=torch.uint8, device=d)
+    for n_lead in (0, 3, 9):                                    # 0, more than W, more than the limit
+        with pytest.raises(RuntimeError):
+            iwp.step_threshold_segmented(plan, w, [None, None], r, leaders, n_lead, thr, EPS, 1.0, mask, cnt, idx, sm,
+                                         16, ws)
+    with pytest.raises(RuntimeError):                           # workspace too small
+        iwp.step_threshold_segmented(plan, w, [None, None], r, leaders, 1, thr, EPS, 1.0, mask, cnt, idx, sm, 16,
+                                     ws[:64])
+    iwp.step_threshold_segmented(plan, w, [None, None], r, leaders, 1, thr, EPS, 1.0, mask, cnt, idx, sm, 16, ws)
+    torch.cuda.synchronize()
+    assert cnt.cpu().tolist() == [0, 0, 0]
