@@ -31,7 +31,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published peak HBM3E bandwidth
 WORKLOADS = {"tiny": 1, "alexnet": 2, "resnet50": 3, "many_small": 4, "flat": 5}
-DOMINANT_KERNEL = {"whole_step": "k_follow_gather", "three_calls": "k_accumulate_all"}
+DOMINANT_KERNEL = {"whole_step": "k_follow_gather", "three_calls": "k_accumulate_all", "threshold": "k_follow_mask"}
 
 
 def step_bytes(ps, W_acc, W_list):
@@ -52,6 +52,20 @@ def dominant_kernel_bytes(ps, W_acc, W_list, route):
     return 12 * (W_acc - 1) * ps.P + (4 + 4 * (W_list - 1)) * ps.K
 
 
+def threshold_step_bytes(ps, W_acc, W_list, n_lead, pairs):
+    """Threshold mode: W_acc workers accumulate (12 B/elem), each chosen node also reads
+    w (4 B/elem), the encoded mask goes out once (1 bit/elem), and per sent pair the
+    same exchange floor as above (index out and in, sum out, weight read-modify-write,
+    W gathers and clears)."""
+    return (12 * W_acc + 4 * n_lead) * ps.P + ps.P / 8 + (8 + 12 + 8 * W_list) * pairs
+
+
+def threshold_dominant_bytes(ps, W_acc, W_list, n_lead, pairs):
+    """k_follow_mask: the W_acc - n_lead workers that are not chosen accumulate
+    (12 B/elem), read the mask once (1 bit/elem) and hand over 4 B per pair each."""
+    return 12 * (W_acc - n_lead) * ps.P + ps.P / 8 + 4 * (W_acc - n_lead) * pairs
+
+
 def traffic_from_profiles(workload, kernel):
     """HBM bytes per launch of the dominant kernel from the committed counter runs
     (profiles/traffic.json), or None if no such measurement exists."""
@@ -69,9 +83,11 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="alexnet", choices=sorted(WORKLOADS))
-    ap.add_argument("--route", default="whole_step", choices=["whole_step", "three_calls"],
+    ap.add_argument("--route", default="whole_step", choices=["whole_step", "three_calls", "threshold"],
                     help="whole_step: iwp_step_segmented; three_calls: compress_segmented + gather_sum_at_indices "
-                         "+ apply_sparse_update (same results)")
+                         "+ apply_sparse_update (same results); threshold: iwp_step_threshold_segmented with fixed "
+                         "per-layer thresholds (calibrated by a few top-k steps to the same keep ratio)")
+    ap.add_argument("--n-lead", type=int, default=1, help="threshold route: chosen nodes per layer")
     ap.add_argument("--no-hint", action="store_true",
                     help="whole_step only: do not pass the previous step's thresholds as a hint (results are "
                          "identical either way; the hint saves the second pass over the leaders' layers)")
@@ -114,7 +130,10 @@ def main():
     gen_s = time.time() - t0
 
     plan = iwp.Plan(ps.rows())
-    fused = args.route == "whole_step"
+    fused = args.route in ("whole_step", "threshold")      # threshold: top-k whole steps calibrate the thresholds
+    thr_mode = args.route == "threshold"
+    assert not (thr_mode and flat_cfg), "the threshold route is measured on the multi-worker workloads"
+    n_lead = args.n_lead
     dominant = DOMINANT_KERNEL[args.route]
     ws_bytes = plan.step_workspace_bytes(W_list) if fused else plan.workspace_bytes
     ws = torch.empty(max(1, ws_bytes), dtype=torch.uint8, device=dev)
@@ -124,7 +143,8 @@ def main():
     thr2 = [torch.zeros(3 * len(ps.layers), dtype=torch.int32, device=dev) for _ in range(2)]   # ping-pong: the
     thr = thr2[0]                                     # records of step t-1 are the hint of step t
     use_hint = fused and not args.no_hint
-    total = args.warmup + args.steps
+    CAL = 8                                           # threshold route: top-k steps that settle the thresholds
+    total = args.warmup + args.steps + (CAL if thr_mode else 0)
     if flat_cfg:
         lead_np = np.zeros((total, 1), np.int32)
     else:
@@ -160,22 +180,52 @@ def main():
     copy_gbps = 2 * 4 * a.numel() * cnt / (ms * 1e-3) / 1e9
     del a, b
 
-    for t in range(args.warmup):
+    first = 0
+    pairs_per_step = ps.K
+    if thr_mode:
+        # fixed thresholds: the k-th largest importance of each layer after CAL top-k steps,
+        # so the mask keeps about the same share of every layer as the top-k route
+        for t in range(CAL):
+            step(t)
+        torch.cuda.synchronize()
+        first = CAL
+        fixed_thr = thr2[(CAL - 1) % 2].view(-1, 3)[:, 0].contiguous().view(torch.float32).clone()
+        max_pairs = min(ps.P, 8 * ps.K)
+        del ws
+        ws = torch.empty(plan.threshold_workspace_bytes(W_list, n_lead, max_pairs), dtype=torch.uint8, device=dev)
+        mask = torch.empty(plan.mask_bytes, dtype=torch.uint8, device=dev)
+        counts = torch.zeros(total, len(ps.layers) + 2, dtype=torch.int32, device=dev)
+        idx = torch.empty(max_pairs, dtype=torch.int32, device=dev)
+        sm = torch.empty(max_pairs, dtype=torch.float32, device=dev)
+        chosen = torch.from_numpy(np.stack([wl.chosen_nodes(ps, t, n_lead).astype(np.int32).ravel()
+                                            for t in range(total)])).to(dev)
+
+        def step(t):                                  # noqa: F811 -- the timed step of this route
+            g = [grads[wl.gradient_set_of(ps, p, t, pool)] for p in range(ps.W)]
+            iwp.step_threshold_segmented(plan, w, g, r, chosen[t], n_lead, fixed_thr, eps, scale, mask, counts[t],
+                                         idx, sm, max_pairs, ws, stream)
+
+    for t in range(first, first + args.warmup):
         step(t)
     torch.cuda.synchronize()
     iwp.timing_enable(dominant, args.steps)
     t0 = time.perf_counter()
-    for t in range(args.warmup, total):
+    for t in range(first + args.warmup, total):
         step(t)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     k_ms, k_cnt = iwp.timing_collect()
+    if thr_mode:
+        c = counts[first + args.warmup:].cpu().numpy()
+        assert not c[:, -1].any(), "pair capacity exceeded in %d timed steps" % int(c[:, -1].sum())
+        pairs_per_step = float(c[:, -2].mean())
+        pairs_minmax = [int(c[:, -2].min()), int(c[:, -2].max())]
 
     # the parts on their own, after the timed region (they change r and w further, which no longer matters):
     # (i) compression of one worker (accumulate + score + select + compact, every layer leads itself),
     # (ii) the exchange as the two separate calls over the K pairs the last step produced
     parts = {}
-    if not args.no_parts:
+    if not args.no_parts and not thr_mode:
         ws1 = torch.empty(max(1, plan.workspace_bytes), dtype=torch.uint8, device=dev)
         reps = 5
         def timed(fn):
@@ -211,8 +261,12 @@ def main():
 
     ms_per_step = elapsed * 1e3 / args.steps
     params_per_s = ps.P * args.steps / elapsed
-    algo_bytes = step_bytes(ps, W_acc, W_list)
-    dom_bytes = dominant_kernel_bytes(ps, W_acc, W_list, args.route)
+    if thr_mode:
+        algo_bytes = threshold_step_bytes(ps, W_acc, W_list, n_lead, pairs_per_step)
+        dom_bytes = threshold_dominant_bytes(ps, W_acc, W_list, n_lead, pairs_per_step)
+    else:
+        algo_bytes = step_bytes(ps, W_acc, W_list)
+        dom_bytes = dominant_kernel_bytes(ps, W_acc, W_list, args.route)
     dom_ms = k_ms / max(1, k_cnt)
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     out = {
@@ -229,7 +283,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": ps.name, "config_id": cfg, "tensors": len(ps.layers), "params": ps.P,
-                   "pairs_per_step": ps.K, "workers_accumulating": W_acc, "residual_list": W_list,
+                   "pairs_per_step": pairs_per_step, "workers_accumulating": W_acc, "residual_list": W_list,
                    "keep": "1/64" if cfg in (1, 2) else ("1/58.8" if cfg == 3 else ("U(0.5%,5%)" if cfg == 4 else "0.1%")),
                    "eps": eps, "gradient_pool": pool, "route": args.route,
                    "threshold_hint": "previous step" if use_hint else "none"},
@@ -255,7 +309,34 @@ def main():
         },
     }
 
-    if not args.no_cpu_baseline and not flat_cfg:
+    if thr_mode:
+        out["config"]["threshold_hint"] = "n/a"
+        out["config"]["chosen_nodes_per_layer"] = n_lead
+        out["config"]["thresholds"] = "fixed per layer: k-th largest importance after %d top-k steps" % CAL
+        out["config"]["pairs_per_step_min_max"] = pairs_minmax
+        out["config"]["pair_capacity"] = max_pairs
+    if not args.no_cpu_baseline and thr_mode:
+        import oracle
+        # the oracle's threshold-mode step from the state the GPU run ended in
+        w_ref = w.cpu().numpy()
+        r_ref = [x.cpu().numpy() for x in r]
+        thr_np = fixed_thr.cpu().numpy()
+        n_steps, spent = 0, 0.0
+        while n_steps < 1 or (spent < 10.0 and n_steps < args.steps):
+            t = total + n_steps
+            g = [grads_np[wl.gradient_set_of(ps, p, t, pool)] for p in range(ps.W)]
+            t1 = time.perf_counter()
+            oracle.step_threshold(w_ref, g, r_ref, ps.rows(), wl.chosen_nodes(ps, t, n_lead), thr_np, eps, scale,
+                                  ps.P)
+            spent += time.perf_counter() - t1
+            n_steps += 1
+        out["cpu_baseline"] = {
+            "value": ps.P * n_steps / spent, "unit": "params/s", "cores": 1, "kind": "oracle",
+            "sample": "%d whole threshold-mode step(s) of the same workload (all %d workers, all %d tensors), %.1f s"
+                      % (n_steps, ps.W, len(ps.layers), spent),
+            "host_cpus": os.cpu_count(),
+        }
+    elif not args.no_cpu_baseline and not flat_cfg:
         import oracle
         # the oracle as it stands, one host core, on a bounded sample: whole steps of the
         # same workload until ~10 s of CPU work have been spent (at least one step)

@@ -329,6 +329,15 @@ def leaders(ps: ParamSet, step: int, n_candidates: Optional[int] = None) -> np.n
     return np.array([_splitmix64(ps.seed ^ (step * L + j)) % W for j in range(L)], np.uint32)
 
 
+def chosen_nodes(ps: ParamSet, step: int, n_lead: int, n_candidates: Optional[int] = None) -> np.ndarray:
+    """Threshold mode: the n_lead randomly chosen nodes of Alg. 1 for every layer at
+    ``step``, shape (layers, n_lead); slot 0 is ``leaders``; a node may come up twice."""
+    W = ps.W if n_candidates is None else n_candidates
+    L = len(ps.layers)
+    return np.array([[_splitmix64((ps.seed ^ (step * L + j)) + 0x51ED270B * q) % W for q in range(n_lead)]
+                     for j in range(L)], np.uint32).reshape(L, n_lead)
+
+
 # --------------------------------------------------------------------------
 # device-side generation for the 1e9-element config (host generation of eleven
 # 4 GB buffers would take minutes); same laws, torch's seeded generator
