@@ -49,6 +49,8 @@ def dominant_kernel_bytes(ps, W_acc, W_list, route):
     index read (4 B) once per worker tile is counted once, + 4 B gathered out per worker."""
     if route == "three_calls":
         return (12 * W_acc + 4) * ps.P
+    if W_acc == 1:                                    # k_leader_pass: r, g, w in, r out
+        return 16 * ps.P
     return 12 * (W_acc - 1) * ps.P + (4 + 4 * (W_list - 1)) * ps.K
 
 
@@ -135,6 +137,8 @@ def main():
     assert not (thr_mode and flat_cfg), "the threshold route is measured on the multi-worker workloads"
     n_lead = args.n_lead
     dominant = DOMINANT_KERNEL[args.route]
+    if flat_cfg and args.route == "whole_step":
+        dominant = "k_leader_pass"                    # one accumulating worker: nothing follows, the leader's look dominates
     ws_bytes = plan.step_workspace_bytes(W_list) if fused else plan.workspace_bytes
     ws = torch.empty(max(1, ws_bytes), dtype=torch.uint8, device=dev)
     idx = torch.empty(ps.K, dtype=torch.int32, device=dev)

@@ -88,10 +88,20 @@ def lib():
         L.oracle_mask_indices.argtypes = [_u8p, C.c_uint64, _u32p]
         L.oracle_mask_indices.restype = C.c_uint64
         L.oracle_step_threshold.argtypes = [_f32p, C.POINTER(_f32p), C.POINTER(_f32p), _u8p, C.c_uint32,
-                                            C.POINTER(Layer), _u32p, C.c_uint32, _f32p, C.c_uint32, C.c_float,
-                                            C.c_float, _u8p, _u32p, _u32p, _f32p, C.c_uint64,
+                                            C.POINTER(Layer), _u32p, C.c_uint32, _f32p, C.c_uint32, C.c_uint32,
+                                            C.c_float, C.c_float, _u8p, _u32p, _u32p, _f32p, C.c_uint64,
                                             C.POINTER(C.c_uint64)]
         L.oracle_step_threshold.restype = C.c_int
+        _f64p = C.POINTER(C.c_double)
+        L.oracle_layer_stats.argtypes = [_f32p, _f32p, C.c_uint64, C.c_float, _f64p, _f64p]
+        L.oracle_layer_stats.restype = None
+        L.oracle_layerwise_threshold.argtypes = [C.c_double] * 5
+        L.oracle_layerwise_threshold.restype = C.c_float
+        L.oracle_step_layerwise.argtypes = [_f32p, C.POINTER(_f32p), C.POINTER(_f32p), _u8p, C.c_uint32,
+                                            C.POINTER(Layer), _u32p, C.c_uint32, C.c_double, C.c_double, C.c_double,
+                                            C.c_uint32, C.c_float, C.c_float, _f64p, _f32p, _u8p, _u32p, _u32p,
+                                            _f32p, C.c_uint64, C.POINTER(C.c_uint64)]
+        L.oracle_step_layerwise.restype = C.c_int
     return _lib
 
 
@@ -244,13 +254,16 @@ def step_threshold(w: np.ndarray, g: Sequence[np.ndarray], r: Sequence[np.ndarra
                    thr: np.ndarray, eps: float, scale: float, max_pairs: int,
                    accumulate_mask: Sequence[int] | None = None):
     """One whole threshold-mode step on flat host buffers; w and every r[p] are updated
-    in place.  leaders: (n_layers, n_lead) uint32; thr: (n_layers,) float32.
+    in place.  leaders: (n_layers, n_lead) uint32; thr: (n_layers,) float32, or
+    (n_layers, n_lead) float32 (2-D) for one threshold per chosen node.
     -> (mask bytes of all layers back to back, counts[n_layers], idx[total], sum[total])."""
     rows = list(rows)
     tab = layer_table(rows)
     W = len(r)
     leaders = np.ascontiguousarray(leaders, np.uint32).reshape(len(rows), -1)
     thr = np.ascontiguousarray(thr, np.float32)
+    per_slot = 1 if thr.size == leaders.size and thr.ndim == 2 else 0
+    assert per_slot or thr.size == len(rows)
     mask = np.zeros(sum(mask_bytes(int(n)) for (_, n, _, _) in rows), np.uint8)
     counts = np.zeros(len(rows), np.uint32)
     idx = np.empty(max_pairs, np.uint32)
@@ -260,8 +273,49 @@ def step_threshold(w: np.ndarray, g: Sequence[np.ndarray], r: Sequence[np.ndarra
     if accumulate_mask is not None:
         acc = (C.c_uint8 * W)(*[1 if a else 0 for a in accumulate_mask])
     rc = lib().oracle_step_threshold(_f32(w), _ptr_array(g), _ptr_array(r), acc, W, tab, _u32(leaders),
-                                     leaders.shape[1], _f32(thr), len(rows), C.c_float(eps), C.c_float(scale),
+                                     leaders.shape[1], _f32(thr), per_slot, len(rows), C.c_float(eps), C.c_float(scale),
                                      _u8(mask), _u32(counts), _u32(idx), _f32(sm), max_pairs, C.byref(total))
     if rc:
         raise ValueError("oracle_step_threshold: rc=%d" % rc)
     return mask, counts, idx[:total.value].copy(), sm[:total.value].copy()
+
+
+def layer_stats(w: np.ndarray, r: np.ndarray, eps: float):
+    """L1: (mean, population variance) of one node's importance over a layer, binary64."""
+    m, v = C.c_double(0), C.c_double(0)
+    lib().oracle_layer_stats(_f32(w), _f32(r), r.size, C.c_float(eps), C.byref(m), C.byref(v))
+    return m.value, v.value
+
+
+def layerwise_threshold(mean: float, var: float, alpha: float, beta: float, c: float) -> np.float32:
+    """L2: the threshold Eq. 4 derives from a layer's statistics."""
+    return np.float32(lib().oracle_layerwise_threshold(mean, var, alpha, beta, c))
+
+
+def step_layerwise(w: np.ndarray, g: Sequence[np.ndarray], r: Sequence[np.ndarray], rows, leaders: np.ndarray,
+                   alpha: float, beta: float, c: float, eps: float, scale: float, max_pairs: int,
+                   accumulate_mask: Sequence[int] | None = None):
+    """One whole step with layer-wise thresholds.
+    -> (stats[n_layers, n_lead, 2] float64, thr[n_layers, n_lead] float32, mask, counts, idx, sum)."""
+    rows = list(rows)
+    tab = layer_table(rows)
+    W = len(r)
+    leaders = np.ascontiguousarray(leaders, np.uint32).reshape(len(rows), -1)
+    n_lead = leaders.shape[1]
+    stats = np.zeros((len(rows), n_lead, 2), np.float64)
+    thr = np.zeros((len(rows), n_lead), np.float32)
+    mask = np.zeros(sum(mask_bytes(int(n)) for (_, n, _, _) in rows), np.uint8)
+    counts = np.zeros(len(rows), np.uint32)
+    idx = np.empty(max_pairs, np.uint32)
+    sm = np.empty(max_pairs, np.float32)
+    total = C.c_uint64(0)
+    acc = None
+    if accumulate_mask is not None:
+        acc = (C.c_uint8 * W)(*[1 if a else 0 for a in accumulate_mask])
+    rc = lib().oracle_step_layerwise(_f32(w), _ptr_array(g), _ptr_array(r), acc, W, tab, _u32(leaders), n_lead,
+                                     alpha, beta, c, len(rows), C.c_float(eps), C.c_float(scale),
+                                     stats.ctypes.data_as(C.POINTER(C.c_double)), _f32(thr), _u8(mask), _u32(counts),
+                                     _u32(idx), _f32(sm), max_pairs, C.byref(total))
+    if rc:
+        raise ValueError("oracle_step_layerwise: rc=%d" % rc)
+    return stats, thr, mask, counts, idx[:total.value].copy(), sm[:total.value].copy()

@@ -39,6 +39,15 @@
 //   T4  split on EVERY node        sent: R_p[i] for Mask[i], kept: the rest   (Alg. 1, G~ / G lines)
 //   then O5..O7 over the masked positions.
 //
+// Layer-wise threshold (Section 3.4, Eq. 4): the threshold of T1 is not given but derived,
+// per layer and per chosen node, from that node's importance values:
+//   L1  mean = (1/n) sum s[i],  var = (1/n) sum (s[i] - mean)^2  (population variance; the paper
+//       says only "mean and variance"), two passes in binary64 over the binary32 scores
+//   L2  ratio = var / mean;  thr = alpha + beta * ratio  if ratio > C,  else  alpha - beta * ratio
+//       (Eq. 4 prints the same condition on both branches; the prose after it raises the
+//       threshold for a large ratio and lowers it otherwise), binary64, rounded once to binary32
+//   then T1..T4 with each chosen node using its own threshold.
+//
 // Pins (tests/test_oracle_pins.py): brute-force rank count on tiny layers,
 // cardinality, exact conservation, the paper's 64x / 58.8x ratios as keep
 // fractions, numpy lexsort cross-check, threshold-mask equivalence with the
@@ -273,11 +282,12 @@ uint64_t oracle_mask_indices(const uint8_t* mask, uint64_t n, uint32_t* idx_out)
 // flat positions of all layers packed in table order and the reduced values, at most
 // max_pairs (returns -4 if there are more).  Every worker with accumulate[p] != 0
 // adds its gradient first; every worker is cleared at the masked positions.
+// thr_per_slot != 0: thr holds n_layers x n_lead values, one per chosen node.
 int oracle_step_threshold(float* w, const float* const* g, float* const* r, const uint8_t* accumulate, uint32_t W,
                           const oracle_layer* layers, const uint32_t* leaders, uint32_t n_lead,
-                          const float* thr, uint32_t n_layers, float eps, float scale, uint8_t* mask_out,
-                          uint32_t* count_out, uint32_t* idx_out, float* sum_out, uint64_t max_pairs,
-                          uint64_t* total_out) {
+                          const float* thr, uint32_t thr_per_slot, uint32_t n_layers, float eps, float scale,
+                          uint8_t* mask_out, uint32_t* count_out, uint32_t* idx_out, float* sum_out,
+                          uint64_t max_pairs, uint64_t* total_out) {
     uint64_t total = 0, mask_off = 0;
     for (uint32_t j = 0; j < n_layers; ++j) {
         const oracle_layer& L = layers[j];
@@ -292,7 +302,8 @@ int oracle_step_threshold(float* w, const float* const* g, float* const* r, cons
         for (uint32_t q = 0; q < n_lead; ++q) {
             const uint32_t lead = leaders[(size_t)j * n_lead + q];
             if (lead >= W) return -2;
-            oracle_mask_threshold(w + L.offset, r[lead] + L.offset, L.n, eps, thr[j], one.data());
+            const float t = thr_per_slot ? thr[(size_t)j * n_lead + q] : thr[j];
+            oracle_mask_threshold(w + L.offset, r[lead] + L.offset, L.n, eps, t, one.data());
             oracle_mask_or(mask, one.data(), nbytes);
         }
         std::vector<uint32_t> local(L.n);
@@ -308,6 +319,62 @@ int oracle_step_threshold(float* w, const float* const* g, float* const* r, cons
     oracle_gather_sum(rc_ptrs.data(), W, idx_out, total, sum_out);
     oracle_apply_sparse_update(w, idx_out, sum_out, total, scale, r, W);
     return 0;
+}
+
+
+// ------------------------------------------------------------------ layer-wise threshold
+
+// L1: mean and population variance of one node's importance values over a layer.
+void oracle_layer_stats(const float* w, const float* r, uint64_t n, float eps, double* mean_out, double* var_out) {
+    if (n == 0) { *mean_out = 0.0; *var_out = 0.0; return; }
+    std::vector<float> s(n);
+    oracle_score(w, r, n, eps, s.data());
+    double sum = 0.0;
+    for (uint64_t i = 0; i < n; ++i) sum += (double)s[i];
+    const double mean = sum / (double)n;
+    double m2 = 0.0;
+    for (uint64_t i = 0; i < n; ++i) {
+        const double d = (double)s[i] - mean;
+        m2 += d * d;
+    }
+    *mean_out = mean;
+    *var_out = m2 / (double)n;
+}
+
+// L2: the threshold Eq. 4 derives from the statistics.
+float oracle_layerwise_threshold(double mean, double var, double alpha, double beta, double C) {
+    const double ratio = var / mean;
+    const double t = ratio > C ? alpha + beta * ratio : alpha - beta * ratio;
+    return (float)t;
+}
+
+// One whole iteration with layer-wise thresholds: accumulate, L1 + L2 on every chosen node
+// (stats_out: n_layers x n_lead x {mean, var}; thr_out: n_layers x n_lead), then the
+// threshold-mode step with those thresholds.
+int oracle_step_layerwise(float* w, const float* const* g, float* const* r, const uint8_t* accumulate, uint32_t W,
+                          const oracle_layer* layers, const uint32_t* leaders, uint32_t n_lead, double alpha,
+                          double beta, double C, uint32_t n_layers, float eps, float scale, double* stats_out,
+                          float* thr_out, uint8_t* mask_out, uint32_t* count_out, uint32_t* idx_out,
+                          float* sum_out, uint64_t max_pairs, uint64_t* total_out) {
+    for (uint32_t j = 0; j < n_layers; ++j) {
+        const oracle_layer& L = layers[j];
+        for (uint32_t p = 0; p < W; ++p) {
+            if (accumulate && !accumulate[p]) continue;
+            oracle_accumulate(r[p] + L.offset, g[p] + L.offset, L.n);
+        }
+        for (uint32_t q = 0; q < n_lead; ++q) {
+            const uint32_t lead = leaders[(size_t)j * n_lead + q];
+            if (lead >= W) return -2;
+            double mean, var;
+            oracle_layer_stats(w + L.offset, r[lead] + L.offset, L.n, eps, &mean, &var);
+            stats_out[2 * ((size_t)j * n_lead + q)] = mean;
+            stats_out[2 * ((size_t)j * n_lead + q) + 1] = var;
+            thr_out[(size_t)j * n_lead + q] = oracle_layerwise_threshold(mean, var, alpha, beta, C);
+        }
+    }
+    std::vector<uint8_t> none(W, 0);                 // everything is accumulated already
+    return oracle_step_threshold(w, g, r, none.data(), W, layers, leaders, n_lead, thr_out, 1, n_layers, eps, scale,
+                                 mask_out, count_out, idx_out, sum_out, max_pairs, total_out);
 }
 
 }  // extern "C"

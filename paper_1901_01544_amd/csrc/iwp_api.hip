@@ -494,18 +494,12 @@ int iwp_step_segmented(const iwp_plan* plan, float* w, const float* const* g, fl
     if (acc.n)
         IWP_LAUNCH("k_follow_gather", k_follow_gather, acc.n * T.tiles, s, P, acc, T.layers, T.n_layers, T.tiles, leader,
                    W, idx_out, ws.tile_out, ws.gathered, T.pairs);
-    if (stat.n && T.any_k) {
-        TimedLaunch tl_("k_gather_static", s);
-        k_gather_static<<<dim3((uint32_t)((T.pairs + BLOCK - 1) / BLOCK), stat.n), BLOCK, 0, s>>>(
-            R, stat, T.layers, T.n_layers, leader, W, idx_out, ws.gathered, T.pairs, plan->flat_end);
+    if (T.any_k) {
+        uint32_t static_mask = 0;
+        for (uint32_t q = 0; q < stat.n; ++q) static_mask |= 1u << stat.id[q];
+        IWP_LAUNCH("k_reduce_update", k_reduce_update, (uint32_t)((T.pairs + BLOCK - 1) / BLOCK), s, R, static_mask, T.layers,
+                   T.n_layers, leader, ws.gathered, W, T.pairs, idx_out, w, scale, sum_out, plan->flat_end);
     }
-    {
-        hipError_t e_ = hipGetLastError();
-        if (e_ != hipSuccess) return hip_fail(e_, "k_gather_static");
-    }
-    if (T.any_k)
-        IWP_LAUNCH("k_reduce_update", k_reduce_update, (uint32_t)((T.pairs + BLOCK - 1) / BLOCK), s, ws.gathered, W,
-                   T.pairs, idx_out, w, scale, sum_out, plan->flat_end);
     return IWP_OK;
 }
 
@@ -625,19 +619,9 @@ int iwp_step_threshold_segmented(const iwp_plan* plan, float* w, const float* co
                ws.stile_counts, ws.lay_out, count_out, max_pairs, ws.tile_out, idx_out);
     IWP_LAUNCH("k_follow_mask", k_follow_mask, W * z.tiles, s, P, layers, z.n_layers, z.tiles, leaders, n_lead, W, mask32,
                ws.tile_out, ws.lay_out, count_out, max_pairs, ws.gathered);
-    const uint32_t pair_blocks = (max_pairs + BLOCK - 1) / BLOCK;
-    {
-        TimedLaunch tl_("k_gather_pairs", s);
-        k_gather_pairs<<<dim3(pair_blocks, W), BLOCK, 0, s>>>(P, layers, z.n_layers, leaders, n_lead, W, ws.lay_out,
-                                                              count_out, max_pairs, idx_out, ws.gathered,
-                                                              plan->flat_end);
-    }
-    {
-        hipError_t e_ = hipGetLastError();
-        if (e_ != hipSuccess) return hip_fail(e_, "k_gather_pairs");
-    }
-    IWP_LAUNCH("k_reduce_update_counted", k_reduce_update_counted, pair_blocks, s, ws.gathered, W, max_pairs, count_out,
-               z.n_layers, idx_out, w, scale, sum_out, plan->flat_end);
+    const uint32_t pair_blocks = std::min<uint32_t>((max_pairs + BLOCK - 1) / BLOCK, 8192u);
+    IWP_LAUNCH("k_reduce_update_counted", k_reduce_update_counted, pair_blocks, s, P, layers, z.n_layers, leaders, n_lead, W,
+               ws.lay_out, count_out, max_pairs, ws.gathered, idx_out, w, scale, sum_out, plan->flat_end);
     return IWP_OK;
 }
 

@@ -29,44 +29,43 @@ __global__ __launch_bounds__(BLOCK) void k_apply_update(float* __restrict__ w, c
     for (uint32_t p = 0; p < W; ++p) R.r[p][i] = 0.0f;
 }
 
-// Whole-step route, workers that do not accumulate (no gradient: their residual is
-// static): nothing streams, so their values at the sent positions are fetched and
-// cleared pair by pair.  Grid: (pairs / 256, stat.n).  The leader of a pair's layer
-// is skipped (its row and its clearing are the pair writer's).
-__global__ __launch_bounds__(BLOCK) void k_gather_static(ResidualPtrs R, WorkerList stat,
+// Whole-step route: the workers that streamed (and each layer's leader) left their
+// values at the K pairs in `gathered` (row p = worker p) and cleared them on the way.
+// A worker that does not accumulate (no gradient: bit p of static_mask) streams
+// nothing, so unless it leads the pair's layer its value is fetched and cleared
+// here, pair by pair.  Then the ordered sum over the workers and the weight update.
+__global__ __launch_bounds__(BLOCK) void k_reduce_update(ResidualPtrs R, uint32_t static_mask,
                                                          const DevLayer* __restrict__ layers, uint32_t n_layers,
-                                                         const uint32_t* __restrict__ leader, uint32_t W,
-                                                         const uint32_t* __restrict__ idx, float* __restrict__ gathered,
-                                                         uint64_t K, uint64_t flat_end) {
-    const uint64_t j = (uint64_t)blockIdx.x * BLOCK + threadIdx.x;
-    if (j >= K) return;
-    const uint32_t p = stat.id[blockIdx.y];
-    uint32_t lo = 0, hi = n_layers;              // layer of pair j: last row with out_offset <= j
-    while (hi - lo > 1) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (layers[mid].out_offset <= j) lo = mid; else hi = mid;
-    }
-    if (leader_of(leader, lo, W) == p) return;
-    const uint32_t i = idx[j];
-    if (i >= flat_end) return;                   // cannot happen for pairs this library wrote
-    gathered[(size_t)p * K + j] = R.r[p][i];
-    R.r[p][i] = 0.0f;
-}
-
-// Whole-step route: the residuals were already gathered into `gathered`
-// (row p = worker p's values at the K pairs, leader's row included) and cleared
-// while they streamed by, so what is left is the ordered sum over the workers and
-// the weight update.
-__global__ __launch_bounds__(BLOCK) void k_reduce_update(const float* __restrict__ gathered, uint32_t W, uint64_t K,
+                                                         const uint32_t* __restrict__ leader,
+                                                         const float* __restrict__ gathered, uint32_t W, uint64_t K,
                                                          const uint32_t* __restrict__ idx, float* __restrict__ w,
                                                          float scale, float* __restrict__ sum_out, uint64_t flat_end) {
     const uint64_t j = (uint64_t)blockIdx.x * BLOCK + threadIdx.x;
     if (j >= K) return;
-    float acc = gathered[j];
-    for (uint32_t p = 1; p < W; ++p) acc = acc + gathered[(size_t)p * K + j];
-    sum_out[j] = acc;
     const uint32_t i = idx[j];
-    if (i >= flat_end) return;                   // cannot happen for pairs this library wrote
+    const bool ok = i < flat_end;                // always true for pairs this library wrote
+    uint32_t direct = 0;
+    if (static_mask) {
+        uint32_t lo = 0, hi = n_layers;          // layer of pair j: last row with out_offset <= j
+        while (hi - lo > 1) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (layers[mid].out_offset <= j) lo = mid; else hi = mid;
+        }
+        direct = static_mask & ~(1u << leader_of(leader, lo, W));
+    }
+    float acc = 0.0f;
+    for (uint32_t p = 0; p < W; ++p) {
+        float v;
+        if ((direct >> p) & 1u) {
+            v = ok ? R.r[p][i] : 0.0f;
+            if (ok) R.r[p][i] = 0.0f;
+        } else {
+            v = gathered[(size_t)p * K + j];
+        }
+        acc = p == 0 ? v : acc + v;
+    }
+    sum_out[j] = acc;
+    if (!ok) return;
     const float t = scale * acc;
     w[i] = w[i] + t;
 }

@@ -327,48 +327,52 @@ __global__ __launch_bounds__(BLOCK) void k_follow_mask(WorkerPtrs P, const DevLa
 }
 
 // ---------------------------------------------------------------------------
-// The nodes the streaming pass left out (chosen for the pair's layer, or without a
-// gradient): value fetched and cleared pair by pair.  Grid: (max_pairs / 256, W).
+// Ordered sum over the W nodes and the weight update, for a pair count that lives
+// on the device.  A node that streamed the pair's layer (k_follow_mask) left its
+// value in its gather row; the others (chosen for the layer, or without a gradient)
+// are read and cleared here, pair by pair.  Fixed grid, strided over the pairs.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(BLOCK) void k_gather_pairs(WorkerPtrs P, const DevLayer* __restrict__ layers,
-                                                        uint32_t n_layers, const uint32_t* __restrict__ leaders,
-                                                        uint32_t n_lead, uint32_t W,
-                                                        const uint32_t* __restrict__ lay_out,
-                                                        const uint32_t* __restrict__ count_out, uint32_t max_pairs,
-                                                        const uint32_t* __restrict__ idx, float* __restrict__ gathered,
-                                                        uint64_t flat_end) {
-    const uint32_t jj = blockIdx.x * BLOCK + threadIdx.x;
-    if (overflowed(count_out, n_layers) || jj >= count_out[n_layers]) return;
-    const uint32_t p = blockIdx.y;
-    uint32_t lo = 0, hi = n_layers;              // layer of pair jj: last layer with lay_out <= jj
-    while (hi - lo > 1) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (lay_out[mid] <= jj) lo = mid; else hi = mid;
-    }
-    if (P.g[p] && !chosen_before(leaders, n_lead, lo, n_lead, W, p)) return;   // done while streaming
-    const uint32_t i = idx[jj];
-    if (i >= flat_end) return;
-    gathered[(size_t)p * max_pairs + jj] = P.r[p][i];
-    P.r[p][i] = 0.0f;
-}
-
-// Ordered sum over the W gather rows and the weight update, for a pair count that
-// lives on the device.
-__global__ __launch_bounds__(BLOCK) void k_reduce_update_counted(const float* __restrict__ gathered, uint32_t W,
-                                                                 uint32_t max_pairs,
+__global__ __launch_bounds__(BLOCK) void k_reduce_update_counted(WorkerPtrs P, const DevLayer* __restrict__ layers,
+                                                                 uint32_t n_layers,
+                                                                 const uint32_t* __restrict__ leaders, uint32_t n_lead,
+                                                                 uint32_t W, const uint32_t* __restrict__ lay_out,
                                                                  const uint32_t* __restrict__ count_out,
-                                                                 uint32_t n_layers, const uint32_t* __restrict__ idx,
+                                                                 uint32_t max_pairs, const float* __restrict__ gathered,
+                                                                 const uint32_t* __restrict__ idx,
                                                                  float* __restrict__ w, float scale,
                                                                  float* __restrict__ sum_out, uint64_t flat_end) {
-    const uint32_t jj = blockIdx.x * BLOCK + threadIdx.x;
-    if (overflowed(count_out, n_layers) || jj >= count_out[n_layers]) return;
-    float acc = gathered[jj];
-    for (uint32_t p = 1; p < W; ++p) acc = acc + gathered[(size_t)p * max_pairs + jj];
-    sum_out[jj] = acc;
-    const uint32_t i = idx[jj];
-    if (i >= flat_end) return;
-    const float t = scale * acc;
-    w[i] = w[i] + t;
+    if (overflowed(count_out, n_layers)) return;
+    const uint32_t total = min(count_out[n_layers], max_pairs);
+    for (uint64_t jj64 = (uint64_t)blockIdx.x * BLOCK + threadIdx.x; jj64 < total; jj64 += (uint64_t)gridDim.x * BLOCK) {
+        const uint32_t jj = (uint32_t)jj64;
+        uint32_t lo = 0, hi = n_layers;              // layer of pair jj: last layer with lay_out <= jj
+        while (hi - lo > 1) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (lay_out[mid] <= jj) lo = mid; else hi = mid;
+        }
+        uint32_t direct = 0;                         // bit p: node p did not stream this layer
+        for (uint32_t p = 0; p < W; ++p)
+            if (!P.g[p]) direct |= 1u << p;
+        for (uint32_t q = 0; q < n_lead; ++q) direct |= 1u << chosen_at(leaders, n_lead, lo, q, W);
+        const uint32_t i = idx[jj];
+        const bool ok = i < flat_end;
+        float acc = 0.0f;
+        for (uint32_t p = 0; p < W; ++p) {
+            float v;
+            if ((direct >> p) & 1u) {
+                v = ok ? P.r[p][i] : 0.0f;
+                if (ok) P.r[p][i] = 0.0f;
+            } else {
+                v = gathered[(size_t)p * max_pairs + jj];
+            }
+            acc = p == 0 ? v : acc + v;
+        }
+        sum_out[jj] = acc;
+        if (ok) {
+            const float t = scale * acc;
+            w[i] = w[i] + t;
+        }
+    }
 }
 
 }  // namespace iwp
