@@ -31,7 +31,8 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published peak HBM3E bandwidth
 WORKLOADS = {"tiny": 1, "alexnet": 2, "resnet50": 3, "many_small": 4, "flat": 5}
-DOMINANT_KERNEL = {"whole_step": "k_follow_gather", "three_calls": "k_accumulate_all", "threshold": "k_follow_mask"}
+DOMINANT_KERNEL = {"whole_step": "k_follow_gather", "three_calls": "k_accumulate_all", "threshold": "k_follow_mask",
+                   "layerwise": "k_follow_mask"}
 
 
 def step_bytes(ps, W_acc, W_list):
@@ -52,6 +53,12 @@ def dominant_kernel_bytes(ps, W_acc, W_list, route):
     if W_acc == 1:                                    # k_leader_pass: r, g, w in, r out
         return 16 * ps.P
     return 12 * (W_acc - 1) * ps.P + (4 + 4 * (W_list - 1)) * ps.K
+
+
+def layerwise_extra_bytes(ps, n_lead):
+    """Layer-wise thresholds: the statistics need the chosen nodes' importance before the
+    threshold exists, so the mask pass reads their residual and the weights again (8 B/elem)."""
+    return 8 * n_lead * ps.P
 
 
 def threshold_step_bytes(ps, W_acc, W_list, n_lead, pairs):
@@ -85,10 +92,11 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="alexnet", choices=sorted(WORKLOADS))
-    ap.add_argument("--route", default="whole_step", choices=["whole_step", "three_calls", "threshold"],
+    ap.add_argument("--route", default="whole_step", choices=["whole_step", "three_calls", "threshold", "layerwise"],
                     help="whole_step: iwp_step_segmented; three_calls: compress_segmented + gather_sum_at_indices "
                          "+ apply_sparse_update (same results); threshold: iwp_step_threshold_segmented with fixed "
-                         "per-layer thresholds (calibrated by a few top-k steps to the same keep ratio)")
+                         "per-layer thresholds (calibrated by a few top-k steps to the same keep ratio); layerwise: "
+                         "iwp_step_layerwise_segmented, thresholds from each layer's importance mean / variance")
     ap.add_argument("--n-lead", type=int, default=1, help="threshold route: chosen nodes per layer")
     ap.add_argument("--no-hint", action="store_true",
                     help="whole_step only: do not pass the previous step's thresholds as a hint (results are "
@@ -132,8 +140,9 @@ def main():
     gen_s = time.time() - t0
 
     plan = iwp.Plan(ps.rows())
-    fused = args.route in ("whole_step", "threshold")      # threshold: top-k whole steps calibrate the thresholds
-    thr_mode = args.route == "threshold"
+    fused = args.route in ("whole_step", "threshold", "layerwise")   # threshold routes: top-k steps calibrate
+    thr_mode = args.route in ("threshold", "layerwise")
+    lw_mode = args.route == "layerwise"
     assert not (thr_mode and flat_cfg), "the threshold route is measured on the multi-worker workloads"
     n_lead = args.n_lead
     dominant = DOMINANT_KERNEL[args.route]
@@ -149,6 +158,7 @@ def main():
     use_hint = fused and not args.no_hint
     CAL = 8                                           # threshold route: top-k steps that settle the thresholds
     total = args.warmup + args.steps + (CAL if thr_mode else 0)
+    spare = 1                                         # the layerwise route spends one more step on calibration
     if flat_cfg:
         lead_np = np.zeros((total, 1), np.int32)
     else:
@@ -198,16 +208,37 @@ def main():
         del ws
         ws = torch.empty(plan.threshold_workspace_bytes(W_list, n_lead, max_pairs), dtype=torch.uint8, device=dev)
         mask = torch.empty(plan.mask_bytes, dtype=torch.uint8, device=dev)
-        counts = torch.zeros(total, len(ps.layers) + 2, dtype=torch.int32, device=dev)
+        counts = torch.zeros(total + spare, len(ps.layers) + 2, dtype=torch.int32, device=dev)
         idx = torch.empty(max_pairs, dtype=torch.int32, device=dev)
         sm = torch.empty(max_pairs, dtype=torch.float32, device=dev)
         chosen = torch.from_numpy(np.stack([wl.chosen_nodes(ps, t, n_lead).astype(np.int32).ravel()
-                                            for t in range(total)])).to(dev)
+                                            for t in range(total + spare)])).to(dev)
+
+        stats = torch.zeros(len(ps.layers), n_lead, 2, dtype=torch.float64, device=dev)
+        thr_slots = torch.zeros(len(ps.layers), n_lead, dtype=torch.float32, device=dev)
+        rule = None
+        if lw_mode:
+            # one rule for all layers: alpha = the median calibrated threshold; one step with beta = 0
+            # gives the layers' var/mean ratios; C = their median, beta = a 10 % correction at C
+            alpha = float(fixed_thr.median())
+            g0 = [grads[wl.gradient_set_of(ps, p, CAL, pool)] for p in range(ps.W)]
+            iwp.step_layerwise_segmented(plan, w, g0, r, chosen[CAL], n_lead, alpha, 0.0, 0.0, eps, scale, stats,
+                                         thr_slots, mask, counts[CAL], idx, sm, max_pairs, ws, stream)
+            torch.cuda.synchronize()
+            ratio = (stats[:, :, 1] / stats[:, :, 0]).flatten()
+            c_rule = float(ratio[torch.isfinite(ratio)].median())
+            rule = (alpha, 0.1 * alpha / c_rule, c_rule)
+            first = CAL + 1
+            total += 1
 
         def step(t):                                  # noqa: F811 -- the timed step of this route
             g = [grads[wl.gradient_set_of(ps, p, t, pool)] for p in range(ps.W)]
-            iwp.step_threshold_segmented(plan, w, g, r, chosen[t], n_lead, fixed_thr, eps, scale, mask, counts[t],
-                                         idx, sm, max_pairs, ws, stream)
+            if lw_mode:
+                iwp.step_layerwise_segmented(plan, w, g, r, chosen[t], n_lead, rule[0], rule[1], rule[2], eps, scale,
+                                             stats, thr_slots, mask, counts[t], idx, sm, max_pairs, ws, stream)
+            else:
+                iwp.step_threshold_segmented(plan, w, g, r, chosen[t], n_lead, fixed_thr, eps, scale, mask, counts[t],
+                                             idx, sm, max_pairs, ws, stream)
 
     for t in range(first, first + args.warmup):
         step(t)
@@ -220,7 +251,7 @@ def main():
     elapsed = time.perf_counter() - t0
     k_ms, k_cnt = iwp.timing_collect()
     if thr_mode:
-        c = counts[first + args.warmup:].cpu().numpy()
+        c = counts[first + args.warmup:total].cpu().numpy()
         assert not c[:, -1].any(), "pair capacity exceeded in %d timed steps" % int(c[:, -1].sum())
         pairs_per_step = float(c[:, -2].mean())
         pairs_minmax = [int(c[:, -2].min()), int(c[:, -2].max())]
@@ -267,6 +298,8 @@ def main():
     params_per_s = ps.P * args.steps / elapsed
     if thr_mode:
         algo_bytes = threshold_step_bytes(ps, W_acc, W_list, n_lead, pairs_per_step)
+        if lw_mode:
+            algo_bytes += layerwise_extra_bytes(ps, n_lead)
         dom_bytes = threshold_dominant_bytes(ps, W_acc, W_list, n_lead, pairs_per_step)
     else:
         algo_bytes = step_bytes(ps, W_acc, W_list)
@@ -317,6 +350,9 @@ def main():
         out["config"]["threshold_hint"] = "n/a"
         out["config"]["chosen_nodes_per_layer"] = n_lead
         out["config"]["thresholds"] = "fixed per layer: k-th largest importance after %d top-k steps" % CAL
+        if lw_mode:
+            out["config"]["thresholds"] = "alpha +/- beta * var/mean per layer and chosen node"
+            out["config"]["rule"] = {"alpha": rule[0], "beta": rule[1], "C": rule[2]}
         out["config"]["pairs_per_step_min_max"] = pairs_minmax
         out["config"]["pair_capacity"] = max_pairs
     if not args.no_cpu_baseline and thr_mode:
@@ -330,8 +366,12 @@ def main():
             t = total + n_steps
             g = [grads_np[wl.gradient_set_of(ps, p, t, pool)] for p in range(ps.W)]
             t1 = time.perf_counter()
-            oracle.step_threshold(w_ref, g, r_ref, ps.rows(), wl.chosen_nodes(ps, t, n_lead), thr_np, eps, scale,
-                                  ps.P)
+            if lw_mode:
+                oracle.step_layerwise(w_ref, g, r_ref, ps.rows(), wl.chosen_nodes(ps, t, n_lead), rule[0], rule[1],
+                                      rule[2], eps, scale, ps.P)
+            else:
+                oracle.step_threshold(w_ref, g, r_ref, ps.rows(), wl.chosen_nodes(ps, t, n_lead), thr_np, eps, scale,
+                                      ps.P)
             spent += time.perf_counter() - t1
             n_steps += 1
         out["cpu_baseline"] = {

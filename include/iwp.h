@@ -227,6 +227,27 @@ int iwp_step_threshold_segmented(const iwp_plan* plan, float* w, const float* co
                                  uint8_t* mask_out, uint32_t* count_out, uint32_t* idx_out, float* sum_out,
                                  uint32_t max_pairs, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The same iteration with layer-wise thresholds (Section 3.4, Eq. 4): every chosen node
+ * derives its own threshold for the layer from the mean and the (population) variance of
+ * its importance values after accumulation:  ratio = var / mean;
+ * thr = alpha + beta * ratio if ratio > C, else alpha - beta * ratio  (the two branches of
+ * Eq. 4 read by the prose that follows it), evaluated in binary64 and rounded once to
+ * binary32; then everything as in iwp_step_threshold_segmented, each node comparing
+ * against its own threshold.  alpha, beta, C: the epoch's hyper-parameters, finite.
+ * Outputs in addition: stats_out[2 * (j * n_lead + q)] = mean, [.. + 1] = variance
+ * (device, 16-byte aligned, binary64) and thr_out[j * n_lead + q] (device, binary32) for
+ * the node in slot q of layer j (a node listed twice: same values in both slots).
+ * A layer whose importance is zero everywhere has ratio 0/0: its threshold is NaN and
+ * nothing of it is sent.  The statistics are sums in binary64 taken in a fixed order
+ * (deterministic run to run); they agree with a sequential binary64 evaluation to
+ * rounding error of the summation, far inside 1e-6 relative.
+ * Workspace: iwp_plan_threshold_workspace_bytes. */
+int iwp_step_layerwise_segmented(const iwp_plan* plan, float* w, const float* const* g, float* const* r, uint32_t W,
+                                 const uint32_t* leaders, uint32_t n_lead, double alpha, double beta, double C, float eps,
+                                 float scale, double* stats_out, float* thr_out, uint8_t* mask_out, uint32_t* count_out,
+                                 uint32_t* idx_out, float* sum_out, uint32_t max_pairs, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream);
+
 /* ------------------------------------------------------------------ helpers */
 
 /* The importance keys exactly as the kernels compute them: key_out[i] = bit

@@ -557,11 +557,12 @@ struct ThresholdWorkspace {
     uint32_t* tile_out;       // tiles
     uint32_t* layer_total;    // n_layers
     uint32_t* lay_out;        // n_layers + 1
+    double2* tile_stats;      // n_lead * tiles (layer-wise thresholds)
     float* gathered;          // W * max_pairs
     size_t bytes;
 };
 
-ThresholdWorkspace carve_threshold(void* base, const Sizes& z, uint32_t W, uint32_t n_lead, uint32_t max_pairs) {
+static ThresholdWorkspace carve_threshold(void* base, const Sizes& z, uint32_t W, uint32_t n_lead, uint32_t max_pairs) {
     ThresholdWorkspace ws;
     const uintptr_t b = reinterpret_cast<uintptr_t>(base);
     size_t off = 0;
@@ -572,24 +573,24 @@ ThresholdWorkspace carve_threshold(void* base, const Sizes& z, uint32_t W, uint3
     ws.tile_out = reinterpret_cast<uint32_t*>(take((size_t)z.tiles * sizeof(uint32_t)));
     ws.layer_total = reinterpret_cast<uint32_t*>(take((size_t)z.n_layers * sizeof(uint32_t)));
     ws.lay_out = reinterpret_cast<uint32_t*>(take(((size_t)z.n_layers + 1) * sizeof(uint32_t)));
+    ws.tile_stats = reinterpret_cast<double2*>(take((size_t)n_lead * z.tiles * sizeof(double2)));
     ws.gathered = reinterpret_cast<float*>(take((size_t)W * max_pairs * sizeof(float)));
     ws.bytes = off;
     return ws;
 }
 
-}  // namespace
+// Rule of the layer-wise threshold; absent (NULL) for caller-supplied thresholds.
+struct LayerwiseRule {
+    double alpha, beta, C;
+    double* stats_out;
+    float* thr_out;
+};
 
-size_t iwp_plan_mask_bytes(const iwp_plan* plan) { return plan ? (size_t)plan->z.mask_words * 4 : 0; }
-
-size_t iwp_plan_threshold_workspace_bytes(const iwp_plan* plan, uint32_t W, uint32_t n_lead, uint32_t max_pairs) {
-    return plan ? carve_threshold(nullptr, plan->z, W, n_lead, max_pairs).bytes : 0;
-}
-
-int iwp_step_threshold_segmented(const iwp_plan* plan, float* w, const float* const* g, float* const* r, uint32_t W,
-                                 const uint32_t* leaders, uint32_t n_lead, const float* thr, float eps, float scale,
-                                 uint8_t* mask_out, uint32_t* count_out, uint32_t* idx_out, float* sum_out,
-                                 uint32_t max_pairs, void* workspace, size_t workspace_bytes, void* hip_stream) {
-    if (!plan || !w || !leaders || !thr || !mask_out || !count_out || !idx_out || !sum_out) return IWP_EINVAL;
+static int run_threshold_step(const iwp_plan* plan, float* w, const float* const* g, float* const* r, uint32_t W,
+                       const uint32_t* leaders, uint32_t n_lead, const float* thr, const LayerwiseRule* rule, float eps,
+                       float scale, uint8_t* mask_out, uint32_t* count_out, uint32_t* idx_out, float* sum_out,
+                       uint32_t max_pairs, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!plan || !w || !leaders || !mask_out || !count_out || !idx_out || !sum_out) return IWP_EINVAL;
     if (n_lead == 0 || n_lead > MAX_LEAD || n_lead > W || max_pairs == 0) return IWP_EINVAL;
     if (check_eps(eps) || !std::isfinite(scale)) return IWP_EINVAL;
     if (!aligned4(w) || !aligned4(leaders) || !aligned4(thr) || !aligned4(mask_out) || !aligned4(count_out) ||
@@ -606,9 +607,18 @@ int iwp_step_threshold_segmented(const iwp_plan* plan, float* w, const float* co
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     uint32_t* mask32 = reinterpret_cast<uint32_t*>(mask_out);
     const DevLayer* layers = plan->dev;
+    if (rule) {
+        // the chosen nodes accumulate while their statistics are taken; the mask pass then only re-reads
+        if (z.tiles)
+            IWP_LAUNCH("k_leader_stats", k_leader_stats, n_lead * z.tiles, s, P, w, layers, z.n_layers, z.tiles, leaders,
+                       n_lead, W, eps, ws.tile_stats);
+        IWP_LAUNCH("k_layer_thr", k_layer_thr, z.n_layers * n_lead, s, layers, z.tiles, leaders, n_lead, W, ws.tile_stats,
+                   rule->alpha, rule->beta, rule->C, reinterpret_cast<double2*>(rule->stats_out), rule->thr_out);
+        thr = rule->thr_out;
+    }
     if (z.tiles) {
         IWP_LAUNCH("k_leader_mask", k_leader_mask, n_lead * z.tiles, s, P, w, layers, z.n_layers, z.tiles, leaders, n_lead, W,
-                   thr, eps, ws.lmask, z.mask_words);
+                   thr, rule != nullptr, rule == nullptr, eps, ws.lmask, z.mask_words);
         IWP_LAUNCH("k_mask_or_count", k_mask_or_count, z.stiles, s, layers, z.n_layers, leaders, n_lead, W, ws.lmask,
                    z.mask_words, mask32, ws.tile_counts, ws.stile_counts);
     }
@@ -623,6 +633,36 @@ int iwp_step_threshold_segmented(const iwp_plan* plan, float* w, const float* co
     IWP_LAUNCH("k_reduce_update_counted", k_reduce_update_counted, pair_blocks, s, P, layers, z.n_layers, leaders, n_lead, W,
                ws.lay_out, count_out, max_pairs, ws.gathered, idx_out, w, scale, sum_out, plan->flat_end);
     return IWP_OK;
+}
+
+}  // namespace
+
+size_t iwp_plan_mask_bytes(const iwp_plan* plan) { return plan ? (size_t)plan->z.mask_words * 4 : 0; }
+
+size_t iwp_plan_threshold_workspace_bytes(const iwp_plan* plan, uint32_t W, uint32_t n_lead, uint32_t max_pairs) {
+    return plan ? carve_threshold(nullptr, plan->z, W, n_lead, max_pairs).bytes : 0;
+}
+
+int iwp_step_threshold_segmented(const iwp_plan* plan, float* w, const float* const* g, float* const* r, uint32_t W,
+                                 const uint32_t* leaders, uint32_t n_lead, const float* thr, float eps, float scale,
+                                 uint8_t* mask_out, uint32_t* count_out, uint32_t* idx_out, float* sum_out,
+                                 uint32_t max_pairs, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!thr) return IWP_EINVAL;
+    return run_threshold_step(plan, w, g, r, W, leaders, n_lead, thr, nullptr, eps, scale, mask_out, count_out, idx_out,
+                              sum_out, max_pairs, workspace, workspace_bytes, hip_stream);
+}
+
+int iwp_step_layerwise_segmented(const iwp_plan* plan, float* w, const float* const* g, float* const* r, uint32_t W,
+                                 const uint32_t* leaders, uint32_t n_lead, double alpha, double beta, double C, float eps,
+                                 float scale, double* stats_out, float* thr_out, uint8_t* mask_out, uint32_t* count_out,
+                                 uint32_t* idx_out, float* sum_out, uint32_t max_pairs, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream) {
+    if (!stats_out || !thr_out) return IWP_EINVAL;
+    if (!std::isfinite(alpha) || !std::isfinite(beta) || !std::isfinite(C)) return IWP_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(stats_out) & 15u) || !aligned4(thr_out)) return IWP_EALIGN;
+    LayerwiseRule rule{alpha, beta, C, stats_out, thr_out};
+    return run_threshold_step(plan, w, g, r, W, leaders, n_lead, thr_out, &rule, eps, scale, mask_out, count_out, idx_out,
+                              sum_out, max_pairs, workspace, workspace_bytes, hip_stream);
 }
 
 // ----------------------------------------------------------------- helpers

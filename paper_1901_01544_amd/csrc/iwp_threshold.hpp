@@ -39,35 +39,14 @@ __device__ __forceinline__ bool overflowed(const uint32_t* __restrict__ count_ou
     return count_out[n_layers + 1] != 0u;
 }
 
-// ---------------------------------------------------------------------------
-// Chosen nodes: accumulate, score, compare, encode.  Grid: n_lead * tiles.  A node
-// that appears in an earlier slot of the same layer is skipped (same mask).
-// lmask: n_lead masks of mask_words words each, laid out like the final mask.
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(BLOCK) void k_leader_mask(WorkerPtrs P, const float* __restrict__ w,
-                                                       const DevLayer* __restrict__ layers, uint32_t n_layers,
-                                                       uint32_t tiles, const uint32_t* __restrict__ leaders,
-                                                       uint32_t n_lead, uint32_t W, const float* __restrict__ thr,
-                                                       float eps, uint32_t* __restrict__ lmask, uint64_t mask_words) {
-    const uint32_t tid = threadIdx.x, lane = tid & (WAVE - 1);
-    const uint32_t q = blockIdx.x / tiles;
-    const uint32_t t = blockIdx.x - q * tiles;
-    const uint32_t j = find_layer<false>(layers, n_layers, t);
-    const DevLayer L = layers[j];
-    const uint32_t p = chosen_at(leaders, n_lead, j, q, W);
-    if (chosen_before(leaders, n_lead, j, q, W, p)) return;
-    const uint32_t lt = t - L.tile_begin;
-    const uint32_t base = lt * TILE;
-    const float* gp = P.g[p];
-    float* rl = P.r[p] + L.offset;
-    const float* gl = gp ? gp + L.offset : nullptr;
-    const float* wl = w + L.offset;
+// One tile of a chosen node in registers: residual (after adding the gradient and storing
+// it back when gp is set) and weights, 16 values per lane; positions past the layer's end
+// read as r = 0, w = 1.
+__device__ __forceinline__ void chosen_tile(const float* gp, float* rl, const float* gl, const float* wl, uint32_t n,
+                                            uint32_t base, uint32_t tid, float (&rv)[CHUNKS_PER_TILE][4],
+                                            float (&wv)[CHUNKS_PER_TILE][4]) {
     const bool vec = is_aligned16(rl) && is_aligned16(wl) && (!gp || is_aligned16(gl));
-    const float th = thr[j];
-    const uint32_t nwords = (L.n + 31) / 32;
-    uint32_t* mw = lmask + (size_t)q * mask_words + L.mask_begin;
-    float rv[CHUNKS_PER_TILE][4], wv[CHUNKS_PER_TILE][4];
-    if (vec && base + TILE <= L.n) {
+    if (vec && base + TILE <= n) {
         v4f rr[CHUNKS_PER_TILE], gg[CHUNKS_PER_TILE], ww[CHUNKS_PER_TILE];
 #pragma unroll
         for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
@@ -92,19 +71,48 @@ __global__ __launch_bounds__(BLOCK) void k_leader_mask(WorkerPtrs P, const float
             const uint32_t i = base + u * CHUNK + tid * VEC;
 #pragma unroll
             for (int c = 0; c < 4; ++c) { rv[u][c] = 0.0f; wv[u][c] = 1.0f; }
-            if (i < L.n) {
-                load_quad(rl, i, L.n, vec, rv[u]);
+            if (i < n) {
+                load_quad(rl, i, n, vec, rv[u]);
                 if (gp) {
                     float gv[4];
-                    load_quad(gl, i, L.n, vec, gv);
+                    load_quad(gl, i, n, vec, gv);
 #pragma unroll
                     for (int c = 0; c < 4; ++c) rv[u][c] = rv[u][c] + gv[c];
-                    store_quad(rl, i, L.n, vec, rv[u]);
+                    store_quad(rl, i, n, vec, rv[u]);
                 }
-                load_quad(wl, i, L.n, vec, wv[u], 1.0f);
+                load_quad(wl, i, n, vec, wv[u], 1.0f);
             }
         }
     }
+}
+
+// ---------------------------------------------------------------------------
+// Chosen nodes: accumulate (if asked), score, compare, encode.  Grid: n_lead * tiles.
+// A node that appears in an earlier slot of the same layer is skipped (same mask).
+// lmask: n_lead masks of mask_words words each, laid out like the final mask.
+// thr: one value per layer, or per (layer, slot) with thr_per_slot.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(BLOCK) void k_leader_mask(WorkerPtrs P, const float* __restrict__ w,
+                                                       const DevLayer* __restrict__ layers, uint32_t n_layers,
+                                                       uint32_t tiles, const uint32_t* __restrict__ leaders,
+                                                       uint32_t n_lead, uint32_t W, const float* __restrict__ thr,
+                                                       bool thr_per_slot, bool accumulate, float eps,
+                                                       uint32_t* __restrict__ lmask, uint64_t mask_words) {
+    const uint32_t tid = threadIdx.x, lane = tid & (WAVE - 1);
+    const uint32_t q = blockIdx.x / tiles;
+    const uint32_t t = blockIdx.x - q * tiles;
+    const uint32_t j = find_layer<false>(layers, n_layers, t);
+    const DevLayer L = layers[j];
+    const uint32_t p = chosen_at(leaders, n_lead, j, q, W);
+    if (chosen_before(leaders, n_lead, j, q, W, p)) return;
+    const uint32_t lt = t - L.tile_begin;
+    const uint32_t base = lt * TILE;
+    const float* gp = accumulate ? P.g[p] : nullptr;
+    const float th = thr_per_slot ? thr[(size_t)j * n_lead + q] : thr[j];
+    const uint32_t nwords = (L.n + 31) / 32;
+    uint32_t* mw = lmask + (size_t)q * mask_words + L.mask_begin;
+    float rv[CHUNKS_PER_TILE][4], wv[CHUNKS_PER_TILE][4];
+    chosen_tile(gp, P.r[p] + L.offset, gp ? gp + L.offset : nullptr, w + L.offset, L.n, base, tid, rv, wv);
 #pragma unroll
     for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
         const uint32_t i = base + u * CHUNK + tid * VEC;
@@ -121,6 +129,106 @@ __global__ __launch_bounds__(BLOCK) void k_leader_mask(WorkerPtrs P, const float
         word |= __shfl_xor(word, 4, WAVE);
         const uint32_t widx = lt * TILE_WORDS + u * (CHUNK / 32) + (tid >> 3);
         if ((lane & 7u) == 0u && widx < nwords) mw[widx] = word;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Layer-wise threshold, part 1 (Section 3.4, Eq. 4): the chosen nodes accumulate and
+// score, and every tile leaves the sum of its importance values and the sum of their
+// squared deviations from the tile's own mean, both binary64.  Grid: n_lead * tiles.
+// tile_stats[q * tiles + t] = (sum, squared deviations).
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ double block_sum_f64(double v, double* slot) {
+#pragma unroll
+    for (int d = WAVE / 2; d > 0; d >>= 1) v += __shfl_xor(v, d, WAVE);
+    __syncthreads();                             // slot may still be read from an earlier call
+    if ((threadIdx.x & (WAVE - 1)) == 0) slot[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return ((slot[0] + slot[1]) + slot[2]) + slot[3];
+}
+
+__global__ __launch_bounds__(BLOCK) void k_leader_stats(WorkerPtrs P, const float* __restrict__ w,
+                                                        const DevLayer* __restrict__ layers, uint32_t n_layers,
+                                                        uint32_t tiles, const uint32_t* __restrict__ leaders,
+                                                        uint32_t n_lead, uint32_t W, float eps,
+                                                        double2* __restrict__ tile_stats) {
+    __shared__ double slot[BLOCK / WAVE];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t q = blockIdx.x / tiles;
+    const uint32_t t = blockIdx.x - q * tiles;
+    const uint32_t j = find_layer<false>(layers, n_layers, t);
+    const DevLayer L = layers[j];
+    const uint32_t p = chosen_at(leaders, n_lead, j, q, W);
+    if (chosen_before(leaders, n_lead, j, q, W, p)) return;
+    const uint32_t base = (t - L.tile_begin) * TILE;
+    const float* gp = P.g[p];
+    float rv[CHUNKS_PER_TILE][4], wv[CHUNKS_PER_TILE][4];
+    chosen_tile(gp, P.r[p] + L.offset, gp ? gp + L.offset : nullptr, w + L.offset, L.n, base, tid, rv, wv);
+    float sc[CHUNKS_PER_TILE][4];
+    double lane_sum = 0.0;
+#pragma unroll
+    for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+        const uint32_t i = base + u * CHUNK + tid * VEC;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            sc[u][c] = fabsf(rv[u][c]) / (fabsf(wv[u][c]) + eps);
+            if (i + c < L.n) lane_sum += (double)sc[u][c];
+        }
+    }
+    const double sum = block_sum_f64(lane_sum, slot);
+    const double mean = sum / (double)min(TILE, L.n - base);
+    double lane_m2 = 0.0;
+#pragma unroll
+    for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+        const uint32_t i = base + u * CHUNK + tid * VEC;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const double d = (double)sc[u][c] - mean;
+            if (i + c < L.n) lane_m2 += d * d;
+        }
+    }
+    const double m2 = block_sum_f64(lane_m2, slot);
+    if (tid == 0) tile_stats[(size_t)q * tiles + t] = make_double2(sum, m2);
+}
+
+// ---------------------------------------------------------------------------
+// Layer-wise threshold, part 2: one workgroup per (layer, slot) merges the tiles
+// (sum of squared deviations about the layer mean = sum over tiles of the tile's own
+// plus n_t * (tile mean - layer mean)^2), then applies the rule:
+// ratio = var / mean; thr = alpha + beta * ratio if ratio > C, else alpha - beta * ratio.
+// stats_out[slot] = (mean, population variance), thr_out[slot] = thr rounded to binary32.
+// A slot repeating an earlier node of the layer takes that node's tiles.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(BLOCK) void k_layer_thr(const DevLayer* __restrict__ layers, uint32_t tiles,
+                                                     const uint32_t* __restrict__ leaders, uint32_t n_lead, uint32_t W,
+                                                     const double2* __restrict__ tile_stats, double alpha, double beta,
+                                                     double C, double2* __restrict__ stats_out,
+                                                     float* __restrict__ thr_out) {
+    __shared__ double slot[BLOCK / WAVE];
+    const uint32_t j = blockIdx.x / n_lead;
+    const uint32_t q = blockIdx.x - j * n_lead;
+    const DevLayer L = layers[j];
+    const uint32_t p = chosen_at(leaders, n_lead, j, q, W);
+    uint32_t q0 = 0;
+    while (chosen_at(leaders, n_lead, j, q0, W) != p) ++q0;      // ends at q at the latest
+    const uint32_t ntiles = (L.n + TILE - 1) / TILE;
+    const double2* ts = tile_stats + (size_t)q0 * tiles + L.tile_begin;
+    double part = 0.0;
+    for (uint32_t t = threadIdx.x; t < ntiles; t += BLOCK) part += ts[t].x;
+    const double n = (double)L.n;
+    const double mean = L.n ? block_sum_f64(part, slot) / n : 0.0;
+    part = 0.0;
+    for (uint32_t t = threadIdx.x; t < ntiles; t += BLOCK) {
+        const double nt = (double)min(TILE, L.n - t * TILE);
+        const double d = ts[t].x / nt - mean;
+        part += ts[t].y + nt * (d * d);
+    }
+    const double var = L.n ? block_sum_f64(part, slot) / n : 0.0;
+    if (threadIdx.x == 0) {
+        const double ratio = var / mean;
+        const double thr = ratio > C ? alpha + beta * ratio : alpha - beta * ratio;
+        stats_out[blockIdx.x] = make_double2(mean, var);
+        thr_out[blockIdx.x] = (float)thr;
     }
 }
 

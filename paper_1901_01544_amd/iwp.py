@@ -69,6 +69,10 @@ def load() -> C.CDLL:
                                                _vp, C.c_float, C.c_float, _vp, _vp, _vp, _vp, C.c_uint32, _vp,
                                                C.c_size_t, _vp]
     L.iwp_step_threshold_segmented.restype = C.c_int
+    L.iwp_step_layerwise_segmented.argtypes = [_vp, _vp, C.POINTER(_vp), C.POINTER(_vp), C.c_uint32, _vp, C.c_uint32,
+                                               C.c_double, C.c_double, C.c_double, C.c_float, C.c_float, _vp, _vp,
+                                               _vp, _vp, _vp, _vp, C.c_uint32, _vp, C.c_size_t, _vp]
+    L.iwp_step_layerwise_segmented.restype = C.c_int
     L.iwp_plan_total_pairs.argtypes = [_vp]
     L.iwp_plan_total_pairs.restype = C.c_uint64
     L.compress_segmented.argtypes = [_vp, _vp, C.POINTER(_vp), C.POINTER(_vp), C.c_uint32, _vp, _vp, C.c_float,
@@ -231,6 +235,18 @@ def step_threshold_segmented(plan: Plan, w, g: Sequence, r: Sequence, leaders, n
                                                n_lead, _ptr(thr), eps, scale, _ptr(mask_out), _ptr(count_out),
                                                _ptr(idx_out), _ptr(sum_out), max_pairs, _ptr(workspace), ws_bytes,
                                                _stream(stream)), "iwp_step_threshold_segmented")
+
+
+def step_layerwise_segmented(plan: Plan, w, g: Sequence, r: Sequence, leaders, n_lead: int, alpha: float, beta: float,
+                             c: float, eps: float, scale: float, stats_out, thr_out, mask_out, count_out, idx_out,
+                             sum_out, max_pairs: int, workspace, stream=None):
+    assert len(g) == len(r)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().iwp_step_layerwise_segmented(plan._h, _ptr(w), _ptr_table(g), _ptr_table(r), len(r), _ptr(leaders),
+                                               n_lead, alpha, beta, c, eps, scale, _ptr(stats_out), _ptr(thr_out),
+                                               _ptr(mask_out), _ptr(count_out), _ptr(idx_out), _ptr(sum_out),
+                                               max_pairs, _ptr(workspace), ws_bytes, _stream(stream)),
+           "iwp_step_layerwise_segmented")
 
 
 def select_threshold_segmented(plan: Plan, w, r, eps: float, thr_out, workspace, stream=None):

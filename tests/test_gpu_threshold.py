@@ -7,51 +7,10 @@ import pytest
 
 import oracle
 from paper_1901_01544_amd import workloads as wl
-from harness import bits
+from harness import ThresholdSet, bits
 
 pytestmark = pytest.mark.gpu
 EPS = 1e-8
-
-
-class ThresholdSet:
-    def __init__(self, iwp, ps, w_np, grads_np, r_np, n_lead, max_pairs):
-        import torch
-        self.torch, self.iwp, self.ps = torch, iwp, ps
-        dev = "cuda:0"
-        self.W = len(r_np)
-        self.w = torch.from_numpy(w_np).to(dev)
-        self.grads = [torch.from_numpy(g).to(dev) for g in grads_np]
-        self.r = [torch.from_numpy(x).to(dev) for x in r_np]
-        self.plan = iwp.Plan(ps.rows())
-        self.n_lead, self.max_pairs = n_lead, max_pairs
-        nl = len(ps.layers)
-        self.mask = torch.full((max(4, self.plan.mask_bytes),), 0xAA, dtype=torch.uint8, device=dev)
-        self.count = torch.full((nl + 2,), -1, dtype=torch.int32, device=dev)
-        self.idx = torch.full((max_pairs + 8,), -1, dtype=torch.int32, device=dev)
-        self.sum = torch.full((max_pairs + 8,), float("nan"), dtype=torch.float32, device=dev)
-        self.ws = torch.empty(max(1, self.plan.threshold_workspace_bytes(self.W, n_lead, max_pairs)),
-                              dtype=torch.uint8, device=dev)
-        self.leaders = torch.zeros(nl * n_lead, dtype=torch.int32, device=dev)
-        self.thr = torch.zeros(nl, dtype=torch.float32, device=dev)
-
-    def step(self, g_ids, leaders_np, thr_np, scale):
-        t = self.torch
-        self.idx.fill_(-1)
-        self.sum.fill_(float("nan"))
-        self.leaders.copy_(t.from_numpy(np.ascontiguousarray(leaders_np, np.uint32).view(np.int32).ravel()))
-        self.thr.copy_(t.from_numpy(np.ascontiguousarray(thr_np, np.float32)))
-        g = [None if i is None else self.grads[i] for i in g_ids]
-        self.iwp.step_threshold_segmented(self.plan, self.w, g, self.r, self.leaders, self.n_lead, self.thr, EPS,
-                                          float(scale), self.mask, self.count, self.idx, self.sum, self.max_pairs,
-                                          self.ws)
-        t.cuda.synchronize()
-
-    def download(self):
-        nl = len(self.ps.layers)
-        return dict(mask=self.mask.cpu().numpy()[:self.plan.mask_bytes],
-                    count=self.count.cpu().numpy().view(np.uint32),
-                    idx=self.idx.cpu().numpy().view(np.uint32), sum=self.sum.cpu().numpy(),
-                    w=self.w.cpu().numpy(), r=[x.cpu().numpy() for x in self.r], nl=nl)
 
 
 def _leaders(rng, n_layers, n_lead, W, wild=False):
