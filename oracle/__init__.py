@@ -92,6 +92,18 @@ def lib():
                                             C.c_float, C.c_float, _u8p, _u32p, _u32p, _f32p, C.c_uint64,
                                             C.POINTER(C.c_uint64)]
         L.oracle_step_threshold.restype = C.c_int
+        L.oracle_step_threshold_random.argtypes = [_f32p, C.POINTER(_f32p), C.POINTER(_f32p), _u8p, C.c_uint32,
+                                                   C.POINTER(Layer), _u32p, C.c_uint32, _f32p, C.c_uint32,
+                                                   C.c_uint64, C.c_uint64, C.c_uint32, C.c_float, C.c_float, _u8p,
+                                                   _u32p, _u32p, _f32p, C.c_uint64, C.POINTER(C.c_uint64)]
+        L.oracle_step_threshold_random.restype = C.c_int
+        L.oracle_philox4x32_10.argtypes = [_u32p, _u32p, _u32p]
+        L.oracle_philox4x32_10.restype = None
+        L.oracle_uniform.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint32]
+        L.oracle_uniform.restype = C.c_float
+        L.oracle_mask_threshold_random.argtypes = [_f32p, _f32p, C.c_uint64, C.c_float, C.c_float, C.c_uint64,
+                                                   C.c_uint64, C.c_uint32, _u8p]
+        L.oracle_mask_threshold_random.restype = None
         _f64p = C.POINTER(C.c_double)
         L.oracle_layer_stats.argtypes = [_f32p, _f32p, C.c_uint64, C.c_float, _f64p, _f64p]
         L.oracle_layer_stats.restype = None
@@ -252,10 +264,11 @@ def mask_indices(mask: np.ndarray, n: int) -> np.ndarray:
 
 def step_threshold(w: np.ndarray, g: Sequence[np.ndarray], r: Sequence[np.ndarray], rows, leaders: np.ndarray,
                    thr: np.ndarray, eps: float, scale: float, max_pairs: int,
-                   accumulate_mask: Sequence[int] | None = None):
+                   accumulate_mask: Sequence[int] | None = None, random: tuple | None = None):
     """One whole threshold-mode step on flat host buffers; w and every r[p] are updated
     in place.  leaders: (n_layers, n_lead) uint32; thr: (n_layers,) float32, or
     (n_layers, n_lead) float32 (2-D) for one threshold per chosen node.
+    random = (seed, step): with random gradient selection (Section 3.3).
     -> (mask bytes of all layers back to back, counts[n_layers], idx[total], sum[total])."""
     rows = list(rows)
     tab = layer_table(rows)
@@ -272,9 +285,16 @@ def step_threshold(w: np.ndarray, g: Sequence[np.ndarray], r: Sequence[np.ndarra
     acc = None
     if accumulate_mask is not None:
         acc = (C.c_uint8 * W)(*[1 if a else 0 for a in accumulate_mask])
-    rc = lib().oracle_step_threshold(_f32(w), _ptr_array(g), _ptr_array(r), acc, W, tab, _u32(leaders),
-                                     leaders.shape[1], _f32(thr), per_slot, len(rows), C.c_float(eps), C.c_float(scale),
-                                     _u8(mask), _u32(counts), _u32(idx), _f32(sm), max_pairs, C.byref(total))
+    if random is None:
+        rc = lib().oracle_step_threshold(_f32(w), _ptr_array(g), _ptr_array(r), acc, W, tab, _u32(leaders),
+                                         leaders.shape[1], _f32(thr), per_slot, len(rows), C.c_float(eps),
+                                         C.c_float(scale), _u8(mask), _u32(counts), _u32(idx), _f32(sm), max_pairs,
+                                         C.byref(total))
+    else:
+        rc = lib().oracle_step_threshold_random(_f32(w), _ptr_array(g), _ptr_array(r), acc, W, tab, _u32(leaders),
+                                                leaders.shape[1], _f32(thr), per_slot, int(random[0]), int(random[1]),
+                                                len(rows), C.c_float(eps), C.c_float(scale), _u8(mask), _u32(counts),
+                                                _u32(idx), _f32(sm), max_pairs, C.byref(total))
     if rc:
         raise ValueError("oracle_step_threshold: rc=%d" % rc)
     return mask, counts, idx[:total.value].copy(), sm[:total.value].copy()
@@ -319,3 +339,26 @@ def step_layerwise(w: np.ndarray, g: Sequence[np.ndarray], r: Sequence[np.ndarra
     if rc:
         raise ValueError("oracle_step_layerwise: rc=%d" % rc)
     return stats, thr, mask, counts, idx[:total.value].copy(), sm[:total.value].copy()
+
+
+def philox4x32_10(ctr, key) -> np.ndarray:
+    """S1: one Philox-4x32-10 block; ctr: 4 words, key: 2 words -> 4 words."""
+    c = np.ascontiguousarray(ctr, np.uint32)
+    k = np.ascontiguousarray(key, np.uint32)
+    out = np.zeros(4, np.uint32)
+    lib().oracle_philox4x32_10(_u32(c), _u32(k), _u32(out))
+    return out
+
+
+def uniform(seed: int, step: int, layer: int, i: int) -> np.float32:
+    """S1: the draw of element i of a layer at a step, a multiple of 2^-24 in [0, 1)."""
+    return np.float32(lib().oracle_uniform(seed, step, layer, i))
+
+
+def mask_threshold_random(w: np.ndarray, r: np.ndarray, eps: float, thr: float, seed: int, step: int,
+                          layer: int) -> np.ndarray:
+    """S2: encoded mask of one chosen node with random gradient selection."""
+    mask = np.zeros(mask_bytes(r.size), np.uint8)
+    lib().oracle_mask_threshold_random(_f32(w), _f32(r), r.size, C.c_float(eps), C.c_float(thr), seed, step, layer,
+                                       _u8(mask))
+    return mask

@@ -48,6 +48,15 @@
 //       threshold for a large ratio and lowers it otherwise), binary64, rounded once to binary32
 //   then T1..T4 with each chosen node using its own threshold.
 //
+// Random gradient selection (Section 3.3): an element that is not above the threshold is
+// still sent with probability importance / threshold.
+//   S1  the draw: Philox-4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw: "Parallel random
+//       numbers: as easy as 1, 2, 3", SC'11), key = the 64-bit seed, counter = (i / 4, layer,
+//       step low word, step high word); element i takes output word i % 4 and
+//       u = (word >> 8) * 2^-24, a multiple of 2^-24 in [0, 1).  The draw depends on
+//       (seed, step, layer, position) only, not on the node.
+//   S2  p = s / thr in binary32;  m[i] = (s > thr) or (u < p).
+//
 // Pins (tests/test_oracle_pins.py): brute-force rank count on tiny layers,
 // cardinality, exact conservation, the paper's 64x / 58.8x ratios as keep
 // fractions, numpy lexsort cross-check, threshold-mask equivalence with the
@@ -282,12 +291,55 @@ uint64_t oracle_mask_indices(const uint8_t* mask, uint64_t n, uint32_t* idx_out)
 // flat positions of all layers packed in table order and the reduced values, at most
 // max_pairs (returns -4 if there are more).  Every worker with accumulate[p] != 0
 // adds its gradient first; every worker is cleared at the masked positions.
-// thr_per_slot != 0: thr holds n_layers x n_lead values, one per chosen node.
-int oracle_step_threshold(float* w, const float* const* g, float* const* r, const uint8_t* accumulate, uint32_t W,
-                          const oracle_layer* layers, const uint32_t* leaders, uint32_t n_lead,
-                          const float* thr, uint32_t thr_per_slot, uint32_t n_layers, float eps, float scale,
-                          uint8_t* mask_out, uint32_t* count_out, uint32_t* idx_out, float* sum_out,
-                          uint64_t max_pairs, uint64_t* total_out) {
+// S1: Philox-4x32-10.
+void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n1 = (uint32_t)p1;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        const uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// S1: the uniform draw of element i of a layer at a step.
+float oracle_uniform(uint64_t seed, uint64_t step, uint32_t layer, uint32_t i) {
+    const uint32_t ctr[4] = {i >> 2, layer, (uint32_t)step, (uint32_t)(step >> 32)};
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t out[4];
+    oracle_philox4x32_10(ctr, key, out);
+    return (float)(out[i & 3u] >> 8) * 0x1p-24f;
+}
+
+// S2 (with T2's encoding): above the threshold, or drawn with probability s / thr.
+void oracle_mask_threshold_random(const float* w, const float* r, uint64_t n, float eps, float thr, uint64_t seed,
+                                  uint64_t step, uint32_t layer, uint8_t* mask) {
+    std::memset(mask, 0, oracle_mask_bytes(n));
+    for (uint64_t i = 0; i < n; ++i) {
+        float denom = std::fabs(w[i]) + eps;
+        float s = std::fabs(r[i]) / denom;
+        float p = s / thr;
+        float u = oracle_uniform(seed, step, layer, (uint32_t)i);
+        if (s > thr || u < p) mask[i >> 3] = (uint8_t)(mask[i >> 3] | (1u << (i & 7)));
+    }
+}
+
+}  // extern "C"
+
+namespace {
+struct RandomSelection { uint64_t seed, step; };
+
+int step_threshold_impl(float* w, const float* const* g, float* const* r, const uint8_t* accumulate, uint32_t W,
+                        const oracle_layer* layers, const uint32_t* leaders, uint32_t n_lead, const float* thr,
+                        uint32_t thr_per_slot, const RandomSelection* rs, uint32_t n_layers, float eps, float scale,
+                        uint8_t* mask_out, uint32_t* count_out, uint32_t* idx_out, float* sum_out, uint64_t max_pairs,
+                        uint64_t* total_out) {
     uint64_t total = 0, mask_off = 0;
     for (uint32_t j = 0; j < n_layers; ++j) {
         const oracle_layer& L = layers[j];
@@ -303,7 +355,11 @@ int oracle_step_threshold(float* w, const float* const* g, float* const* r, cons
             const uint32_t lead = leaders[(size_t)j * n_lead + q];
             if (lead >= W) return -2;
             const float t = thr_per_slot ? thr[(size_t)j * n_lead + q] : thr[j];
-            oracle_mask_threshold(w + L.offset, r[lead] + L.offset, L.n, eps, t, one.data());
+            if (rs)
+                oracle_mask_threshold_random(w + L.offset, r[lead] + L.offset, L.n, eps, t, rs->seed, rs->step, j,
+                                             one.data());
+            else
+                oracle_mask_threshold(w + L.offset, r[lead] + L.offset, L.n, eps, t, one.data());
             oracle_mask_or(mask, one.data(), nbytes);
         }
         std::vector<uint32_t> local(L.n);
@@ -320,7 +376,30 @@ int oracle_step_threshold(float* w, const float* const* g, float* const* r, cons
     oracle_apply_sparse_update(w, idx_out, sum_out, total, scale, r, W);
     return 0;
 }
+}  // namespace
 
+extern "C" {
+
+// thr_per_slot != 0: thr holds n_layers x n_lead values, one per chosen node.
+int oracle_step_threshold(float* w, const float* const* g, float* const* r, const uint8_t* accumulate, uint32_t W,
+                          const oracle_layer* layers, const uint32_t* leaders, uint32_t n_lead,
+                          const float* thr, uint32_t thr_per_slot, uint32_t n_layers, float eps, float scale,
+                          uint8_t* mask_out, uint32_t* count_out, uint32_t* idx_out, float* sum_out,
+                          uint64_t max_pairs, uint64_t* total_out) {
+    return step_threshold_impl(w, g, r, accumulate, W, layers, leaders, n_lead, thr, thr_per_slot, nullptr, n_layers,
+                               eps, scale, mask_out, count_out, idx_out, sum_out, max_pairs, total_out);
+}
+
+// The same step with random gradient selection (S1, S2) on every chosen node.
+int oracle_step_threshold_random(float* w, const float* const* g, float* const* r, const uint8_t* accumulate,
+                                 uint32_t W, const oracle_layer* layers, const uint32_t* leaders, uint32_t n_lead,
+                                 const float* thr, uint32_t thr_per_slot, uint64_t seed, uint64_t step,
+                                 uint32_t n_layers, float eps, float scale, uint8_t* mask_out, uint32_t* count_out,
+                                 uint32_t* idx_out, float* sum_out, uint64_t max_pairs, uint64_t* total_out) {
+    const RandomSelection rs{seed, step};
+    return step_threshold_impl(w, g, r, accumulate, W, layers, leaders, n_lead, thr, thr_per_slot, &rs, n_layers, eps,
+                               scale, mask_out, count_out, idx_out, sum_out, max_pairs, total_out);
+}
 
 // ------------------------------------------------------------------ layer-wise threshold
 
