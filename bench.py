@@ -98,6 +98,8 @@ def main():
                          "per-layer thresholds (calibrated by a few top-k steps to the same keep ratio); layerwise: "
                          "iwp_step_layerwise_segmented, thresholds from each layer's importance mean / variance")
     ap.add_argument("--n-lead", type=int, default=1, help="threshold route: chosen nodes per layer")
+    ap.add_argument("--random-selection", action="store_true",
+                    help="threshold route: also send sub-threshold elements with probability importance / threshold")
     ap.add_argument("--no-hint", action="store_true",
                     help="whole_step only: do not pass the previous step's thresholds as a hint (results are "
                          "identical either way; the hint saves the second pass over the leaders' layers)")
@@ -204,7 +206,7 @@ def main():
         torch.cuda.synchronize()
         first = CAL
         fixed_thr = thr2[(CAL - 1) % 2].view(-1, 3)[:, 0].contiguous().view(torch.float32).clone()
-        max_pairs = min(ps.P, 8 * ps.K)
+        max_pairs = min(ps.P, (16 if args.random_selection else 8) * ps.K)
         del ws
         ws = torch.empty(plan.threshold_workspace_bytes(W_list, n_lead, max_pairs), dtype=torch.uint8, device=dev)
         mask = torch.empty(plan.mask_bytes, dtype=torch.uint8, device=dev)
@@ -236,6 +238,9 @@ def main():
             if lw_mode:
                 iwp.step_layerwise_segmented(plan, w, g, r, chosen[t], n_lead, rule[0], rule[1], rule[2], eps, scale,
                                              stats, thr_slots, mask, counts[t], idx, sm, max_pairs, ws, stream)
+            elif args.random_selection:
+                iwp.step_threshold_random_segmented(plan, w, g, r, chosen[t], n_lead, fixed_thr, ps.seed, t, eps, scale,
+                                                    mask, counts[t], idx, sm, max_pairs, ws, stream)
             else:
                 iwp.step_threshold_segmented(plan, w, g, r, chosen[t], n_lead, fixed_thr, eps, scale, mask, counts[t],
                                              idx, sm, max_pairs, ws, stream)
@@ -349,6 +354,7 @@ def main():
     if thr_mode:
         out["config"]["threshold_hint"] = "n/a"
         out["config"]["chosen_nodes_per_layer"] = n_lead
+        out["config"]["random_selection"] = bool(args.random_selection)
         out["config"]["thresholds"] = "fixed per layer: k-th largest importance after %d top-k steps" % CAL
         if lw_mode:
             out["config"]["thresholds"] = "alpha +/- beta * var/mean per layer and chosen node"
@@ -371,7 +377,7 @@ def main():
                                       rule[2], eps, scale, ps.P)
             else:
                 oracle.step_threshold(w_ref, g, r_ref, ps.rows(), wl.chosen_nodes(ps, t, n_lead), thr_np, eps, scale,
-                                      ps.P)
+                                      ps.P, random=(ps.seed, t) if args.random_selection else None)
             spent += time.perf_counter() - t1
             n_steps += 1
         out["cpu_baseline"] = {

@@ -227,6 +227,22 @@ int iwp_step_threshold_segmented(const iwp_plan* plan, float* w, const float* co
                                  uint8_t* mask_out, uint32_t* count_out, uint32_t* idx_out, float* sum_out,
                                  uint32_t max_pairs, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* iwp_step_threshold_segmented with random gradient selection (Section 3.3): on every
+ * chosen node an element that is not above the threshold is still marked with
+ * probability importance / threshold, to bound the staleness of small gradients.
+ * The draw of element i (position inside its layer) of layer j is
+ * u = (x >> 8) * 2^-24, x = output word i % 4 of Philox-4x32 with 10 rounds (Salmon et
+ * al., SC'11) under key (seed low word, seed high word) and counter (i / 4, j, step low
+ * word, step high word); the element is marked iff importance > thr or
+ * u < importance / thr (binary32 divide).  The draw does not depend on the node, so a
+ * caller can reproduce it.  seed, step: any values; use the iteration number as step.
+ * Everything else as in iwp_step_threshold_segmented. */
+int iwp_step_threshold_random_segmented(const iwp_plan* plan, float* w, const float* const* g, float* const* r,
+                                        uint32_t W, const uint32_t* leaders, uint32_t n_lead, const float* thr,
+                                        uint64_t seed, uint64_t step, float eps, float scale, uint8_t* mask_out,
+                                        uint32_t* count_out, uint32_t* idx_out, float* sum_out, uint32_t max_pairs,
+                                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* The same iteration with layer-wise thresholds (Section 3.4, Eq. 4): every chosen node
  * derives its own threshold for the layer from the mean and the (population) variance of
  * its importance values after accumulation:  ratio = var / mean;

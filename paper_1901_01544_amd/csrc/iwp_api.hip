@@ -587,8 +587,8 @@ struct LayerwiseRule {
 };
 
 static int run_threshold_step(const iwp_plan* plan, float* w, const float* const* g, float* const* r, uint32_t W,
-                       const uint32_t* leaders, uint32_t n_lead, const float* thr, const LayerwiseRule* rule, float eps,
-                       float scale, uint8_t* mask_out, uint32_t* count_out, uint32_t* idx_out, float* sum_out,
+                       const uint32_t* leaders, uint32_t n_lead, const float* thr, const LayerwiseRule* rule,
+                       RandomSel rs, float eps, float scale, uint8_t* mask_out, uint32_t* count_out, uint32_t* idx_out, float* sum_out,
                        uint32_t max_pairs, void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!plan || !w || !leaders || !mask_out || !count_out || !idx_out || !sum_out) return IWP_EINVAL;
     if (n_lead == 0 || n_lead > MAX_LEAD || n_lead > W || max_pairs == 0) return IWP_EINVAL;
@@ -618,7 +618,7 @@ static int run_threshold_step(const iwp_plan* plan, float* w, const float* const
     }
     if (z.tiles) {
         IWP_LAUNCH("k_leader_mask", k_leader_mask, n_lead * z.tiles, s, P, w, layers, z.n_layers, z.tiles, leaders, n_lead, W,
-                   thr, rule != nullptr, rule == nullptr, eps, ws.lmask, z.mask_words);
+                   thr, rule != nullptr, rule == nullptr, rs, eps, ws.lmask, z.mask_words);
         IWP_LAUNCH("k_mask_or_count", k_mask_or_count, z.stiles, s, layers, z.n_layers, leaders, n_lead, W, ws.lmask,
                    z.mask_words, mask32, ws.tile_counts, ws.stile_counts);
     }
@@ -648,7 +648,18 @@ int iwp_step_threshold_segmented(const iwp_plan* plan, float* w, const float* co
                                  uint8_t* mask_out, uint32_t* count_out, uint32_t* idx_out, float* sum_out,
                                  uint32_t max_pairs, void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!thr) return IWP_EINVAL;
-    return run_threshold_step(plan, w, g, r, W, leaders, n_lead, thr, nullptr, eps, scale, mask_out, count_out, idx_out,
+    return run_threshold_step(plan, w, g, r, W, leaders, n_lead, thr, nullptr, RandomSel{0, 0, 0, 0, 0}, eps, scale, mask_out,
+                              count_out, idx_out, sum_out, max_pairs, workspace, workspace_bytes, hip_stream);
+}
+
+int iwp_step_threshold_random_segmented(const iwp_plan* plan, float* w, const float* const* g, float* const* r,
+                                        uint32_t W, const uint32_t* leaders, uint32_t n_lead, const float* thr,
+                                        uint64_t seed, uint64_t step, float eps, float scale, uint8_t* mask_out,
+                                        uint32_t* count_out, uint32_t* idx_out, float* sum_out, uint32_t max_pairs,
+                                        void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!thr) return IWP_EINVAL;
+    const RandomSel rs{1u, (uint32_t)seed, (uint32_t)(seed >> 32), (uint32_t)step, (uint32_t)(step >> 32)};
+    return run_threshold_step(plan, w, g, r, W, leaders, n_lead, thr, nullptr, rs, eps, scale, mask_out, count_out, idx_out,
                               sum_out, max_pairs, workspace, workspace_bytes, hip_stream);
 }
 
@@ -661,7 +672,7 @@ int iwp_step_layerwise_segmented(const iwp_plan* plan, float* w, const float* co
     if (!std::isfinite(alpha) || !std::isfinite(beta) || !std::isfinite(C)) return IWP_EINVAL;
     if ((reinterpret_cast<uintptr_t>(stats_out) & 15u) || !aligned4(thr_out)) return IWP_EALIGN;
     LayerwiseRule rule{alpha, beta, C, stats_out, thr_out};
-    return run_threshold_step(plan, w, g, r, W, leaders, n_lead, thr_out, &rule, eps, scale, mask_out, count_out, idx_out,
+    return run_threshold_step(plan, w, g, r, W, leaders, n_lead, thr_out, &rule, RandomSel{0, 0, 0, 0, 0}, eps, scale, mask_out, count_out, idx_out,
                               sum_out, max_pairs, workspace, workspace_bytes, hip_stream);
 }
 

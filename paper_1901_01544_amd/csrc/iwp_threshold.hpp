@@ -39,6 +39,32 @@ __device__ __forceinline__ bool overflowed(const uint32_t* __restrict__ count_ou
     return count_out[n_layers + 1] != 0u;
 }
 
+// Random gradient selection (Section 3.3): an element not above the threshold is still
+// sent with probability importance / threshold.  The draw comes from Philox-4x32 with 10
+// rounds (Salmon et al., SC'11): key = the caller's 64-bit seed, counter = (i / 4, layer,
+// step low, step high); element i of the layer takes output word i % 4, and
+// u = (word >> 8) * 2^-24.  It depends on (seed, step, layer, position) only, so every
+// node, and any other implementation of the same generator, sees the same draw.
+struct RandomSel {
+    uint32_t on, key0, key1, step0, step1;
+};
+
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                              uint32_t k1, uint32_t (&out)[4]) {
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        c0 = hi1 ^ c1 ^ k0;
+        c1 = lo1;
+        c2 = hi0 ^ c3 ^ k1;
+        c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
 // One tile of a chosen node in registers: residual (after adding the gradient and storing
 // it back when gp is set) and weights, 16 values per lane; positions past the layer's end
 // read as r = 0, w = 1.
@@ -96,7 +122,7 @@ __global__ __launch_bounds__(BLOCK) void k_leader_mask(WorkerPtrs P, const float
                                                        const DevLayer* __restrict__ layers, uint32_t n_layers,
                                                        uint32_t tiles, const uint32_t* __restrict__ leaders,
                                                        uint32_t n_lead, uint32_t W, const float* __restrict__ thr,
-                                                       bool thr_per_slot, bool accumulate, float eps,
+                                                       bool thr_per_slot, bool accumulate, RandomSel rs, float eps,
                                                        uint32_t* __restrict__ lmask, uint64_t mask_words) {
     const uint32_t tid = threadIdx.x, lane = tid & (WAVE - 1);
     const uint32_t q = blockIdx.x / tiles;
@@ -117,10 +143,18 @@ __global__ __launch_bounds__(BLOCK) void k_leader_mask(WorkerPtrs P, const float
     for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
         const uint32_t i = base + u * CHUNK + tid * VEC;
         uint32_t nib = 0;
+        uint32_t word4[4] = {0u, 0u, 0u, 0u};
+        if (rs.on) philox4x32_10(i >> 2, j, rs.step0, rs.step1, rs.key0, rs.key1, word4);   // i is a multiple of 4
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const float s = fabsf(rv[u][c]) / (fabsf(wv[u][c]) + eps);
-            if (i + c < L.n && s > th) nib |= 1u << c;
+            bool send = s > th;
+            if (rs.on) {
+                const float draw = (float)(word4[c] >> 8) * 0x1p-24f;
+                const float prob = s / th;
+                send = send || draw < prob;
+            }
+            if (i + c < L.n && send) nib |= 1u << c;
         }
         // eight lanes (32 consecutive elements) make one word of the encoded mask
         uint32_t word = nib << (4u * (lane & 7u));

@@ -69,6 +69,10 @@ def load() -> C.CDLL:
                                                _vp, C.c_float, C.c_float, _vp, _vp, _vp, _vp, C.c_uint32, _vp,
                                                C.c_size_t, _vp]
     L.iwp_step_threshold_segmented.restype = C.c_int
+    L.iwp_step_threshold_random_segmented.argtypes = [_vp, _vp, C.POINTER(_vp), C.POINTER(_vp), C.c_uint32, _vp,
+                                                      C.c_uint32, _vp, C.c_uint64, C.c_uint64, C.c_float, C.c_float,
+                                                      _vp, _vp, _vp, _vp, C.c_uint32, _vp, C.c_size_t, _vp]
+    L.iwp_step_threshold_random_segmented.restype = C.c_int
     L.iwp_step_layerwise_segmented.argtypes = [_vp, _vp, C.POINTER(_vp), C.POINTER(_vp), C.c_uint32, _vp, C.c_uint32,
                                                C.c_double, C.c_double, C.c_double, C.c_float, C.c_float, _vp, _vp,
                                                _vp, _vp, _vp, _vp, C.c_uint32, _vp, C.c_size_t, _vp]
@@ -235,6 +239,18 @@ def step_threshold_segmented(plan: Plan, w, g: Sequence, r: Sequence, leaders, n
                                                n_lead, _ptr(thr), eps, scale, _ptr(mask_out), _ptr(count_out),
                                                _ptr(idx_out), _ptr(sum_out), max_pairs, _ptr(workspace), ws_bytes,
                                                _stream(stream)), "iwp_step_threshold_segmented")
+
+
+def step_threshold_random_segmented(plan: Plan, w, g: Sequence, r: Sequence, leaders, n_lead: int, thr, seed: int,
+                                    step: int, eps: float, scale: float, mask_out, count_out, idx_out, sum_out,
+                                    max_pairs: int, workspace, stream=None):
+    assert len(g) == len(r)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().iwp_step_threshold_random_segmented(plan._h, _ptr(w), _ptr_table(g), _ptr_table(r), len(r),
+                                                      _ptr(leaders), n_lead, _ptr(thr), seed, step, eps, scale,
+                                                      _ptr(mask_out), _ptr(count_out), _ptr(idx_out), _ptr(sum_out),
+                                                      max_pairs, _ptr(workspace), ws_bytes, _stream(stream)),
+           "iwp_step_threshold_random_segmented")
 
 
 def step_layerwise_segmented(plan: Plan, w, g: Sequence, r: Sequence, leaders, n_lead: int, alpha: float, beta: float,

@@ -134,16 +134,22 @@ class ThresholdSet:
         self.leaders = torch.zeros(nl * n_lead, dtype=torch.int32, device=dev)
         self.thr = torch.zeros(nl, dtype=torch.float32, device=dev)
 
-    def step(self, g_ids, leaders_np, thr_np, scale):
+    def step(self, g_ids, leaders_np, thr_np, scale, random=None):
+        """random = (seed, step): with random gradient selection."""
         t = self.torch
         self.idx.fill_(-1)
         self.sum.fill_(float("nan"))
         self.leaders.copy_(t.from_numpy(np.ascontiguousarray(leaders_np, np.uint32).view(np.int32).ravel()))
         self.thr.copy_(t.from_numpy(np.ascontiguousarray(thr_np, np.float32)))
         g = [None if i is None else self.grads[i] for i in g_ids]
-        self.iwp.step_threshold_segmented(self.plan, self.w, g, self.r, self.leaders, self.n_lead, self.thr, self.eps,
-                                          float(scale), self.mask, self.count, self.idx, self.sum, self.max_pairs,
-                                          self.ws)
+        if random is not None:
+            self.iwp.step_threshold_random_segmented(self.plan, self.w, g, self.r, self.leaders, self.n_lead, self.thr,
+                                                     int(random[0]), int(random[1]), self.eps, float(scale), self.mask,
+                                                     self.count, self.idx, self.sum, self.max_pairs, self.ws)
+        else:
+            self.iwp.step_threshold_segmented(self.plan, self.w, g, self.r, self.leaders, self.n_lead, self.thr,
+                                              self.eps, float(scale), self.mask, self.count, self.idx, self.sum,
+                                              self.max_pairs, self.ws)
         t.cuda.synchronize()
 
     def step_layerwise(self, g_ids, leaders_np, alpha, beta, c, scale):

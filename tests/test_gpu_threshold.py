@@ -42,7 +42,8 @@ def _thr_for(w, r_list, g_list, ps, density, rng):
     return thr
 
 
-def _run_case(iwp, ps, W, n_lead, steps, density, seed, static=(), slack=8, wild=True, align_msg=""):
+def _run_case(iwp, ps, W, n_lead, steps, density, seed, static=(), slack=8, wild=True, align_msg="", random_seed=None):
+    """random_seed: run with random gradient selection (Section 3.3), the step number as the draw's step."""
     rng = np.random.default_rng(seed)
     w = wl.gen_weights(ps)
     pool = [wl.gen_gradient(ps, s) for s in range(3)]
@@ -64,8 +65,9 @@ def _run_case(iwp, ps, W, n_lead, steps, density, seed, static=(), slack=8, wild
         mask_ref, cnt_ref, idx_ref, sum_ref = oracle.step_threshold(
             w_ref, [g if g is not None else zero for g in g_np], r_ref, rows, np.where(leaders >= W, 0, leaders), thr,
             EPS, float(scale),
-            max_pairs, accumulate_mask=[g is not None for g in g_np])
-        ts.step(g_ids, leaders, thr, scale)
+            max_pairs, accumulate_mask=[g is not None for g in g_np],
+            random=None if random_seed is None else (random_seed, 2 ** 32 * t + t))
+        ts.step(g_ids, leaders, thr, scale, random=None if random_seed is None else (random_seed, 2 ** 32 * t + t))
         got = ts.download()
         tag = "%s step %d" % (align_msg, t)
         nl = got["nl"]
@@ -140,6 +142,41 @@ def test_threshold_step_config1(gpu_lib):
         assert np.array_equal(bits(got["w"]), bits(w_ref))
         for p in range(W):
             assert np.array_equal(bits(got["r"][p]), bits(r_ref[p]))
+
+
+@pytest.mark.parametrize("n_lead", [1, 3])
+@pytest.mark.parametrize("align", [1, 64])
+def test_random_selection_ragged_layers(gpu_lib, n_lead, align):
+    """Random gradient selection: the device's Philox draws, uniform mapping and
+    importance / threshold comparison against the oracle's, bit for bit."""
+    ps = wl.custom_set(RAGGED, W=4, seed=30 + n_lead, align=align, start=1 if align == 1 else 0, zero_frac=0.01)
+    _run_case(gpu_lib, ps, 4, n_lead, steps=3, density=0.01, seed=300 + n_lead, random_seed=2 ** 63 + 12345,
+              align_msg="random align %d" % align)
+
+
+def test_random_selection_densities_and_static(gpu_lib):
+    ps = wl.custom_set([(300_000, 0), (50_000, 0), (1234, 0)], W=5, seed=3, align=64)
+    for density in (0.0005, 0.2):
+        _run_case(gpu_lib, ps, 5, 2, steps=2, density=density, seed=7, random_seed=77, static=(2,))
+
+
+def test_random_selection_sends_more_than_plain_threshold(gpu_lib):
+    """Same state and thresholds with and without the random rule: a strict superset."""
+    import torch
+    ps = wl.custom_set([(200_000, 0)], W=2, seed=9, align=64)
+    rng = np.random.default_rng(5)
+    w = wl.gen_weights(ps)
+    pool = [wl.gen_gradient(ps, s) for s in range(2)]
+    r0 = [(rng.standard_t(3, ps.flat) * 1e-3).astype(np.float32) for _ in range(2)]
+    thr = _thr_for(w, r0, pool, ps, 0.01, np.random.default_rng(3))
+    thr[:] = np.where((thr == 0) | (thr > 1e30), 0.05, thr)
+    leaders = np.zeros((1, 1), np.uint32)
+    masks = []
+    for random in (None, (1, 2)):
+        ts = ThresholdSet(gpu_lib, ps, w, pool, r0, 1, ps.flat)
+        ts.step([0, 1], leaders, thr, -0.01, random=random)
+        masks.append(np.unpackbits(ts.download()["mask"], bitorder="little").astype(bool))
+    assert np.all(masks[1][masks[0]]) and masks[1].sum() > masks[0].sum() > 0
 
 
 def test_threshold_step_capacity(gpu_lib):
