@@ -74,7 +74,9 @@ def lib():
         L.oracle_apply_sparse_update.argtypes = [_f32p, _u32p, _f32p, C.c_uint64, C.c_float,
                                                  C.POINTER(_f32p), C.c_uint32]
         L.oracle_apply_sparse_update.restype = None
-        L.oracle_step.argtypes = [_f32p, C.POINTER(_f32p), C.POINTER(_f32p), C.POINTER(C.c_uint8),
+        L.oracle_accumulate_momentum.argtypes = [_f32p, _f32p, C.c_uint64, C.c_float]
+        L.oracle_accumulate_momentum.restype = None
+        L.oracle_step.argtypes = [_f32p, C.POINTER(_f32p), C.POINTER(_f32p), C.POINTER(C.c_uint8), C.c_float,
                                   C.c_uint32, C.POINTER(Layer), _u32p, C.c_uint32, C.c_float, C.c_float,
                                   _u32p, _f32p, _f32p, C.POINTER(Threshold)]
         L.oracle_step.restype = C.c_int
@@ -87,12 +89,12 @@ def lib():
         L.oracle_mask_or.restype = None
         L.oracle_mask_indices.argtypes = [_u8p, C.c_uint64, _u32p]
         L.oracle_mask_indices.restype = C.c_uint64
-        L.oracle_step_threshold.argtypes = [_f32p, C.POINTER(_f32p), C.POINTER(_f32p), _u8p, C.c_uint32,
+        L.oracle_step_threshold.argtypes = [_f32p, C.POINTER(_f32p), C.POINTER(_f32p), _u8p, C.c_float, C.c_uint32,
                                             C.POINTER(Layer), _u32p, C.c_uint32, _f32p, C.c_uint32, C.c_uint32,
                                             C.c_float, C.c_float, _u8p, _u32p, _u32p, _f32p, C.c_uint64,
                                             C.POINTER(C.c_uint64)]
         L.oracle_step_threshold.restype = C.c_int
-        L.oracle_step_threshold_random.argtypes = [_f32p, C.POINTER(_f32p), C.POINTER(_f32p), _u8p, C.c_uint32,
+        L.oracle_step_threshold_random.argtypes = [_f32p, C.POINTER(_f32p), C.POINTER(_f32p), _u8p, C.c_float, C.c_uint32,
                                                    C.POINTER(Layer), _u32p, C.c_uint32, _f32p, C.c_uint32,
                                                    C.c_uint64, C.c_uint64, C.c_uint32, C.c_float, C.c_float, _u8p,
                                                    _u32p, _u32p, _f32p, C.c_uint64, C.POINTER(C.c_uint64)]
@@ -109,7 +111,7 @@ def lib():
         L.oracle_layer_stats.restype = None
         L.oracle_layerwise_threshold.argtypes = [C.c_double] * 5
         L.oracle_layerwise_threshold.restype = C.c_float
-        L.oracle_step_layerwise.argtypes = [_f32p, C.POINTER(_f32p), C.POINTER(_f32p), _u8p, C.c_uint32,
+        L.oracle_step_layerwise.argtypes = [_f32p, C.POINTER(_f32p), C.POINTER(_f32p), _u8p, C.c_float, C.c_uint32,
                                             C.POINTER(Layer), _u32p, C.c_uint32, C.c_double, C.c_double, C.c_double,
                                             C.c_uint32, C.c_float, C.c_float, _f64p, _f32p, _u8p, _u32p, _u32p,
                                             _f32p, C.c_uint64, C.POINTER(C.c_uint64)]
@@ -134,6 +136,11 @@ def _ptr_array(arrays: Sequence[np.ndarray]):
 def accumulate(r: np.ndarray, g: np.ndarray) -> None:
     assert r.shape == g.shape
     lib().oracle_accumulate(_f32(r), _f32(g), r.size)
+
+
+def accumulate_momentum(r: np.ndarray, g: np.ndarray, m: float) -> None:
+    """M1: r <- (m * r) + g in place, two roundings."""
+    lib().oracle_accumulate_momentum(_f32(r), _f32(g), r.size, C.c_float(m))
 
 
 def score(w: np.ndarray, r: np.ndarray, eps: float) -> np.ndarray:
@@ -210,9 +217,9 @@ def layer_table(rows) -> "C.Array[Layer]":
 
 
 def step(w: np.ndarray, g: Sequence[np.ndarray], r: Sequence[np.ndarray], rows, leader: np.ndarray,
-         eps: float, scale: float, accumulate_mask: Sequence[int] | None = None):
+         eps: float, scale: float, accumulate_mask: Sequence[int] | None = None, momentum: float = 1.0):
     """One whole emulated step on flat host buffers; w and every r[p] are updated
-    in place.  -> (idx, val, sum, thr[n_layers] as uint32 array of shape (L, 3))."""
+    in place (momentum: M1 in place of O1).  -> (idx, val, sum, thr[n_layers] as uint32 array of shape (L, 3))."""
     rows = list(rows)
     tab = layer_table(rows)
     W = len(r)
@@ -225,7 +232,7 @@ def step(w: np.ndarray, g: Sequence[np.ndarray], r: Sequence[np.ndarray], rows, 
     if accumulate_mask is not None:
         acc = (C.c_uint8 * W)(*[1 if a else 0 for a in accumulate_mask])
     leader = np.ascontiguousarray(leader, np.uint32)
-    rc = lib().oracle_step(_f32(w), _ptr_array(g), _ptr_array(r), acc, W, tab, _u32(leader), len(rows),
+    rc = lib().oracle_step(_f32(w), _ptr_array(g), _ptr_array(r), acc, C.c_float(momentum), W, tab, _u32(leader), len(rows),
                            C.c_float(eps), C.c_float(scale), _u32(idx), _f32(val), _f32(sm), thr)
     if rc:
         raise ValueError("oracle_step: rc=%d" % rc)
@@ -264,7 +271,7 @@ def mask_indices(mask: np.ndarray, n: int) -> np.ndarray:
 
 def step_threshold(w: np.ndarray, g: Sequence[np.ndarray], r: Sequence[np.ndarray], rows, leaders: np.ndarray,
                    thr: np.ndarray, eps: float, scale: float, max_pairs: int,
-                   accumulate_mask: Sequence[int] | None = None, random: tuple | None = None):
+                   accumulate_mask: Sequence[int] | None = None, random: tuple | None = None, momentum: float = 1.0):
     """One whole threshold-mode step on flat host buffers; w and every r[p] are updated
     in place.  leaders: (n_layers, n_lead) uint32; thr: (n_layers,) float32, or
     (n_layers, n_lead) float32 (2-D) for one threshold per chosen node.
@@ -286,12 +293,12 @@ def step_threshold(w: np.ndarray, g: Sequence[np.ndarray], r: Sequence[np.ndarra
     if accumulate_mask is not None:
         acc = (C.c_uint8 * W)(*[1 if a else 0 for a in accumulate_mask])
     if random is None:
-        rc = lib().oracle_step_threshold(_f32(w), _ptr_array(g), _ptr_array(r), acc, W, tab, _u32(leaders),
+        rc = lib().oracle_step_threshold(_f32(w), _ptr_array(g), _ptr_array(r), acc, C.c_float(momentum), W, tab, _u32(leaders),
                                          leaders.shape[1], _f32(thr), per_slot, len(rows), C.c_float(eps),
                                          C.c_float(scale), _u8(mask), _u32(counts), _u32(idx), _f32(sm), max_pairs,
                                          C.byref(total))
     else:
-        rc = lib().oracle_step_threshold_random(_f32(w), _ptr_array(g), _ptr_array(r), acc, W, tab, _u32(leaders),
+        rc = lib().oracle_step_threshold_random(_f32(w), _ptr_array(g), _ptr_array(r), acc, C.c_float(momentum), W, tab, _u32(leaders),
                                                 leaders.shape[1], _f32(thr), per_slot, int(random[0]), int(random[1]),
                                                 len(rows), C.c_float(eps), C.c_float(scale), _u8(mask), _u32(counts),
                                                 _u32(idx), _f32(sm), max_pairs, C.byref(total))
@@ -314,7 +321,7 @@ def layerwise_threshold(mean: float, var: float, alpha: float, beta: float, c: f
 
 def step_layerwise(w: np.ndarray, g: Sequence[np.ndarray], r: Sequence[np.ndarray], rows, leaders: np.ndarray,
                    alpha: float, beta: float, c: float, eps: float, scale: float, max_pairs: int,
-                   accumulate_mask: Sequence[int] | None = None):
+                   accumulate_mask: Sequence[int] | None = None, momentum: float = 1.0):
     """One whole step with layer-wise thresholds.
     -> (stats[n_layers, n_lead, 2] float64, thr[n_layers, n_lead] float32, mask, counts, idx, sum)."""
     rows = list(rows)
@@ -332,7 +339,7 @@ def step_layerwise(w: np.ndarray, g: Sequence[np.ndarray], r: Sequence[np.ndarra
     acc = None
     if accumulate_mask is not None:
         acc = (C.c_uint8 * W)(*[1 if a else 0 for a in accumulate_mask])
-    rc = lib().oracle_step_layerwise(_f32(w), _ptr_array(g), _ptr_array(r), acc, W, tab, _u32(leaders), n_lead,
+    rc = lib().oracle_step_layerwise(_f32(w), _ptr_array(g), _ptr_array(r), acc, C.c_float(momentum), W, tab, _u32(leaders), n_lead,
                                      alpha, beta, c, len(rows), C.c_float(eps), C.c_float(scale),
                                      stats.ctypes.data_as(C.POINTER(C.c_double)), _f32(thr), _u8(mask), _u32(counts),
                                      _u32(idx), _f32(sm), max_pairs, C.byref(total))

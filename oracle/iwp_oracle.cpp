@@ -48,6 +48,11 @@
 //       threshold for a large ratio and lowers it otherwise), binary64, rounded once to binary32
 //   then T1..T4 with each chosen node using its own threshold.
 //
+// Momentum-weighted residual (Eq. 3: what is sparsified is m * g_{t-1} + g_t, the residual
+// "accumulated local with momentum"):
+//   M1  r[i] <- (m * r[i]) + g[i], product rounded, then sum rounded (no contraction);
+//       m = 1 is O1.  The whole-step functions take m and use M1 in place of O1.
+//
 // Random gradient selection (Section 3.3): an element that is not above the threshold is
 // still sent with probability importance / threshold.
 //   S1  the draw: Philox-4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw: "Parallel random
@@ -112,6 +117,14 @@ extern "C" {
 // O1.  Alg. 1 accumulation line / Eq. 3: one fp32 add per element.
 void oracle_accumulate(float* r, const float* g, uint64_t n) {
     for (uint64_t i = 0; i < n; ++i) r[i] = r[i] + g[i];
+}
+
+// M1: local accumulation with momentum, r <- (m * r) + g, two roundings.
+void oracle_accumulate_momentum(float* r, const float* g, uint64_t n, float m) {
+    for (uint64_t i = 0; i < n; ++i) {
+        float decayed = m * r[i];
+        r[i] = decayed + g[i];
+    }
 }
 
 // O2.  Alg. 1 mask line: importance of every element, eps added to |w| in fp32
@@ -225,7 +238,7 @@ void oracle_apply_sparse_update(float* w, const uint32_t* idx, const float* sum,
 // within the layer, layers in table order); then reduce, update and clear over
 // the concatenated index list.  pairs_total = sum of k over the table.
 // accumulate[p] == 0 skips O1 for worker p (a peer whose residual is static).
-int oracle_step(float* w, const float* const* g, float* const* r, const uint8_t* accumulate, uint32_t W,
+int oracle_step(float* w, const float* const* g, float* const* r, const uint8_t* accumulate, float momentum, uint32_t W,
                 const oracle_layer* layers, const uint32_t* leader, uint32_t n_layers, float eps,
                 float scale, uint32_t* idx_out, float* val_out, float* sum_out, oracle_threshold* thr_out) {
     uint64_t pairs_total = 0;
@@ -235,7 +248,7 @@ int oracle_step(float* w, const float* const* g, float* const* r, const uint8_t*
         if (L.out_offset != pairs_total) return -3;  // pairs of the layers are packed back to back
         for (uint32_t p = 0; p < W; ++p) {
             if (accumulate && !accumulate[p]) continue;
-            oracle_accumulate(r[p] + L.offset, g[p] + L.offset, L.n);
+            oracle_accumulate_momentum(r[p] + L.offset, g[p] + L.offset, L.n, momentum);
         }
         if (L.k == 0) continue;
         uint32_t lead = leader[j];
@@ -335,7 +348,8 @@ void oracle_mask_threshold_random(const float* w, const float* r, uint64_t n, fl
 namespace {
 struct RandomSelection { uint64_t seed, step; };
 
-int step_threshold_impl(float* w, const float* const* g, float* const* r, const uint8_t* accumulate, uint32_t W,
+int step_threshold_impl(float* w, const float* const* g, float* const* r, const uint8_t* accumulate, float momentum,
+                        uint32_t W,
                         const oracle_layer* layers, const uint32_t* leaders, uint32_t n_lead, const float* thr,
                         uint32_t thr_per_slot, const RandomSelection* rs, uint32_t n_layers, float eps, float scale,
                         uint8_t* mask_out, uint32_t* count_out, uint32_t* idx_out, float* sum_out, uint64_t max_pairs,
@@ -345,7 +359,7 @@ int step_threshold_impl(float* w, const float* const* g, float* const* r, const 
         const oracle_layer& L = layers[j];
         for (uint32_t p = 0; p < W; ++p) {
             if (accumulate && !accumulate[p]) continue;
-            oracle_accumulate(r[p] + L.offset, g[p] + L.offset, L.n);
+            oracle_accumulate_momentum(r[p] + L.offset, g[p] + L.offset, L.n, momentum);
         }
         const uint64_t nbytes = oracle_mask_bytes(L.n);
         uint8_t* mask = mask_out + mask_off;
@@ -381,23 +395,24 @@ int step_threshold_impl(float* w, const float* const* g, float* const* r, const 
 extern "C" {
 
 // thr_per_slot != 0: thr holds n_layers x n_lead values, one per chosen node.
-int oracle_step_threshold(float* w, const float* const* g, float* const* r, const uint8_t* accumulate, uint32_t W,
+int oracle_step_threshold(float* w, const float* const* g, float* const* r, const uint8_t* accumulate, float momentum,
+                          uint32_t W,
                           const oracle_layer* layers, const uint32_t* leaders, uint32_t n_lead,
                           const float* thr, uint32_t thr_per_slot, uint32_t n_layers, float eps, float scale,
                           uint8_t* mask_out, uint32_t* count_out, uint32_t* idx_out, float* sum_out,
                           uint64_t max_pairs, uint64_t* total_out) {
-    return step_threshold_impl(w, g, r, accumulate, W, layers, leaders, n_lead, thr, thr_per_slot, nullptr, n_layers,
+    return step_threshold_impl(w, g, r, accumulate, momentum, W, layers, leaders, n_lead, thr, thr_per_slot, nullptr, n_layers,
                                eps, scale, mask_out, count_out, idx_out, sum_out, max_pairs, total_out);
 }
 
 // The same step with random gradient selection (S1, S2) on every chosen node.
 int oracle_step_threshold_random(float* w, const float* const* g, float* const* r, const uint8_t* accumulate,
-                                 uint32_t W, const oracle_layer* layers, const uint32_t* leaders, uint32_t n_lead,
+                                 float momentum, uint32_t W, const oracle_layer* layers, const uint32_t* leaders, uint32_t n_lead,
                                  const float* thr, uint32_t thr_per_slot, uint64_t seed, uint64_t step,
                                  uint32_t n_layers, float eps, float scale, uint8_t* mask_out, uint32_t* count_out,
                                  uint32_t* idx_out, float* sum_out, uint64_t max_pairs, uint64_t* total_out) {
     const RandomSelection rs{seed, step};
-    return step_threshold_impl(w, g, r, accumulate, W, layers, leaders, n_lead, thr, thr_per_slot, &rs, n_layers, eps,
+    return step_threshold_impl(w, g, r, accumulate, momentum, W, layers, leaders, n_lead, thr, thr_per_slot, &rs, n_layers, eps,
                                scale, mask_out, count_out, idx_out, sum_out, max_pairs, total_out);
 }
 
@@ -430,7 +445,8 @@ float oracle_layerwise_threshold(double mean, double var, double alpha, double b
 // One whole iteration with layer-wise thresholds: accumulate, L1 + L2 on every chosen node
 // (stats_out: n_layers x n_lead x {mean, var}; thr_out: n_layers x n_lead), then the
 // threshold-mode step with those thresholds.
-int oracle_step_layerwise(float* w, const float* const* g, float* const* r, const uint8_t* accumulate, uint32_t W,
+int oracle_step_layerwise(float* w, const float* const* g, float* const* r, const uint8_t* accumulate, float momentum,
+                          uint32_t W,
                           const oracle_layer* layers, const uint32_t* leaders, uint32_t n_lead, double alpha,
                           double beta, double C, uint32_t n_layers, float eps, float scale, double* stats_out,
                           float* thr_out, uint8_t* mask_out, uint32_t* count_out, uint32_t* idx_out,
@@ -439,7 +455,7 @@ int oracle_step_layerwise(float* w, const float* const* g, float* const* r, cons
         const oracle_layer& L = layers[j];
         for (uint32_t p = 0; p < W; ++p) {
             if (accumulate && !accumulate[p]) continue;
-            oracle_accumulate(r[p] + L.offset, g[p] + L.offset, L.n);
+            oracle_accumulate_momentum(r[p] + L.offset, g[p] + L.offset, L.n, momentum);
         }
         for (uint32_t q = 0; q < n_lead; ++q) {
             const uint32_t lead = leaders[(size_t)j * n_lead + q];
@@ -452,7 +468,7 @@ int oracle_step_layerwise(float* w, const float* const* g, float* const* r, cons
         }
     }
     std::vector<uint8_t> none(W, 0);                 // everything is accumulated already
-    return oracle_step_threshold(w, g, r, none.data(), W, layers, leaders, n_lead, thr_out, 1, n_layers, eps, scale,
+    return oracle_step_threshold(w, g, r, none.data(), 1.0f, W, layers, leaders, n_lead, thr_out, 1, n_layers, eps, scale,
                                  mask_out, count_out, idx_out, sum_out, max_pairs, total_out);
 }
 
