@@ -139,6 +139,16 @@ typedef struct iwp_plan iwp_plan;
  * no overlap in table order, range). */
 int iwp_plan_create(const iwp_layer* layers, uint32_t n_layers, iwp_plan** plan_out);
 void iwp_plan_destroy(iwp_plan* plan);
+/* Momentum-weighted residual (Eq. 3: what is sparsified is m * g_{t-1} + g_t, the residual
+ * accumulated locally with momentum).  After this call every entry point that accumulates
+ * through the plan (compress_segmented, iwp_step_segmented, iwp_step_threshold_segmented,
+ * iwp_step_threshold_random_segmented, iwp_step_layerwise_segmented) computes
+ * r[i] <- (m * r[i]) + g[i], the product rounded to binary32, then the sum (never fused).
+ * m = 1 (the state of a new plan) is the plain accumulation, bit for bit.  m must be
+ * finite.  Host-side state of the plan: takes effect for calls issued afterwards;
+ * compress_layer has no plan and always uses m = 1. */
+int iwp_plan_set_momentum(iwp_plan* plan, float momentum);
+
 /* Workspace bytes the segmented calls need for this plan (256-byte aligned). */
 size_t iwp_plan_workspace_bytes(const iwp_plan* plan);
 /* Workspace bytes iwp_step_segmented needs for this plan and W residual buffers. */

@@ -199,6 +199,7 @@ struct iwp_plan {
     Sizes z{};
     uint64_t flat_end = 0;        // one past the last element any layer covers
     bool any_k = false;
+    float momentum = 1.0f;        // r <- momentum * r + g in every call that accumulates through this plan
 };
 
 extern "C" {
@@ -252,6 +253,7 @@ static int single_common(SingleOp op, const float* w, const float* g, float* r, 
     memset(&P, 0, sizeof P);
     P.g[0] = g;
     P.r[0] = r;
+    P.momentum = 1.0f;
     ResidualPtrs R;
     memset(&R, 0, sizeof R);
     R.r[0] = r;
@@ -394,6 +396,12 @@ void iwp_plan_destroy(iwp_plan* plan) {
     delete plan;
 }
 
+int iwp_plan_set_momentum(iwp_plan* plan, float momentum) {
+    if (!plan || !std::isfinite(momentum)) return IWP_EINVAL;
+    plan->momentum = momentum;
+    return IWP_OK;
+}
+
 size_t iwp_plan_workspace_bytes(const iwp_plan* plan) { return plan ? carve(nullptr, plan->z).bytes : 0; }
 
 size_t iwp_plan_step_workspace_bytes(const iwp_plan* plan, uint32_t W) {
@@ -411,10 +419,12 @@ static int check_ws(size_t need, void* workspace, size_t workspace_bytes) {
     return IWP_OK;
 }
 
-static int worker_tables(const float* const* g, float* const* r, uint32_t W, WorkerPtrs* P, ResidualPtrs* R) {
+static int worker_tables(const float* const* g, float* const* r, uint32_t W, float momentum, WorkerPtrs* P,
+                         ResidualPtrs* R) {
     if (!g || !r || W == 0 || W > IWP_MAX_WORKERS) return IWP_EINVAL;
     memset(P, 0, sizeof *P);
     memset(R, 0, sizeof *R);
+    P->momentum = momentum;
     for (uint32_t p = 0; p < W; ++p) {
         if (!r[p]) return IWP_EINVAL;
         if (!aligned4(r[p]) || !aligned4(g[p])) return IWP_EALIGN;
@@ -438,7 +448,7 @@ int compress_segmented(const iwp_plan* plan, const float* w, const float* const*
     if (thr_hint && thr_hint == thr_out) return IWP_EINVAL;   // the hint is read while the records are written
     WorkerPtrs P;
     ResidualPtrs R;
-    int rc = worker_tables(g, r, W, &P, &R);
+    int rc = worker_tables(g, r, W, plan->momentum, &P, &R);
     if (rc) return rc;
     Workspace ws = carve(workspace, plan->z);
     rc = check_ws(ws.bytes, workspace, workspace_bytes);
@@ -467,7 +477,7 @@ int iwp_step_segmented(const iwp_plan* plan, float* w, const float* const* g, fl
     if (thr_hint && thr_hint == thr_out) return IWP_EINVAL;   // the hint is read while the records are written
     WorkerPtrs P;
     ResidualPtrs R;
-    int rc = worker_tables(g, r, W, &P, &R);
+    int rc = worker_tables(g, r, W, plan->momentum, &P, &R);
     if (rc) return rc;
     Sizes z = plan->z;
     z.W_gather = W;
@@ -518,6 +528,7 @@ int select_threshold_segmented(const iwp_plan* plan, const float* w, const float
     WorkerPtrs P;
     memset(&P, 0, sizeof P);
     P.r[0] = const_cast<float*>(r);       // no gradient pointer: the residual is only read
+    P.momentum = 1.0f;
     ResidualPtrs R;
     memset(&R, 0, sizeof R);
     R.r[0] = const_cast<float*>(r);
@@ -598,7 +609,7 @@ static int run_threshold_step(const iwp_plan* plan, float* w, const float* const
         return IWP_EALIGN;
     WorkerPtrs P;
     ResidualPtrs R;
-    int rc = worker_tables(g, r, W, &P, &R);
+    int rc = worker_tables(g, r, W, plan->momentum, &P, &R);
     if (rc) return rc;
     const Sizes& z = plan->z;
     ThresholdWorkspace ws = carve_threshold(workspace, z, W, n_lead, max_pairs);

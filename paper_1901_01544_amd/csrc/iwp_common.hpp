@@ -16,6 +16,18 @@ namespace iwp {
 
 typedef float v4f __attribute__((ext_vector_type(4)));   // one 128-bit access
 
+// Local accumulation with momentum (Eq. 3): the product is rounded, then the sum
+// (contraction is off for the whole library).  m = 1 leaves the product exact, so the
+// result is bit for bit the plain r + g.
+__device__ __forceinline__ float accum(float r, float g, float m) {
+    const float decayed = m * r;
+    return decayed + g;
+}
+__device__ __forceinline__ v4f accum(v4f r, v4f g, float m) {
+    const v4f decayed = r * m;
+    return decayed + g;
+}
+
 constexpr int BLOCK = 256;                         // 4 wavefronts
 constexpr int WAVE = 64;
 constexpr int VEC = 4;
@@ -73,6 +85,7 @@ struct StageArrays {       // staged candidates, structure of arrays; tile t of 
 struct WorkerPtrs {        // passed by value as a kernel argument
     const float* g[IWP_MAX_WORKERS];
     float* r[IWP_MAX_WORKERS];
+    float momentum;        // local accumulation is r <- momentum * r + g (Eq. 3); 1 = plain accumulation
 };
 
 struct ResidualPtrs {

@@ -31,7 +31,7 @@ struct LeadCtx {
 
 // One tile of a plain worker: r <- r + g, streaming (non-temporal) accesses.
 __device__ __forceinline__ void stream_tile(const float* __restrict__ gl, float* __restrict__ rl, uint32_t n,
-                                            uint32_t base, bool vec) {
+                                            uint32_t base, bool vec, float m) {
     const uint32_t tid = threadIdx.x;
     if (vec && base + TILE <= n) {
         v4f rr[CHUNKS_PER_TILE], gg[CHUNKS_PER_TILE];
@@ -44,7 +44,7 @@ __device__ __forceinline__ void stream_tile(const float* __restrict__ gl, float*
 #pragma unroll
         for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
             const uint32_t i = base + u * CHUNK + tid * VEC;
-            store_v4<true>(rl + i, rr[u] + gg[u]);
+            store_v4<true>(rl + i, accum(rr[u], gg[u], m));
         }
     } else {
         // ragged tail of a layer, or a layer whose base is not 16-byte aligned
@@ -55,7 +55,7 @@ __device__ __forceinline__ void stream_tile(const float* __restrict__ gl, float*
             load_quad(rl, i, n, vec, rv);
             load_quad(gl, i, n, vec, gv);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) rv[q] = rv[q] + gv[q];
+            for (int q = 0; q < 4; ++q) rv[q] = accum(rv[q], gv[q], m);
             store_quad(rl, i, n, vec, rv);
         }
     }
@@ -70,7 +70,7 @@ __device__ __forceinline__ void stream_tile(const float* __restrict__ gl, float*
 template <bool ACC>
 __device__ __forceinline__ void lead_tile(const float* __restrict__ gl, float* __restrict__ rl,
                                           const float* __restrict__ wl, uint32_t n, uint32_t lt, bool vec,
-                                          float eps, const LeadCtx& C) {
+                                          float eps, float m, const LeadCtx& C) {
     const uint32_t tid = threadIdx.x;
     const uint32_t base = lt * TILE;
     uint32_t key[CHUNKS_PER_TILE][4];
@@ -88,7 +88,7 @@ __device__ __forceinline__ void lead_tile(const float* __restrict__ gl, float* _
         for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
             const uint32_t i = base + u * CHUNK + tid * VEC;
             if (ACC) {
-                rr[u] = rr[u] + gg[u];
+                rr[u] = accum(rr[u], gg[u], m);
                 store_v4<true>(rl + i, rr[u]);
             }
             val[u][0] = rr[u].x; val[u][1] = rr[u].y; val[u][2] = rr[u].z; val[u][3] = rr[u].w;
@@ -108,7 +108,7 @@ __device__ __forceinline__ void lead_tile(const float* __restrict__ gl, float* _
                 if (ACC) {
                     load_quad(gl, i, n, vec, gv);
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) val[u][q] = val[u][q] + gv[q];
+                    for (int q = 0; q < 4; ++q) val[u][q] = accum(val[u][q], gv[q], m);
                     store_quad(rl, i, n, vec, val[u]);
                 }
                 load_quad(wl, i, n, vec, wv, 1.0f);
@@ -132,7 +132,7 @@ __device__ __forceinline__ void lead_tile(const float* __restrict__ gl, float* _
 // The leader's share of one group (up to LGROUP tiles of the same layer):
 // one LDS histogram of the top digit for the whole group, flushed once.
 __device__ __forceinline__ void leader_group(const float* gp, float* rp, const float* __restrict__ w, const DevLayer& L,
-                                             uint32_t first_tile /*in layer*/, float eps, LeadCtx& C,
+                                             uint32_t first_tile /*in layer*/, float eps, float m, LeadCtx& C,
                                              uint32_t* __restrict__ ghist) {
     for (uint32_t b = threadIdx.x; b < HIST0; b += BLOCK) C.lh[b] = 0u;
     __syncthreads();
@@ -143,8 +143,8 @@ __device__ __forceinline__ void leader_group(const float* gp, float* rp, const f
     const uint32_t ntiles = (L.n + TILE - 1) / TILE;
     const uint32_t last = min(first_tile + LGROUP, ntiles);
     for (uint32_t t = first_tile; t < last; ++t) {
-        if (gp) lead_tile<true>(gl, rl, wl, L.n, t, vec, eps, C);
-        else lead_tile<false>(gl, rl, wl, L.n, t, vec, eps, C);
+        if (gp) lead_tile<true>(gl, rl, wl, L.n, t, vec, eps, m, C);
+        else lead_tile<false>(gl, rl, wl, L.n, t, vec, eps, m, C);
     }
     __syncthreads();
     for (uint32_t b = threadIdx.x; b < HIST0; b += BLOCK) {
@@ -188,13 +188,13 @@ __global__ __launch_bounds__(BLOCK) void k_accumulate_all(WorkerPtrs P, const fl
     if (L.k > 0 && leader_of(leader, j, W) == p) {
         if (lt % LGROUP) return;
         LeadCtx C = lead_ctx(lh, slot, L, state, j, stage_cnt, A);
-        leader_group(gp, rp, w, L, lt, eps, C, hist + (size_t)j * HIST_STRIDE);
+        leader_group(gp, rp, w, L, lt, eps, P.momentum, C, hist + (size_t)j * HIST_STRIDE);
         return;
     }
     if (!gp) return;
     float* rl = rp + L.offset;
     const float* gl = gp + L.offset;
-    stream_tile(gl, rl, L.n, lt * TILE, is_aligned16(rl) && is_aligned16(gl));
+    stream_tile(gl, rl, L.n, lt * TILE, is_aligned16(rl) && is_aligned16(gl), P.momentum);
 }
 
 // Leaders only: one workgroup per group of LGROUP tiles of every layer with k > 0.
@@ -215,7 +215,7 @@ __global__ __launch_bounds__(BLOCK) void k_leader_pass(WorkerPtrs P, const float
     if (first * TILE >= L.n) return;
     const uint32_t p = leader_of(leader, j, W);
     LeadCtx C = lead_ctx(lh, slot, L, state, j, stage_cnt, A);
-    leader_group(P.g[p], P.r[p], w, L, first, eps, C, hist + (size_t)j * HIST_STRIDE);
+    leader_group(P.g[p], P.r[p], w, L, first, eps, P.momentum, C, hist + (size_t)j * HIST_STRIDE);
 }
 
 // The other workers, after the leader's pairs are known: accumulate, and where the
@@ -281,7 +281,7 @@ __global__ __launch_bounds__(BLOCK) void k_follow_gather(WorkerPtrs P, WorkerLis
 #pragma unroll
         for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
             const uint32_t loc = u * CHUNK + tid * VEC;
-            rr[u] = rr[u] + gg[u];
+            rr[u] = accum(rr[u], gg[u], P.momentum);
             const uint32_t nib = cnt ? (map[loc >> 5] >> (loc & 31u)) & 0xFu : 0u;
             if (nib) {
                 uint32_t rank = bitmap_rank(map, pre, loc);
@@ -305,7 +305,7 @@ __global__ __launch_bounds__(BLOCK) void k_follow_gather(WorkerPtrs P, WorkerLis
             uint32_t rank = nib ? bitmap_rank(map, pre, loc) : 0u;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                rv[q] = rv[q] + gv[q];
+                rv[q] = accum(rv[q], gv[q], P.momentum);
                 if ((nib >> q) & 1u) { go[rank++] = rv[q]; rv[q] = 0.0f; }
             }
             store_quad(rl, i, L.n, vec, rv);

@@ -68,8 +68,8 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 // One tile of a chosen node in registers: residual (after adding the gradient and storing
 // it back when gp is set) and weights, 16 values per lane; positions past the layer's end
 // read as r = 0, w = 1.
-__device__ __forceinline__ void chosen_tile(const float* gp, float* rl, const float* gl, const float* wl, uint32_t n,
-                                            uint32_t base, uint32_t tid, float (&rv)[CHUNKS_PER_TILE][4],
+__device__ __forceinline__ void chosen_tile(const float* gp, float* rl, const float* gl, const float* wl, float m,
+                                            uint32_t n, uint32_t base, uint32_t tid, float (&rv)[CHUNKS_PER_TILE][4],
                                             float (&wv)[CHUNKS_PER_TILE][4]) {
     const bool vec = is_aligned16(rl) && is_aligned16(wl) && (!gp || is_aligned16(gl));
     if (vec && base + TILE <= n) {
@@ -85,7 +85,7 @@ __device__ __forceinline__ void chosen_tile(const float* gp, float* rl, const fl
         for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
             const uint32_t i = base + u * CHUNK + tid * VEC;
             if (gp) {
-                rr[u] = rr[u] + gg[u];
+                rr[u] = accum(rr[u], gg[u], m);
                 store_v4<true>(rl + i, rr[u]);
             }
             rv[u][0] = rr[u].x; rv[u][1] = rr[u].y; rv[u][2] = rr[u].z; rv[u][3] = rr[u].w;
@@ -103,7 +103,7 @@ __device__ __forceinline__ void chosen_tile(const float* gp, float* rl, const fl
                     float gv[4];
                     load_quad(gl, i, n, vec, gv);
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) rv[u][c] = rv[u][c] + gv[c];
+                    for (int c = 0; c < 4; ++c) rv[u][c] = accum(rv[u][c], gv[c], m);
                     store_quad(rl, i, n, vec, rv[u]);
                 }
                 load_quad(wl, i, n, vec, wv[u], 1.0f);
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(BLOCK) void k_leader_mask(WorkerPtrs P, const float
     const uint32_t nwords = (L.n + 31) / 32;
     uint32_t* mw = lmask + (size_t)q * mask_words + L.mask_begin;
     float rv[CHUNKS_PER_TILE][4], wv[CHUNKS_PER_TILE][4];
-    chosen_tile(gp, P.r[p] + L.offset, gp ? gp + L.offset : nullptr, w + L.offset, L.n, base, tid, rv, wv);
+    chosen_tile(gp, P.r[p] + L.offset, gp ? gp + L.offset : nullptr, w + L.offset, P.momentum, L.n, base, tid, rv, wv);
 #pragma unroll
     for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
         const uint32_t i = base + u * CHUNK + tid * VEC;
@@ -197,7 +197,7 @@ __global__ __launch_bounds__(BLOCK) void k_leader_stats(WorkerPtrs P, const floa
     const uint32_t base = (t - L.tile_begin) * TILE;
     const float* gp = P.g[p];
     float rv[CHUNKS_PER_TILE][4], wv[CHUNKS_PER_TILE][4];
-    chosen_tile(gp, P.r[p] + L.offset, gp ? gp + L.offset : nullptr, w + L.offset, L.n, base, tid, rv, wv);
+    chosen_tile(gp, P.r[p] + L.offset, gp ? gp + L.offset : nullptr, w + L.offset, P.momentum, L.n, base, tid, rv, wv);
     float sc[CHUNKS_PER_TILE][4];
     double lane_sum = 0.0;
 #pragma unroll
@@ -437,7 +437,7 @@ __global__ __launch_bounds__(BLOCK) void k_follow_mask(WorkerPtrs P, const DevLa
 #pragma unroll
         for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
             const uint32_t loc = u * CHUNK + tid * VEC;
-            rr[u] = rr[u] + gg[u];
+            rr[u] = accum(rr[u], gg[u], P.momentum);
             const uint32_t nib = (map[loc >> 5] >> (loc & 31u)) & 0xFu;
             if (nib) {
                 uint32_t rank = bitmap_rank(map, pre, loc);
@@ -460,7 +460,7 @@ __global__ __launch_bounds__(BLOCK) void k_follow_mask(WorkerPtrs P, const DevLa
             uint32_t rank = nib ? bitmap_rank(map, pre, loc) : 0u;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                rv[q] = rv[q] + gv[q];
+                rv[q] = accum(rv[q], gv[q], P.momentum);
                 if ((nib >> q) & 1u) { if (rank < room) go[rank] = rv[q]; ++rank; rv[q] = 0.0f; }
             }
             store_quad(rl, i, L.n, vec, rv);

@@ -61,6 +61,8 @@ def load() -> C.CDLL:
     L.iwp_step_segmented.argtypes = [_vp, _vp, C.POINTER(_vp), C.POINTER(_vp), C.c_uint32, _vp, _vp, C.c_float,
                                      C.c_float, _vp, _vp, _vp, _vp, _vp, C.c_size_t, _vp]
     L.iwp_step_segmented.restype = C.c_int
+    L.iwp_plan_set_momentum.argtypes = [_vp, C.c_float]
+    L.iwp_plan_set_momentum.restype = C.c_int
     L.iwp_plan_mask_bytes.argtypes = [_vp]
     L.iwp_plan_mask_bytes.restype = C.c_size_t
     L.iwp_plan_threshold_workspace_bytes.argtypes = [_vp, C.c_uint32, C.c_uint32, C.c_uint32]
@@ -190,6 +192,9 @@ class Plan:
 
     def step_workspace_bytes(self, W: int) -> int:
         return int(load().iwp_plan_step_workspace_bytes(self._h, W))
+
+    def set_momentum(self, m: float) -> None:
+        _check(load().iwp_plan_set_momentum(self._h, m), "iwp_plan_set_momentum")
 
     @property
     def mask_bytes(self) -> int:

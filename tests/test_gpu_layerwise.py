@@ -20,7 +20,7 @@ EPS = 1e-8
 RTOL = 1e-6
 
 
-def _oracle_stats(w_ref, r_ref, g_np, ps, leaders, W):
+def _oracle_stats(w_ref, r_ref, g_np, ps, leaders, W, momentum=1.0):
     """Oracle statistics of every (layer, slot) on accumulated copies."""
     nl, n_lead = leaders.shape
     out = np.zeros((nl, n_lead, 2))
@@ -32,7 +32,7 @@ def _oracle_stats(w_ref, r_ref, g_np, ps, leaders, W):
             if (j, p) not in acc:
                 a = r_ref[p][sl].copy()
                 if g_np[p] is not None:
-                    oracle.accumulate(a, np.ascontiguousarray(g_np[p][sl]))
+                    oracle.accumulate_momentum(a, np.ascontiguousarray(g_np[p][sl]), momentum)
                 acc[(j, p)] = a
             out[j, q] = oracle.layer_stats(np.ascontiguousarray(w_ref[sl]), acc[(j, p)], EPS)
     return out
@@ -42,7 +42,7 @@ def _close(a, b):
     return np.all((np.abs(a - b) <= RTOL * np.abs(b)) | (a == b) | (np.isnan(a) & np.isnan(b)))
 
 
-def _run(iwp, ps, W, n_lead, steps, seed, static=(), rule=None, zero_layer=None):
+def _run(iwp, ps, W, n_lead, steps, seed, static=(), rule=None, zero_layer=None, momentum=1.0):
     rng = np.random.default_rng(seed)
     w = wl.gen_weights(ps)
     pool = [wl.gen_gradient(ps, s) for s in range(3)]
@@ -54,6 +54,8 @@ def _run(iwp, ps, W, n_lead, steps, seed, static=(), rule=None, zero_layer=None)
     w_ref, r_ref = w.copy(), [x.copy() for x in r0]
     max_pairs = int(ps.flat) + 8
     ts = ThresholdSet(iwp, ps, w, pool, r0, n_lead, max_pairs)
+    if momentum != 1.0:
+        ts.plan.set_momentum(momentum)
     rows = ps.rows()
     nl = len(ps.layers)
     branches = set()
@@ -64,7 +66,7 @@ def _run(iwp, ps, W, n_lead, steps, seed, static=(), rule=None, zero_layer=None)
         if n_lead > 1:
             leaders[rng.integers(0, nl)] = leaders[0, 0]       # one layer lists a node in every slot
         leaders[rng.integers(0, nl), 0] = W + 3                # out of range: node 0
-        want = _oracle_stats(w_ref, r_ref, g_np, ps, leaders, W)
+        want = _oracle_stats(w_ref, r_ref, g_np, ps, leaders, W, momentum)
         if rule is None:
             with np.errstate(invalid="ignore", divide="ignore"):
                 ratio = want[:, :, 1] / want[:, :, 0]
@@ -104,7 +106,7 @@ def _run(iwp, ps, W, n_lead, steps, seed, static=(), rule=None, zero_layer=None)
         mask_ref, cnt_ref, idx_ref, sum_ref = oracle.step_threshold(
             w_ref, [g if g is not None else zero for g in g_np], r_ref, rows, np.where(leaders >= W, 0, leaders),
             np.ascontiguousarray(thr.reshape(nl, n_lead)) if n_lead > 1 else np.ascontiguousarray(thr[:, 0]),
-            EPS, float(scale), max_pairs, accumulate_mask=[g is not None for g in g_np])
+            EPS, float(scale), max_pairs, accumulate_mask=[g is not None for g in g_np], momentum=momentum)
         got = ts.download()
         total = int(cnt_ref.sum())
         assert np.array_equal(got["count"][:nl], cnt_ref), "%s counts %s vs %s" % (tag, got["count"][:nl], cnt_ref)
@@ -146,6 +148,11 @@ def test_layerwise_negative_threshold_sends_everything(gpu_lib):
     """alpha - beta * ratio below zero: every element of the layer is above it, zeros included."""
     ps = wl.custom_set([(10_000, 0), (4097, 0)], W=2, seed=6, align=64)
     _run(gpu_lib, ps, 2, 1, steps=2, seed=10, rule=(0.0, 1.0, 1e30))
+
+
+def test_layerwise_with_momentum(gpu_lib):
+    ps = wl.custom_set(RAGGED, W=4, seed=27, align=1, start=1)
+    _run(gpu_lib, ps, 4, 2, steps=3, seed=207, static=(2,), momentum=0.9)
 
 
 def test_layerwise_config1(gpu_lib):

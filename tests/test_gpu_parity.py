@@ -229,12 +229,15 @@ def _route(fused):
     return dict(fused=True, hint=fused)
 
 
-def _run_steps(iwp, ps, steps, pool, W=None, r0=None, g_ids_fn=None, leader_fn=None, tag="", fused=False):
+def _run_steps(iwp, ps, steps, pool, W=None, r0=None, g_ids_fn=None, leader_fn=None, tag="", fused=False,
+               momentum=None, sets=None):
     W = ps.W if W is None else W
     w = wl.gen_weights(ps)
-    sets = [wl.gen_gradient(ps, s) for s in range(pool)]
+    sets = [wl.gen_gradient(ps, s) for s in range(pool)] if sets is None else sets
     r_ref = [np.zeros(ps.flat, np.float32) for _ in range(W)] if r0 is None else [x.copy() for x in r0]
     gs = GpuSet(iwp, ps, w, sets, r_np=r0, W=W, **_route(fused))
+    if momentum is not None:
+        gs.plan.set_momentum(momentum)
     w_ref = w.copy()
     for t in range(steps):
         lead = wl.leaders(ps, t, n_candidates=W) if leader_fn is None else leader_fn(t)
@@ -242,7 +245,8 @@ def _run_steps(iwp, ps, steps, pool, W=None, r0=None, g_ids_fn=None, leader_fn=N
         g = [sets[i] if i is not None else sets[0] for i in ids]
         acc = [i is not None for i in ids]
         idx_ref, val_ref, sum_ref, thr_ref = oracle.step(w_ref, g, r_ref, ps.rows(), lead, float(ps.eps),
-                                                         float(ps.scale), accumulate_mask=acc)
+                                                         float(ps.scale), accumulate_mask=acc,
+                                                         momentum=1.0 if momentum is None else momentum)
         gs.step(ids, lead)
         assert_step_equal(gs.download(), w_ref, r_ref, idx_ref, val_ref, sum_ref, thr_ref, ps.layers,
                           tag="%s step %d" % (tag, t))
@@ -379,6 +383,28 @@ def test_wrong_hints_change_nothing(gpu_lib, fused):
 def test_wrong_hints_config3(gpu_lib, fused):
     ps = wl.make_config(3)
     _run_steps(gpu_lib, ps, 3, pool=4, tag="cfg3 " + fused, fused=fused)
+
+
+@ROUTES
+def test_momentum_weighted_residual(gpu_lib, fused):
+    """Eq. 3: r <- m * r + g on every accumulating worker (leaders, followers, ragged and
+    misaligned layers), two roundings: one layer carries values for which a fused
+    multiply-add would give a different residual."""
+    m = float(np.float32(1 + 2.0 ** -12))
+    sizes = [(300, 5), (TILE + 1, 70), (777, 13), (40000, 625), (STILE + 3, 600), (2 * TILE, 100)]
+    for align, start in ((1, 3), (64, 0)):
+        ps = wl.custom_set(sizes, W=3, seed=90 + align, align=align, start=start, zero_frac=0.01)
+        sets = [wl.gen_gradient(ps, s) for s in range(3)]
+        r0 = [np.zeros(ps.flat, np.float32) for _ in range(3)]
+        L = ps.layers[-1]
+        for p in range(3):                                     # m * r = 1 + 2^-11 + 2^-24 -> tie; g cancels the rounded product
+            r0[p][L.offset:L.offset + L.n] = np.float32(1 + 2.0 ** -12)
+            for g in sets:
+                g[L.offset:L.offset + L.n:2] = np.float32(-(1 + 2.0 ** -11))
+        _run_steps(gpu_lib, ps, 3, pool=3, W=3, r0=r0, sets=sets, tag="momentum fma", fused=fused, momentum=m,
+                   g_ids_fn=lambda t: [(p + t) % 3 if p != 1 or t != 1 else None for p in range(3)])
+    ps = wl.make_config(1)
+    _run_steps(gpu_lib, ps, 4, pool=4, tag="cfg1 m=0.9", fused=fused, momentum=0.9)
 
 
 def test_determinism_run_to_run(gpu_lib):

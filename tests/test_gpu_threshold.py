@@ -42,7 +42,8 @@ def _thr_for(w, r_list, g_list, ps, density, rng):
     return thr
 
 
-def _run_case(iwp, ps, W, n_lead, steps, density, seed, static=(), slack=8, wild=True, align_msg="", random_seed=None):
+def _run_case(iwp, ps, W, n_lead, steps, density, seed, static=(), slack=8, wild=True, align_msg="", random_seed=None,
+              momentum=None):
     """random_seed: run with random gradient selection (Section 3.3), the step number as the draw's step."""
     rng = np.random.default_rng(seed)
     w = wl.gen_weights(ps)
@@ -54,6 +55,8 @@ def _run_case(iwp, ps, W, n_lead, steps, density, seed, static=(), slack=8, wild
     # capacity: generous, the oracle tells the real totals
     max_pairs = max(16, int(ps.flat) + slack)
     ts = ThresholdSet(iwp, ps, w, pool, r0, n_lead, max_pairs)
+    if momentum is not None:
+        ts.plan.set_momentum(momentum)
     rows = ps.rows()
     for t in range(steps):
         g_ids = [None if p in static else (p + t) % len(pool) for p in range(W)]
@@ -66,7 +69,8 @@ def _run_case(iwp, ps, W, n_lead, steps, density, seed, static=(), slack=8, wild
             w_ref, [g if g is not None else zero for g in g_np], r_ref, rows, np.where(leaders >= W, 0, leaders), thr,
             EPS, float(scale),
             max_pairs, accumulate_mask=[g is not None for g in g_np],
-            random=None if random_seed is None else (random_seed, 2 ** 32 * t + t))
+            random=None if random_seed is None else (random_seed, 2 ** 32 * t + t),
+            momentum=1.0 if momentum is None else momentum)
         ts.step(g_ids, leaders, thr, scale, random=None if random_seed is None else (random_seed, 2 ** 32 * t + t))
         got = ts.download()
         tag = "%s step %d" % (align_msg, t)
@@ -177,6 +181,13 @@ def test_random_selection_sends_more_than_plain_threshold(gpu_lib):
         ts.step([0, 1], leaders, thr, -0.01, random=random)
         masks.append(np.unpackbits(ts.download()["mask"], bitorder="little").astype(bool))
     assert np.all(masks[1][masks[0]]) and masks[1].sum() > masks[0].sum() > 0
+
+
+@pytest.mark.parametrize("random_seed", [None, 4242])
+def test_threshold_step_with_momentum(gpu_lib, random_seed):
+    """Eq. 3 accumulation (r <- m * r + g) on the chosen nodes and on the followers."""
+    ps = wl.custom_set(RAGGED, W=4, seed=41, align=1, start=2, zero_frac=0.01)
+    _run_case(gpu_lib, ps, 4, 2, steps=3, density=0.02, seed=401, static=(3,), random_seed=random_seed, momentum=0.9)
 
 
 def test_threshold_step_capacity(gpu_lib):
