@@ -43,6 +43,9 @@ def load() -> C.CDLL:
         raise FileNotFoundError(
             "%s is missing: build it with `python -m paper_1901_01544_amd.build`; "
             "there is no fallback path" % LIB_PATH)
+    # The device pointers and streams this binding passes come from torch, so the library has to
+    # bind to the HIP runtime torch carries: torch is imported (its runtime loaded) before the library.
+    import torch  # noqa: F401
     L = C.CDLL(LIB_PATH)
     L.iwp_workspace_bytes.argtypes = [C.c_uint32, C.c_uint32]
     L.iwp_workspace_bytes.restype = C.c_size_t

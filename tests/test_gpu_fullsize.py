@@ -95,3 +95,73 @@ def test_config5_full_size_two_steps(gpu_lib):
             assert torch.equal(peers_before[p], r[1 + p]), "peer %d step %d" % (p, t)
         del g, w_before, il, peers_before
         w_host = w.cpu().numpy()
+
+
+@pytest.mark.timeout(900)
+def test_config2_full_size_threshold_routes(gpu_lib):
+    """The AlexNet-shaped set at full size (61.1 M parameters, 8 workers, one chosen node
+    per layer: the configuration bench.py times on its threshold / layerwise routes): one
+    fixed-threshold step, one with random selection, one with layer-wise thresholds, each
+    against the oracle's whole step, every output bit for bit (the layer-wise statistics
+    to 1e-6 relative, its decisions from the device's thresholds)."""
+    import torch
+    from harness import ThresholdSet
+    iwp = gpu_lib
+    ps = wl.make_config(2)
+    W, nl = ps.W, len(ps.layers)
+    eps, scale = float(ps.eps), float(ps.scale)
+    w = wl.gen_weights(ps)
+    pool = [wl.gen_gradient(ps, s) for s in range(2)]
+    r0 = [np.zeros(ps.flat, np.float32) for _ in range(W)]
+    max_pairs = ps.flat // 4
+    ts = ThresholdSet(iwp, ps, w, pool, r0, 1, max_pairs)
+    w_ref, r_ref = w.copy(), [x.copy() for x in r0]
+    rows = ps.rows()
+    # thresholds that keep about 1/64 of each layer on worker 0's first accumulated gradient
+    thr = np.zeros(nl, np.float32)
+    for j, L in enumerate(ps.layers):
+        sl = slice(L.offset, L.offset + L.n)
+        s = oracle.score(np.ascontiguousarray(w[sl]), np.ascontiguousarray(pool[0][sl]), eps)
+        kk = max(1, L.n // 64)
+        thr[j] = np.partition(s, L.n - kk)[L.n - kk]
+
+    def compare(tag, ref):
+        mask_ref, cnt_ref, idx_ref, sum_ref = ref
+        got = ts.download()
+        total = int(cnt_ref.sum())
+        assert 0 < total <= max_pairs, (tag, total)
+        assert np.array_equal(got["count"][:nl], cnt_ref) and got["count"][nl] == total and got["count"][nl + 1] == 0, tag
+        assert np.array_equal(got["mask"], mask_ref), tag + " mask"
+        assert np.array_equal(got["idx"][:total], idx_ref), tag + " idx"
+        assert np.array_equal(bits(got["sum"][:total]), bits(sum_ref)), tag + " sum"
+        assert np.array_equal(bits(got["w"]), bits(w_ref)), tag + " w"
+        for p in range(W):
+            assert np.array_equal(bits(got["r"][p]), bits(r_ref[p])), "%s residual %d" % (tag, p)
+        return total
+
+    for t, mode in enumerate(("threshold", "random", "layerwise")):
+        ids = [(p + t) % 2 for p in range(W)]
+        g = [pool[i] for i in ids]
+        chosen = wl.chosen_nodes(ps, t, 1)
+        if mode == "layerwise":
+            alpha, beta, c = float(np.median(thr)), 1e-6, 50.0
+            acc = [None] * nl
+            want = np.zeros((nl, 2))
+            for j, L in enumerate(ps.layers):
+                sl = slice(L.offset, L.offset + L.n)
+                a = r_ref[chosen[j, 0]][sl].copy()
+                oracle.accumulate(a, np.ascontiguousarray(g[chosen[j, 0]][sl]))
+                want[j] = oracle.layer_stats(np.ascontiguousarray(w_ref[sl]), a, eps)
+            ts.step_layerwise(ids, chosen, alpha, beta, c, scale)
+            stats = ts.stats.cpu().numpy()[:, 0, :]
+            thr_dev = ts.thr_slots.cpu().numpy()[:, 0].copy()
+            assert np.all(np.abs(stats - want) <= 1e-6 * np.abs(want)), (stats, want)
+            for j in range(nl):
+                assert bits(oracle.layerwise_threshold(stats[j, 0], stats[j, 1], alpha, beta, c)) == bits(thr_dev[j])
+            ref = oracle.step_threshold(w_ref, g, r_ref, rows, chosen, thr_dev, eps, scale, max_pairs)
+        else:
+            rnd = (ps.seed, t) if mode == "random" else None
+            ref = oracle.step_threshold(w_ref, g, r_ref, rows, chosen, thr, eps, scale, max_pairs, random=rnd)
+            ts.step(ids, chosen, thr, scale, random=rnd)
+        total = compare(mode, ref)
+        print("%s: %d pairs sent" % (mode, total), flush=True)
