@@ -31,7 +31,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published peak HBM3E bandwidth
 WORKLOADS = {"tiny": 1, "alexnet": 2, "resnet50": 3, "many_small": 4, "flat": 5}
-DOMINANT_KERNEL = {"whole_step": "k_follow_gather", "three_calls": "k_accumulate_all", "threshold": "k_follow_mask",
+DOMINANT_KERNEL = {"whole_step": "k_follow_gather", "three_calls": "k_accumulate_rest", "threshold": "k_follow_mask",
                    "layerwise": "k_follow_mask"}
 
 
@@ -44,14 +44,14 @@ def step_bytes(ps, W_acc, W_list):
 
 def dominant_kernel_bytes(ps, W_acc, W_list, route):
     """Algorithmic bytes one launch of the dominant streaming kernel moves.
-    three_calls: every worker accumulates (12 B/elem) and the leader reads w (4 B/elem).
+    three_calls: the W_acc - 1 non-leading workers accumulate (12 B/elem).
     whole_step: the W_acc - 1 non-leading workers accumulate (12 B/elem) and all
     W_list - 1 non-leaders hand over their value at the K pairs and clear it:
     index read (4 B) once per worker tile is counted once, + 4 B gathered out per worker."""
-    if route == "three_calls":
-        return (12 * W_acc + 4) * ps.P
     if W_acc == 1:                                    # k_leader_pass: r, g, w in, r out
         return 16 * ps.P
+    if route == "three_calls":
+        return 12 * (W_acc - 1) * ps.P
     return 12 * (W_acc - 1) * ps.P + (4 + 4 * (W_list - 1)) * ps.K
 
 
@@ -101,7 +101,7 @@ def main():
     ap.add_argument("--random-selection", action="store_true",
                     help="threshold route: also send sub-threshold elements with probability importance / threshold")
     ap.add_argument("--no-hint", action="store_true",
-                    help="whole_step only: do not pass the previous step's thresholds as a hint (results are "
+                    help="top-k routes: do not pass the previous step's thresholds as a hint (results are "
                          "identical either way; the hint saves the second pass over the leaders' layers)")
     ap.add_argument("--no-parts", action="store_true", help="skip the stand-alone compress / exchange timings")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
@@ -148,7 +148,7 @@ def main():
     assert not (thr_mode and flat_cfg), "the threshold route is measured on the multi-worker workloads"
     n_lead = args.n_lead
     dominant = DOMINANT_KERNEL[args.route]
-    if flat_cfg and args.route == "whole_step":
+    if flat_cfg and args.route in ("whole_step", "three_calls"):
         dominant = "k_leader_pass"                    # one accumulating worker: nothing follows, the leader's look dominates
     ws_bytes = plan.step_workspace_bytes(W_list) if fused else plan.workspace_bytes
     ws = torch.empty(max(1, ws_bytes), dtype=torch.uint8, device=dev)
@@ -157,7 +157,7 @@ def main():
     sm = torch.empty(ps.K, dtype=torch.float32, device=dev)
     thr2 = [torch.zeros(3 * len(ps.layers), dtype=torch.int32, device=dev) for _ in range(2)]   # ping-pong: the
     thr = thr2[0]                                     # records of step t-1 are the hint of step t
-    use_hint = fused and not args.no_hint
+    use_hint = not thr_mode and not args.no_hint
     CAL = 8                                           # threshold route: top-k steps that settle the thresholds
     total = args.warmup + args.steps + (CAL if thr_mode else 0)
     spare = 1                                         # the layerwise route spends one more step on calibration
@@ -179,7 +179,8 @@ def main():
             iwp.step_segmented(plan, w, g, r, leaders[t], eps, scale, idx, val, sm, thr2[t % 2], ws, stream,
                                thr_hint=hint)
         else:
-            iwp.compress_segmented(plan, w, g, r, leaders[t], eps, idx, val, thr2[t % 2], ws, stream)
+            hint = thr2[(t + 1) % 2] if (use_hint and t > 0) else None
+            iwp.compress_segmented(plan, w, g, r, leaders[t], eps, idx, val, thr2[t % 2], ws, stream, thr_hint=hint)
             iwp.gather_sum_at_indices(r, idx, ps.K, sm, stream)
             iwp.apply_sparse_update(w, idx, sm, ps.K, scale, r, stream)
 

@@ -199,6 +199,7 @@ struct iwp_plan {
     Sizes z{};
     uint64_t flat_end = 0;        // one past the last element any layer covers
     bool any_k = false;
+    bool all_k = true;            // every non-empty layer selects something
     float momentum = 1.0f;        // r <- momentum * r + g in every call that accumulates through this plan
 };
 
@@ -266,8 +267,11 @@ static int single_common(SingleOp op, const float* w, const float* g, float* r, 
     if (rc) return rc;
     Table T{ws.single_table, 1, z.tiles, z.stiles, k, k > 0};
     if (op == OP_COMPACT) return run_compact_from(T, ws, R, w, eps, from_thr, idx_out, val_out, s);
-    IWP_LAUNCH("k_accumulate_all", k_accumulate_all, z.tiles, s, P, w, T.layers, 1u, z.tiles, nullptr, 1u, eps, ws.hist,
-               ws.state, ws.stage, ws.A);
+    if (k > 0)
+        IWP_LAUNCH("k_leader_pass", k_leader_pass, z.stiles * (GROUP / LGROUP), s, P, w, T.layers, 1u, nullptr, 1u, eps, ws.hist,
+                   ws.state, ws.stage, ws.A);
+    else if (g)
+        IWP_LAUNCH("k_accumulate_rest", k_accumulate_rest, z.tiles, s, P, T.layers, 1u, z.tiles, nullptr, 1u);
     return run_select(T, ws, R, w, nullptr, 1u, eps, op == OP_SELECT ? STOP_AT_THRESHOLD : FULL, false, idx_out,
                       val_out, thr_out, s);
 }
@@ -340,7 +344,7 @@ int iwp_plan_create(const iwp_layer* layers, uint32_t n_layers, iwp_plan** plan_
     if (!layers || n_layers == 0) return IWP_EINVAL;
     std::vector<DevLayer> dev(n_layers + 1);
     uint64_t pairs = 0, slots = 0, tiles = 0, stiles = 0, end = 0, mask_words = 0;
-    bool any_k = false;
+    bool any_k = false, all_k = true;
     for (uint32_t j = 0; j < n_layers; ++j) {
         const iwp_layer& L = layers[j];
         if (L.offset < 0 || L.k > L.n) return IWP_EINVAL;
@@ -365,6 +369,7 @@ int iwp_plan_create(const iwp_layer* layers, uint32_t n_layers, iwp_plan** plan_
         stiles += stiles_of(L.n);
         mask_words += ((uint64_t)L.n + 31) / 32;
         any_k = any_k || L.k > 0;
+        if (L.n > 0 && L.k == 0) all_k = false;
         if (pairs > 0xFFFFFFFFull || tiles > 0x7FFFFFFFull / IWP_MAX_WORKERS) return IWP_ERANGE;
     }
     DevLayer& S = dev[n_layers];
@@ -378,6 +383,7 @@ int iwp_plan_create(const iwp_layer* layers, uint32_t n_layers, iwp_plan** plan_
     plan->rows.assign(layers, layers + n_layers);
     plan->z = Sizes{n_layers, (uint32_t)tiles, (uint32_t)stiles, pairs, slots, mask_words, 0};
     plan->any_k = any_k;
+    plan->all_k = all_k;
     plan->flat_end = end;
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&plan->dev), dev.size() * sizeof(DevLayer));
     if (e == hipSuccess) e = hipMemcpy(plan->dev, dev.data(), dev.size() * sizeof(DevLayer), hipMemcpyHostToDevice);
@@ -458,8 +464,11 @@ int compress_segmented(const iwp_plan* plan, const float* w, const float* const*
     rc = launch_init(ws, plan->z.n_layers, thr_hint, nullptr, nullptr, s);
     if (rc) return rc;
     Table T{plan->dev, plan->z.n_layers, plan->z.tiles, plan->z.stiles, plan->z.pairs, plan->any_k};
-    IWP_LAUNCH("k_accumulate_all", k_accumulate_all, W * T.tiles, s, P, w, T.layers, T.n_layers, T.tiles, leader, W, eps,
-               ws.hist, ws.state, ws.stage, ws.A);
+    if (T.any_k)
+        IWP_LAUNCH("k_leader_pass", k_leader_pass, T.stiles * (GROUP / LGROUP), s, P, w, T.layers, T.n_layers, leader, W, eps,
+                   ws.hist, ws.state, ws.stage, ws.A);
+    if (W > 1 || !plan->all_k)
+        IWP_LAUNCH("k_accumulate_rest", k_accumulate_rest, W * T.tiles, s, P, T.layers, T.n_layers, T.tiles, leader, W);
     return run_select(T, ws, R, w, leader, W, eps, FULL, false, idx_out, val_out, thr_out, s);
 }
 

@@ -166,35 +166,21 @@ __device__ __forceinline__ LeadCtx lead_ctx(uint32_t* lh, uint32_t* slot, const 
     return C;
 }
 
-// Every worker, every layer, one launch: W * tiles workgroups, worker-major.
-// A worker without a gradient pointer is not accumulated.  The leader of a layer
-// (k > 0) works in groups of LGROUP tiles: the first workgroup of a group does the
-// group, the others leave at once.
-__global__ __launch_bounds__(BLOCK) void k_accumulate_all(WorkerPtrs P, const float* __restrict__ w,
-                                                          const DevLayer* __restrict__ layers, uint32_t n_layers,
-                                                          uint32_t tiles, const uint32_t* __restrict__ leader,
-                                                          uint32_t W, float eps, uint32_t* __restrict__ hist,
-                                                          const LayerState* __restrict__ state,
-                                                          uint32_t* __restrict__ stage_cnt, StageArrays A) {
-    __shared__ uint32_t lh[HIST0];
-    __shared__ uint32_t slot[8];
+// Every worker that is not the leader of the tile's layer (and every worker of a layer
+// without selection): plain accumulation, W * tiles workgroups, worker-major.  A worker
+// without a gradient pointer is not accumulated.  The leaders go through k_leader_pass.
+__global__ __launch_bounds__(BLOCK) void k_accumulate_rest(WorkerPtrs P, const DevLayer* __restrict__ layers,
+                                                           uint32_t n_layers, uint32_t tiles,
+                                                           const uint32_t* __restrict__ leader, uint32_t W) {
     const uint32_t p = blockIdx.x / tiles;
     const uint32_t t = blockIdx.x - p * tiles;
     const uint32_t j = find_layer<false>(layers, n_layers, t);
     const DevLayer L = layers[j];
-    const uint32_t lt = t - L.tile_begin;
     const float* gp = P.g[p];
-    float* rp = P.r[p];
-    if (L.k > 0 && leader_of(leader, j, W) == p) {
-        if (lt % LGROUP) return;
-        LeadCtx C = lead_ctx(lh, slot, L, state, j, stage_cnt, A);
-        leader_group(gp, rp, w, L, lt, eps, P.momentum, C, hist + (size_t)j * HIST_STRIDE);
-        return;
-    }
-    if (!gp) return;
-    float* rl = rp + L.offset;
+    if (!gp || (L.k > 0 && leader_of(leader, j, W) == p)) return;
+    float* rl = P.r[p] + L.offset;
     const float* gl = gp + L.offset;
-    stream_tile(gl, rl, L.n, lt * TILE, is_aligned16(rl) && is_aligned16(gl), P.momentum);
+    stream_tile(gl, rl, L.n, (t - L.tile_begin) * TILE, is_aligned16(rl) && is_aligned16(gl), P.momentum);
 }
 
 // Leaders only: one workgroup per group of LGROUP tiles of every layer with k > 0.
