@@ -165,3 +165,98 @@ def test_config2_full_size_threshold_routes(gpu_lib):
             ts.step(ids, chosen, thr, scale, random=rnd)
         total = compare(mode, ref)
         print("%s: %d pairs sent" % (mode, total), flush=True)
+
+
+@pytest.mark.timeout(2400)
+def test_largest_supported_layer(gpu_lib):
+    """One layer of the largest size the 32-bit positions allow (2^32 - 65536 - 3 elements, a
+    ragged last tile), one worker: a top-k whole step and a threshold-mode step.  The oracle
+    cannot sort this many pairs inside a test, so -- as for the 10^9-element set above -- the
+    outputs are checked against what it can compute at this size: its scores for every
+    element, its rank-by-counting for sampled elements, its encoded mask, its reduce / update
+    on the compacted pairs, and set-level facts that follow from its scores by comparisons."""
+    import torch
+    iwp = gpu_lib
+    dev = "cuda:0"
+    n = 0xFFFF0000 - 3
+    k = 1_000_003
+    eps, scale = 1e-8, float(np.float32(-0.01))
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(20260)
+    w = torch.empty(n, device=dev).normal_(0.0, 0.02, generator=gen)
+    g = torch.empty(n, device=dev).normal_(0.0, 1e-4, generator=gen)
+    g[-5000:] *= 50.0                                        # kept elements in the very last tiles and at the last position
+    g[:3] = 1.0                                              # and at the first / last positions for certain
+    g[-1] = -1.0
+    r = torch.zeros(n, device=dev)
+    print("inputs drawn", flush=True)
+    w_host = w.cpu().numpy()
+    A_host = np.zeros(n, np.float32)
+    oracle.accumulate(A_host, g.cpu().numpy())               # O1 on the host mirror
+    keys = oracle.score_keys(w_host, A_host, eps)            # O2 for every element
+    print("oracle scores done", flush=True)
+    plan = iwp.Plan([(0, n, k, 0)])
+    ws = torch.empty(plan.step_workspace_bytes(1), dtype=torch.uint8, device=dev)
+    idx = torch.empty(k, dtype=torch.int32, device=dev)
+    val = torch.empty(k, device=dev)
+    sm = torch.empty(k, device=dev)
+    thr = torch.zeros(3, dtype=torch.int32, device=dev)
+    leader = torch.zeros(1, dtype=torch.int32, device=dev)
+    w_before = w.clone()
+    iwp.step_segmented(plan, w, [g], [r], leader, eps, scale, idx, val, sm, thr, ws)
+    torch.cuda.synchronize()
+    print("top-k step done", flush=True)
+    rng = np.random.default_rng(3)
+    i_np, v_np = _check_step("largest layer", torch, keys, A_host, idx, val, thr, k, rng)
+    assert int(i_np[-1]) == n - 1 and i_np[:3].tolist() == [0, 1, 2], "the planted extremes at both ends are kept"
+    print("selection checked", flush=True)
+    il = torch.from_numpy(i_np.astype(np.int64)).to(dev)
+    ar = np.arange(k, dtype=np.uint32)
+    s_ref = oracle.gather_sum([v_np], ar)                    # one worker: the sum is the value, through O5
+    assert np.array_equal(bits(sm.cpu().numpy()), bits(s_ref))
+    w_sel = w_before.index_select(0, il).cpu().numpy()
+    oracle.apply_sparse_update(w_sel, ar, s_ref, scale, [])
+    assert np.array_equal(bits(w.index_select(0, il).cpu().numpy()), bits(w_sel))
+    w_before.index_copy_(0, il, w.index_select(0, il))
+    assert torch.equal(w_before, w), "weights outside the index set changed"
+    del w_before
+    A_host[i_np] = 0.0
+    assert torch.equal(r, torch.from_numpy(A_host).to(dev)), "residual after the top-k step"
+    w_host[i_np] = w_sel
+    print("top-k step checked", flush=True)
+
+    # threshold mode on the state the first step left (no new gradient): a threshold somewhat below the
+    # k-th largest importance of before, so the mask holds the next few hundred thousand elements
+    key_t = int(thr.cpu().numpy().view(np.uint32)[0])
+    t_f = np.float32(np.array([key_t], np.uint32).view(np.float32)[0] * np.float32(0.9))
+    del keys
+    mask_ref = oracle.mask_threshold(w_host, A_host, eps, float(t_f))      # T1 + T2 over the whole layer
+    want = np.nonzero(np.unpackbits(mask_ref, bitorder="little")[:n])[0].astype(np.uint32)
+    total = want.size
+    assert 1000 < total < 4_000_000, total
+    print("oracle mask done: %d marked" % total, flush=True)
+    cap = 4_000_000
+    ws2 = torch.empty(plan.threshold_workspace_bytes(1, 1, cap), dtype=torch.uint8, device=dev)
+    mask = torch.zeros(plan.mask_bytes, dtype=torch.uint8, device=dev)
+    count = torch.zeros(3, dtype=torch.int32, device=dev)
+    idx2 = torch.full((cap,), -1, dtype=torch.int32, device=dev)
+    sum2 = torch.full((cap,), float("nan"), device=dev)
+    thr_d = torch.tensor([float(t_f)], device=dev)
+    w_before = w.clone()
+    iwp.step_threshold_segmented(plan, w, [None], [r], leader, 1, thr_d, eps, scale, mask, count, idx2, sum2, cap, ws2)
+    torch.cuda.synchronize()
+    print("threshold step done", flush=True)
+    assert count.cpu().tolist() == [total, total, 0]
+    assert np.array_equal(mask.cpu().numpy(), mask_ref), "encoded mask"
+    got_idx = idx2.cpu().numpy().view(np.uint32)
+    assert np.array_equal(got_idx[:total], want) and np.all(got_idx[total:] == 0xFFFFFFFF)
+    s2 = oracle.gather_sum([A_host[want]], np.arange(total, dtype=np.uint32))
+    assert np.array_equal(bits(sum2.cpu().numpy()[:total]), bits(s2))
+    il = torch.from_numpy(want.astype(np.int64)).to(dev)
+    w_sel = w_before.index_select(0, il).cpu().numpy()
+    oracle.apply_sparse_update(w_sel, np.arange(total, dtype=np.uint32), s2, scale, [])
+    assert np.array_equal(bits(w.index_select(0, il).cpu().numpy()), bits(w_sel))
+    w_before.index_copy_(0, il, w.index_select(0, il))
+    assert torch.equal(w_before, w), "weights outside the mask changed"
+    A_host[want] = 0.0
+    assert torch.equal(r, torch.from_numpy(A_host).to(dev)), "residual after the threshold step"

@@ -407,6 +407,17 @@ def test_momentum_weighted_residual(gpu_lib, fused):
     _run_steps(gpu_lib, ps, 4, pool=4, tag="cfg1 m=0.9", fused=fused, momentum=0.9)
 
 
+@ROUTES
+def test_most_workers(gpu_lib, fused):
+    """32 workers, the limit of the interface, some of them without a gradient."""
+    sizes = [(300, 5), (TILE + 1, 70), (40000, 625), (STILE + 3, 600)]
+    ps = wl.custom_set(sizes, W=32, seed=95, align=64, zero_frac=0.01)
+    rng = np.random.default_rng(7)
+    r0 = [(rng.standard_t(3, ps.flat) * 1e-3).astype(np.float32) for _ in range(32)]
+    _run_steps(gpu_lib, ps, 2, pool=3, W=32, r0=r0, tag="W=32", fused=fused,
+               g_ids_fn=lambda t: [None if p in (4, 31) else (p + t) % 3 for p in range(32)])
+
+
 def test_determinism_run_to_run(gpu_lib):
     ps = wl.make_config(1)
     outs = []

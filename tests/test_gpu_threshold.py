@@ -190,6 +190,12 @@ def test_threshold_step_with_momentum(gpu_lib, random_seed):
     _run_case(gpu_lib, ps, 4, 2, steps=3, density=0.02, seed=401, static=(3,), random_seed=random_seed, momentum=0.9)
 
 
+def test_threshold_step_most_workers_and_chosen_nodes(gpu_lib):
+    """The limits of the interface: 32 workers, 8 chosen nodes per layer (with repeats)."""
+    ps = wl.custom_set([(9000, 0), (4097, 0), (70_000, 0), (33, 0)], W=32, seed=43, align=64)
+    _run_case(gpu_lib, ps, 32, 8, steps=2, density=0.01, seed=403, static=(5, 31), random_seed=9)
+
+
 def test_threshold_step_capacity(gpu_lib):
     """Capacity exactly the total: exchanged.  One less: flag set, workers accumulated,
     mask and counts valid, nothing exchanged, updated or cleared."""
