@@ -75,6 +75,21 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     rows[0].offset, rows[0].n = 0xFFFF0000 - 5, 10
     assert lib.iwp_plan_create(rows, 1, C.byref(h)) == iwp.IWP_ERANGE
     assert lib.iwp_plan_create(None, 1, C.byref(h)) == iwp.IWP_EINVAL
+    # plan-taking entry points without a plan: nothing to launch on
+    assert lib.iwp_plan_set_momentum(None, 0.9) == iwp.IWP_EINVAL
+    assert lib.iwp_plan_mask_bytes(None) == 0 and lib.iwp_plan_threshold_workspace_bytes(None, 2, 1, 16) == 0
+    assert lib.iwp_plan_workspace_bytes(None) == 0 and lib.iwp_plan_total_pairs(None) == 0
+    tabs = (C.c_void_p * 2)(fake, fake)
+    assert lib.iwp_step_threshold_segmented(None, fake, tabs, tabs, 2, fake, 1, fake, 1e-8, 1.0, fake, fake, fake,
+                                            fake, 16, fake, 1 << 20, None) == iwp.IWP_EINVAL
+    assert lib.iwp_step_threshold_random_segmented(None, fake, tabs, tabs, 2, fake, 1, fake, 1, 2, 1e-8, 1.0, fake,
+                                                   fake, fake, fake, 16, fake, 1 << 20, None) == iwp.IWP_EINVAL
+    assert lib.iwp_step_layerwise_segmented(None, fake, tabs, tabs, 2, fake, 1, 0.1, 0.1, 1.0, 1e-8, 1.0, fake, fake,
+                                            fake, fake, fake, fake, 16, fake, 1 << 20, None) == iwp.IWP_EINVAL
+    assert lib.iwp_step_segmented(None, fake, tabs, tabs, 2, fake, None, 1e-8, 1.0, fake, fake, fake, fake, fake,
+                                  1 << 20, None) == iwp.IWP_EINVAL
+    assert lib.compress_segmented(None, fake, tabs, tabs, 2, fake, None, 1e-8, fake, fake, fake, fake, 1 << 20,
+                                  None) == iwp.IWP_EINVAL
     for code in (0, -1, -2, -3, -4, -5, -99):
         assert lib.iwp_strerror(code)
 
