@@ -385,8 +385,16 @@ int iwp_plan_create(const iwp_layer* layers, uint32_t n_layers, iwp_plan** plan_
     plan->any_k = any_k;
     plan->all_k = all_k;
     plan->flat_end = end;
-    hipError_t e = hipMalloc(reinterpret_cast<void**>(&plan->dev), dev.size() * sizeof(DevLayer));
-    if (e == hipSuccess) e = hipMemcpy(plan->dev, dev.data(), dev.size() * sizeof(DevLayer), hipMemcpyHostToDevice);
+    // the table, then the layer of every tile and of every super-tile (find_layer reads them)
+    std::vector<uint32_t> map;
+    map.reserve(tiles + stiles);
+    for (uint32_t j = 0; j < n_layers; ++j) map.insert(map.end(), tiles_of(layers[j].n), j);
+    for (uint32_t j = 0; j < n_layers; ++j) map.insert(map.end(), stiles_of(layers[j].n), j);
+    const size_t table_bytes = dev.size() * sizeof(DevLayer), map_bytes = map.size() * sizeof(uint32_t);
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&plan->dev), table_bytes + std::max<size_t>(map_bytes, 4));
+    if (e == hipSuccess) e = hipMemcpy(plan->dev, dev.data(), table_bytes, hipMemcpyHostToDevice);
+    if (e == hipSuccess && map_bytes)
+        e = hipMemcpy(reinterpret_cast<char*>(plan->dev) + table_bytes, map.data(), map_bytes, hipMemcpyHostToDevice);
     if (e != hipSuccess) {
         if (plan->dev) (void)hipFree(plan->dev);
         delete plan;

@@ -113,17 +113,15 @@ __device__ __forceinline__ uint32_t leader_of(const uint32_t* __restrict__ leade
     return l < W ? l : 0u;
 }
 
-// Which layer does tile t belong to: the last row whose tile_begin (or stile_begin)
-// is <= t.  Uniform across the workgroup.
+// Which layer does tile t (or super-tile t) belong to.  Uniform across the workgroup.
+// A table of more than one layer comes from a plan, which stores the answer behind the
+// table's sentinel row: one word per tile, then one per super-tile (a binary search over a
+// thousand layers is ten dependent loads before a workgroup can issue its first tile load).
 template <bool SUPER>
 __device__ __forceinline__ uint32_t find_layer(const DevLayer* __restrict__ layers, uint32_t n_layers, uint32_t t) {
-    uint32_t lo = 0, hi = n_layers;          // invariant: begin[lo] <= t < begin[hi]
-    while (hi - lo > 1) {
-        const uint32_t mid = (lo + hi) >> 1;
-        const uint32_t b = SUPER ? layers[mid].stile_begin : layers[mid].tile_begin;
-        if (b <= t) lo = mid; else hi = mid;
-    }
-    return lo;
+    if (n_layers == 1) return 0u;
+    const uint32_t* map = reinterpret_cast<const uint32_t*>(layers + n_layers + 1);
+    return SUPER ? map[layers[n_layers].tile_begin + t] : map[t];
 }
 
 __device__ __forceinline__ bool is_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
