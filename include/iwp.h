@@ -7,6 +7,11 @@
  * with the importance measure of Section 3.2 (|accumulated gradient / weight|).
  * "Choose threshold" is taken as the exact k-th largest importance of the layer,
  * k being given by the caller as an integer, so every output has a static size.
+ * The iwp_step_threshold_* / iwp_step_layerwise_* entry points instead follow the
+ * front end as printed -- a fixed threshold per layer (Section 4.1) or one derived
+ * from the layer's importance statistics (Section 3.4), masks of several chosen
+ * nodes encoded and OR-ed, optional random selection (Section 3.3) -- and report
+ * how many elements were sent in device memory.
  *
  * Conventions for every entry point
  *  - All buffer pointers are DEVICE pointers unless the comment says "host".
@@ -17,7 +22,9 @@
  *  - The caller owns every buffer, the workspace included.  The hot-path calls
  *    allocate nothing, free nothing, read nothing back to the host and keep no
  *    state between calls; they only enqueue kernels on `hip_stream` (a
- *    hipStream_t passed as void*, NULL = the default stream) and return.
+ *    hipStream_t passed as void*, NULL = the default stream) and return, so a
+ *    caller may capture them into a HIP graph (scratch is cleared by fill
+ *    kernels, never by memset nodes).
  *    Outputs are valid once the stream has been synchronised.  A workspace may be
  *    reused by the next call on the same stream; its contents are scratch.
  *  - Buffers must be 4-byte aligned.  16-byte alignment of (pointer + layer
