@@ -1,5 +1,5 @@
 // The streaming kernels: Alg. 1's accumulation line (r <- r + g for every worker
-// and layer) fused with what can ride along on the same pass over HBM --
+// and layer; r <- m * r + g with the momentum of Eq. 3) fused with what can ride along on the same pass over HBM --
 //  * on the leader of a layer: the importance of every element and the histogram
 //    of its most significant key digit (first look of the selection);
 //  * on the other workers, once the leader's index set is known: the gather of
@@ -29,7 +29,7 @@ struct LeadCtx {
     StageArrays A;
 };
 
-// One tile of a plain worker: r <- r + g, streaming (non-temporal) accesses.
+// One tile of a plain worker: r <- m * r + g, streaming (non-temporal) accesses.
 __device__ __forceinline__ void stream_tile(const float* __restrict__ gl, float* __restrict__ rl, uint32_t n,
                                             uint32_t base, bool vec, float m) {
     const uint32_t tid = threadIdx.x;
