@@ -250,11 +250,15 @@ def main():
         step(t)
     torch.cuda.synchronize()
     iwp.timing_enable(dominant, args.steps)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # per-step times, same stream
     t0 = time.perf_counter()
-    for t in range(first + args.warmup, total):
+    for q, t in enumerate(range(first + args.warmup, total)):
+        marks[q].record(stream)
         step(t)
+    marks[args.steps].record(stream)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    step_ms = sorted(marks[q].elapsed_time(marks[q + 1]) for q in range(args.steps))
     k_ms, k_cnt = iwp.timing_collect()
     if thr_mode:
         c = counts[first + args.warmup:total].cpu().numpy()
@@ -312,6 +316,8 @@ def main():
         dom_bytes = dominant_kernel_bytes(ps, W_acc, W_list, args.route)
     dom_ms = k_ms / max(1, k_cnt)
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    # HBM bytes the counters saw for one whole (hinted) step of this route, if such a run is on file
+    step_traffic = traffic_from_profiles(args.workload, "step:" + args.route) if use_hint or thr_mode else None
     out = {
         "metric": "params/sec and achieved HBM GB/s (% of peak) for compress+exchange step",
         "value": params_per_s,
@@ -331,9 +337,13 @@ def main():
                    "eps": eps, "gradient_pool": pool, "route": args.route,
                    "threshold_hint": "previous step" if use_hint else "none"},
         "worker_params_per_s": ps.P * W_acc * args.steps / elapsed,
+        "ms_per_step_median": step_ms[len(step_ms) // 2],
+        "ms_per_step_min": step_ms[0],
         "step_algorithmic_bytes": algo_bytes,
         "step_algorithmic_GBps": algo_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": algo_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "step_traffic_bytes": step_traffic,
+        "step_traffic_GBps": None if step_traffic is None else step_traffic / (ms_per_step * 1e-3) / 1e9,
         "copy_kernel_GBps": copy_gbps,
         "parts": parts,
         "input_generation_s": gen_s,
