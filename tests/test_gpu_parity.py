@@ -229,24 +229,44 @@ def _route(fused):
     return dict(fused=True, hint=fused)
 
 
-def _run_steps(iwp, ps, steps, pool, W=None, r0=None, g_ids_fn=None, leader_fn=None, tag="", fused=False,
-               momentum=None, sets=None):
-    W = ps.W if W is None else W
+# The oracle's side of the large configurations (inputs, and after every step its outputs, weights and
+# residuals) does not depend on the route under test: it is computed once per configuration and kept
+# for the other routes, which saves the oracle's sorts (most of these tests' time) three times over.
+_ORACLE_RUNS = {}
+
+
+def _oracle_run(ps, steps, pool, W, r0, g_ids_fn, leader_fn, momentum, sets):
     w = wl.gen_weights(ps)
     sets = [wl.gen_gradient(ps, s) for s in range(pool)] if sets is None else sets
     r_ref = [np.zeros(ps.flat, np.float32) for _ in range(W)] if r0 is None else [x.copy() for x in r0]
-    gs = GpuSet(iwp, ps, w, sets, r_np=r0, W=W, **_route(fused))
-    if momentum is not None:
-        gs.plan.set_momentum(momentum)
     w_ref = w.copy()
+    per_step = []
     for t in range(steps):
         lead = wl.leaders(ps, t, n_candidates=W) if leader_fn is None else leader_fn(t)
         ids = [wl.gradient_set_of(ps, p, t, pool) for p in range(W)] if g_ids_fn is None else g_ids_fn(t)
         g = [sets[i] if i is not None else sets[0] for i in ids]
         acc = [i is not None for i in ids]
-        idx_ref, val_ref, sum_ref, thr_ref = oracle.step(w_ref, g, r_ref, ps.rows(), lead, float(ps.eps),
-                                                         float(ps.scale), accumulate_mask=acc,
-                                                         momentum=1.0 if momentum is None else momentum)
+        ref = oracle.step(w_ref, g, r_ref, ps.rows(), lead, float(ps.eps), float(ps.scale), accumulate_mask=acc,
+                          momentum=1.0 if momentum is None else momentum)
+        per_step.append((lead, ids, ref, w_ref.copy(), [x.copy() for x in r_ref]))
+    return w, sets, per_step
+
+
+def _run_steps(iwp, ps, steps, pool, W=None, r0=None, g_ids_fn=None, leader_fn=None, tag="", fused=False,
+               momentum=None, sets=None, keep=None):
+    """keep: a name under which the oracle's run is kept for the other routes (only for calls whose
+    inputs are fully determined by the configuration)."""
+    W = ps.W if W is None else W
+    if keep is not None and keep in _ORACLE_RUNS:
+        w, sets, per_step = _ORACLE_RUNS[keep]
+    else:
+        w, sets, per_step = _oracle_run(ps, steps, pool, W, r0, g_ids_fn, leader_fn, momentum, sets)
+        if keep is not None:
+            _ORACLE_RUNS[keep] = (w, sets, per_step)
+    gs = GpuSet(iwp, ps, w, sets, r_np=r0, W=W, **_route(fused))
+    if momentum is not None:
+        gs.plan.set_momentum(momentum)
+    for t, (lead, ids, (idx_ref, val_ref, sum_ref, thr_ref), w_ref, r_ref) in enumerate(per_step):
         gs.step(ids, lead)
         assert_step_equal(gs.download(), w_ref, r_ref, idx_ref, val_ref, sum_ref, thr_ref, ps.layers,
                           tag="%s step %d" % (tag, t))
@@ -299,14 +319,14 @@ def test_leader_table_out_of_range_reads_as_worker_zero(gpu_lib, fused):
 @pytest.mark.timeout(600)
 def test_config3_resnet50_shaped(gpu_lib, fused):
     ps = wl.make_config(3)
-    _run_steps(gpu_lib, ps, 3, pool=4, tag="cfg3", fused=fused)
+    _run_steps(gpu_lib, ps, 3, pool=4, tag="cfg3", fused=fused, keep="cfg3")
 
 
 @ROUTES
 @pytest.mark.timeout(600)
 def test_config4_many_small_tie_heavy(gpu_lib, fused):
     ps = wl.make_config(4)
-    gs = _run_steps(gpu_lib, ps, 2, pool=3, tag="cfg4", fused=fused)
+    gs = _run_steps(gpu_lib, ps, 2, pool=3, tag="cfg4", fused=fused, keep="cfg4")
     # the tie-heavy layers really put their cut inside the run of equal scores
     thr = gs.download()["thr"]
     tie_cut = [j for j, L in enumerate(ps.layers) if L.block is not None and thr[j][0] == 0]
@@ -317,7 +337,7 @@ def test_config4_many_small_tie_heavy(gpu_lib, fused):
 @pytest.mark.timeout(900)
 def test_config2_alexnet_shaped_full_size(gpu_lib, fused):
     ps = wl.make_config(2)
-    _run_steps(gpu_lib, ps, 2, pool=3, tag="cfg2", fused=fused)
+    _run_steps(gpu_lib, ps, 2, pool=3, tag="cfg2", fused=fused, keep="cfg2")
 
 
 @ROUTES
@@ -331,7 +351,7 @@ def test_config5_scaled_local_plus_static_peers(gpu_lib, fused):
     peers = [wl.gen_gradient(ps, 100 + p) for p in range(8)]
     r0 = [np.zeros(ps.flat, np.float32)] + peers
     ps.W = 9
-    _run_steps(gpu_lib, ps, 3, pool=2, W=W, r0=r0, tag="cfg5/50", fused=fused,
+    _run_steps(gpu_lib, ps, 3, pool=2, W=W, r0=r0, tag="cfg5/50", fused=fused, keep="cfg5/50",
                g_ids_fn=lambda t: [t % 2] + [None] * 8, leader_fn=lambda t: np.zeros(1, np.uint32))
 
 
@@ -382,7 +402,7 @@ def test_wrong_hints_change_nothing(gpu_lib, fused):
 @pytest.mark.timeout(600)
 def test_wrong_hints_config3(gpu_lib, fused):
     ps = wl.make_config(3)
-    _run_steps(gpu_lib, ps, 3, pool=4, tag="cfg3 " + fused, fused=fused)
+    _run_steps(gpu_lib, ps, 3, pool=4, tag="cfg3 " + fused, fused=fused, keep="cfg3")
 
 
 @ROUTES
