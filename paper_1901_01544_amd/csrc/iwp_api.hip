@@ -268,7 +268,7 @@ static int single_common(SingleOp op, const float* w, const float* g, float* r, 
     Table T{ws.single_table, 1, z.tiles, z.stiles, k, k > 0};
     if (op == OP_COMPACT) return run_compact_from(T, ws, R, w, eps, from_thr, idx_out, val_out, s);
     if (k > 0)
-        IWP_LAUNCH("k_leader_pass", k_leader_pass, z.stiles * (GROUP / LGROUP), s, P, w, T.layers, 1u, nullptr, 1u, eps, ws.hist,
+        IWP_LAUNCH("k_leader_pass", k_leader_pass<LGROUP>, z.stiles * (GROUP / LGROUP), s, P, w, T.layers, 1u, nullptr, 1u, eps, ws.hist,
                    ws.state, ws.stage, ws.A);
     else if (g)
         IWP_LAUNCH("k_accumulate_rest", k_accumulate_rest, z.tiles, s, P, T.layers, 1u, z.tiles, nullptr, 1u);
@@ -473,7 +473,7 @@ int compress_segmented(const iwp_plan* plan, const float* w, const float* const*
     if (rc) return rc;
     Table T{plan->dev, plan->z.n_layers, plan->z.tiles, plan->z.stiles, plan->z.pairs, plan->any_k};
     if (T.any_k)
-        IWP_LAUNCH("k_leader_pass", k_leader_pass, T.stiles * (GROUP / LGROUP), s, P, w, T.layers, T.n_layers, leader, W, eps,
+        IWP_LAUNCH("k_leader_pass", k_leader_pass<LGROUP>, T.stiles * (GROUP / LGROUP), s, P, w, T.layers, T.n_layers, leader, W, eps,
                    ws.hist, ws.state, ws.stage, ws.A);
     if (W > 1 || !plan->all_k)
         IWP_LAUNCH("k_accumulate_rest", k_accumulate_rest, W * T.tiles, s, P, T.layers, T.n_layers, T.tiles, leader, W);
@@ -507,7 +507,7 @@ int iwp_step_segmented(const iwp_plan* plan, float* w, const float* const* g, fl
     if (rc) return rc;
     Table T{plan->dev, z.n_layers, z.tiles, z.stiles, z.pairs, plan->any_k};
     if (T.any_k) {
-        IWP_LAUNCH("k_leader_pass", k_leader_pass, T.stiles * (GROUP / LGROUP), s, P, w, T.layers, T.n_layers, leader, W, eps,
+        IWP_LAUNCH("k_leader_pass", k_leader_pass<LGROUP>, T.stiles * (GROUP / LGROUP), s, P, w, T.layers, T.n_layers, leader, W, eps,
                    ws.hist, ws.state, ws.stage, ws.A);
         rc = run_select(T, ws, R, w, leader, W, eps, FULL, true, idx_out, val_out, thr_out, s);
         if (rc) return rc;
@@ -550,7 +550,7 @@ int select_threshold_segmented(const iwp_plan* plan, const float* w, const float
     memset(&R, 0, sizeof R);
     R.r[0] = const_cast<float*>(r);
     Table T{plan->dev, plan->z.n_layers, plan->z.tiles, plan->z.stiles, plan->z.pairs, plan->any_k};
-    IWP_LAUNCH("k_leader_pass", k_leader_pass, T.stiles * (GROUP / LGROUP), s, P, w, T.layers, T.n_layers, nullptr, 1u, eps,
+    IWP_LAUNCH("k_leader_pass", k_leader_pass<LGROUP>, T.stiles * (GROUP / LGROUP), s, P, w, T.layers, T.n_layers, nullptr, 1u, eps,
                ws.hist, ws.state, ws.stage, ws.A);
     return run_select(T, ws, R, w, nullptr, 1u, eps, STOP_AT_THRESHOLD, false, nullptr, nullptr, thr_out, s);
 }

@@ -35,8 +35,9 @@ constexpr uint32_t CHUNK = BLOCK * VEC;            // 1024 elements per workgrou
 constexpr uint32_t CHUNKS_PER_TILE = 4;
 constexpr uint32_t TILE = CHUNK * CHUNKS_PER_TILE; // 4096 elements: the streaming unit (measured best on MI355X)
 constexpr uint32_t GROUP = 8;                      // tiles per super-tile
-constexpr uint32_t LGROUP = 4;                     // tiles that share one LDS histogram in look 1 (divides GROUP;
-                                                   // 4 measured better than 8 and 2)
+constexpr uint32_t LGROUP = 2;                     // tiles that share one LDS histogram in look 1 (divides GROUP;
+                                                   // 2 and 4 measure alike on large layers, 2 is ahead by about
+                                                   // 1 % on sets of many small layers; 1 and 8 are behind)
 constexpr uint32_t STILE = TILE * GROUP;           // 32768 elements: unit of the leader-side passes
 constexpr uint32_t TILE_WORDS = TILE / 32;         // words of a one-bit-per-element tile bitmap
 

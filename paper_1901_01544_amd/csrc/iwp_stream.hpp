@@ -132,8 +132,8 @@ __device__ __forceinline__ void lead_tile(const float* __restrict__ gl, float* _
 // The leader's share of one group (up to LGROUP tiles of the same layer):
 // one LDS histogram of the top digit for the whole group, flushed once.
 __device__ __forceinline__ void leader_group(const float* gp, float* rp, const float* __restrict__ w, const DevLayer& L,
-                                             uint32_t first_tile /*in layer*/, float eps, float m, LeadCtx& C,
-                                             uint32_t* __restrict__ ghist) {
+                                             uint32_t first_tile /*in layer*/, uint32_t group_tiles, float eps, float m,
+                                             LeadCtx& C, uint32_t* __restrict__ ghist) {
     for (uint32_t b = threadIdx.x; b < HIST0; b += BLOCK) C.lh[b] = 0u;
     __syncthreads();
     float* rl = rp + L.offset;
@@ -141,7 +141,7 @@ __device__ __forceinline__ void leader_group(const float* gp, float* rp, const f
     const float* wl = w + L.offset;
     const bool vec = is_aligned16(rl) && is_aligned16(wl) && (!gp || is_aligned16(gl));
     const uint32_t ntiles = (L.n + TILE - 1) / TILE;
-    const uint32_t last = min(first_tile + LGROUP, ntiles);
+    const uint32_t last = min(first_tile + group_tiles, ntiles);
     for (uint32_t t = first_tile; t < last; ++t) {
         if (gp) lead_tile<true>(gl, rl, wl, L.n, t, vec, eps, m, C);
         else lead_tile<false>(gl, rl, wl, L.n, t, vec, eps, m, C);
@@ -184,6 +184,7 @@ __global__ __launch_bounds__(BLOCK) void k_accumulate_rest(WorkerPtrs P, const D
 }
 
 // Leaders only: one workgroup per group of LGROUP tiles of every layer with k > 0.
+template <uint32_t LG>
 __global__ __launch_bounds__(BLOCK) void k_leader_pass(WorkerPtrs P, const float* __restrict__ w,
                                                        const DevLayer* __restrict__ layers, uint32_t n_layers,
                                                        const uint32_t* __restrict__ leader, uint32_t W, float eps,
@@ -192,16 +193,16 @@ __global__ __launch_bounds__(BLOCK) void k_leader_pass(WorkerPtrs P, const float
                                                        uint32_t* __restrict__ stage_cnt, StageArrays A) {
     __shared__ uint32_t lh[HIST0];
     __shared__ uint32_t slot[8];
-    constexpr uint32_t SUB = GROUP / LGROUP;                 // workgroups per super-tile
+    constexpr uint32_t SUB = GROUP / LG;                     // workgroups per super-tile
     const uint32_t s = blockIdx.x / SUB;
     const uint32_t j = find_layer<true>(layers, n_layers, s);
     const DevLayer L = layers[j];
     if (L.k == 0) return;
-    const uint32_t first = (s - L.stile_begin) * GROUP + (blockIdx.x % SUB) * LGROUP;
+    const uint32_t first = (s - L.stile_begin) * GROUP + (blockIdx.x % SUB) * LG;
     if (first * TILE >= L.n) return;
     const uint32_t p = leader_of(leader, j, W);
     LeadCtx C = lead_ctx(lh, slot, L, state, j, stage_cnt, A);
-    leader_group(P.g[p], P.r[p], w, L, first, eps, P.momentum, C, hist + (size_t)j * HIST_STRIDE);
+    leader_group(P.g[p], P.r[p], w, L, first, LG, eps, P.momentum, C, hist + (size_t)j * HIST_STRIDE);
 }
 
 // The other workers, after the leader's pairs are known: accumulate, and where the
