@@ -295,7 +295,7 @@ int iwp_score_keys(const float* w, const float* r, uint32_t n, float eps, uint32
 int iwp_copy_f32(float* dst, const float* src, uint64_t n, void* hip_stream);
 
 /* Measurement aid, not on the hot path: time every launch of one kernel (by its
- * name, e.g. "k_accumulate_hist") with HIP event pairs recorded on the stream the
+ * name, e.g. "k_follow_gather") with HIP event pairs recorded on the stream the
  * kernel is launched on.  enable() creates the events (at most max_launches pairs,
  * 0 = the built-in maximum) and starts recording; collect() stops, waits for the
  * recorded events and returns the summed duration in milliseconds and the number
