@@ -4,7 +4,7 @@
 //
 // The selection is an MSB-first radix select on the 31-bit importance key
 // (digits of 12 + 10 + 9 bits).  Look 1 (iwp_stream.hpp) histograms the top digit
-// of every element.  k_pick0 finds the bin b1 that holds rank k.  Look 2 (k_stage)
+// of every element.  k_pick<0> finds the bin b1 that holds rank k.  Look 2 (k_stage)
 // reads the leader's residual and weights once more and copies out, per tile, the
 // only elements that can still matter: those whose top digit is >= b1 (above b1 all
 // of them are kept, the threshold lies among those inside b1), and histograms the
@@ -13,8 +13,8 @@
 // hint (say, last step's thresholds) look 1 already copies out everything from a
 // bin slightly below the hinted one; if the new b1 is not below that bin the copies
 // are complete and look 2 only reads the slots, not the layer.  Everything after
-// that works on the staged copies, a few percent of the layer: k_pick1, k_refine2
-// and k_pick2 finish the threshold, k_count / k_scan / k_write place every kept
+// that works on the staged copies, a few percent of the layer: k_pick<1>, k_refine2
+// and k_pick<2> finish the threshold, k_count / k_scan / k_write place every kept
 // element at its rank in index order.  A tile whose candidates do not fit its slot
 // (heavy ties, e.g. a tile that is all zeros) is marked RAW and is simply re-read
 // from r and w by the later passes.  Both routes are exact.
