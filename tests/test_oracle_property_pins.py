@@ -23,7 +23,7 @@ def layers(draw, max_n=40):
     return w, r
 
 
-@settings(max_examples=300, deadline=None)
+@settings(max_examples=300, deadline=None, derandomize=True)
 @given(layers(), st.data())
 def test_select_is_the_sorted_prefix(layer, data):
     """O3/O4: the k first under (score descending, index ascending), returned ascending."""
@@ -47,7 +47,7 @@ def test_select_is_the_sorted_prefix(layer, data):
         assert oracle.rank_of(s, i) == rank and (rank < k) == bool(i in set(want.tolist()))
 
 
-@settings(max_examples=200, deadline=None)
+@settings(max_examples=200, deadline=None, derandomize=True)
 @given(layers(), st.sampled_from([0.0, 0.005, 0.5, 1.0, 1e-30, 3e38, float("inf")]))
 def test_threshold_mask_is_the_strict_comparison(layer, thr):
     w, r = layer
@@ -62,7 +62,7 @@ def test_threshold_mask_is_the_strict_comparison(layer, thr):
     assert np.array_equal(oracle.mask_indices(mask, n), np.nonzero(want)[0].astype(np.uint32))
 
 
-@settings(max_examples=150, deadline=None)
+@settings(max_examples=150, deadline=None, derandomize=True)
 @given(st.lists(st.floats(min_value=0, max_value=100, width=32), min_size=1, max_size=30))
 def test_layer_statistics_are_exact_rationals_rounded(scores):
     """L1 with |w| + eps = 1 (score = |r|): mean and population variance against exact arithmetic."""
@@ -76,7 +76,7 @@ def test_layer_statistics_are_exact_rationals_rounded(scores):
     assert abs(Fraction(v) - var) <= var * Fraction(1, 10 ** 12) + Fraction(1, 10 ** 40)
 
 
-@settings(max_examples=150, deadline=None)
+@settings(max_examples=150, deadline=None, derandomize=True)
 @given(layers(max_n=24), st.sampled_from([1.0, 0.5, 0.9, 0.0]),
        st.lists(small_f32, min_size=24, max_size=24))
 def test_conservation_through_a_step(layer, m, gs):
