@@ -297,13 +297,6 @@ uint64_t oracle_mask_indices(const uint8_t* mask, uint64_t n, uint32_t* idx_out)
     return c;
 }
 
-// One whole iteration of Algorithm 1 in threshold mode on a flat parameter set.
-// leaders: n_layers x n_lead chosen nodes per layer (row-major); thr: one threshold
-// per layer; mask_out: the layers' encoded masks back to back (oracle_mask_bytes(n)
-// each); count_out[j]: masked positions of layer j; idx_out / sum_out: the masked
-// flat positions of all layers packed in table order and the reduced values, at most
-// max_pairs (returns -4 if there are more).  Every worker with accumulate[p] != 0
-// adds its gradient first; every worker is cleared at the masked positions.
 // S1: Philox-4x32-10.
 void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
     uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
@@ -348,6 +341,13 @@ void oracle_mask_threshold_random(const float* w, const float* r, uint64_t n, fl
 namespace {
 struct RandomSelection { uint64_t seed, step; };
 
+// One whole iteration of Algorithm 1 in threshold mode on a flat parameter set.
+// leaders: n_layers x n_lead chosen nodes per layer (row-major); thr: one threshold
+// per layer; mask_out: the layers' encoded masks back to back (oracle_mask_bytes(n)
+// each); count_out[j]: masked positions of layer j; idx_out / sum_out: the masked
+// flat positions of all layers packed in table order and the reduced values, at most
+// max_pairs (returns -4 if there are more).  Every worker with accumulate[p] != 0
+// adds its gradient first; every worker is cleared at the masked positions.
 int step_threshold_impl(float* w, const float* const* g, float* const* r, const uint8_t* accumulate, float momentum,
                         uint32_t W,
                         const oracle_layer* layers, const uint32_t* leaders, uint32_t n_lead, const float* thr,

@@ -16,7 +16,8 @@ class GpuSet:
     three separate calls (compress_segmented, gather_sum_at_indices,
     apply_sparse_update) or, with fused=True, the whole-step entry point."""
 
-    def __init__(self, iwp, ps, w_np, grads_np, r_np=None, W=None, fused=False, hint="none"):
+    def __init__(self, iwp, ps, w_np, grads_np, r_np=None, W=None, fused=False, hint="none", grads_dev=None):
+        """grads_dev: gradient sets already on the device (shared between several sets), instead of grads_np."""
         import torch
         self.torch = torch
         self.iwp = iwp
@@ -24,7 +25,7 @@ class GpuSet:
         self.W = ps.W if W is None else W
         dev = torch.device("cuda:0")
         self.w = torch.from_numpy(w_np).to(dev)
-        self.grads = [torch.from_numpy(g).to(dev) for g in grads_np]
+        self.grads = [torch.from_numpy(g).to(dev) for g in grads_np] if grads_dev is None else grads_dev
         if r_np is None:
             self.r = [torch.zeros(ps.flat, dtype=torch.float32, device=dev) for _ in range(self.W)]
         else:
@@ -45,8 +46,10 @@ class GpuSet:
         self.thr = torch.zeros(len(ps.layers) * 3, dtype=torch.int32, device=dev)
         self.leader = torch.zeros(len(ps.layers), dtype=torch.int32, device=dev)
 
-    def step(self, g_ids, leader_np, scale=None):
-        """g_ids[p]: index into the gradient pool for worker p, or None (no accumulate)."""
+    def step(self, g_ids, leader_np, scale=None, hint_records=None):
+        """g_ids[p]: index into the gradient pool for worker p, or None (no accumulate).
+        hint_records: (layers, 3) uint32 records to pass as this step's threshold hint, whatever the set's
+        hint mode says (a set with hint mode "none" ignores them)."""
         iwp, ps = self.iwp, self.ps
         self.idx.fill_(-1)
         self.val.fill_(float("nan"))
@@ -54,7 +57,10 @@ class GpuSet:
         g = [None if i is None else self.grads[i] for i in g_ids]
         sc = float(ps.scale if scale is None else scale)
         hint = None
-        if self.hint_mode == "previous" and self.steps_done > 0:
+        if hint_records is not None and self.hint_mode != "none":
+            self.hint.copy_(self.torch.from_numpy(np.ascontiguousarray(hint_records, np.uint32).view(np.int32).ravel()))
+            hint = self.hint
+        elif self.hint_mode == "previous" and self.steps_done > 0:
             self.hint.copy_(self.thr)
             hint = self.hint
         elif self.hint_mode == "garbage":
@@ -90,6 +96,34 @@ class GpuSet:
             w=self.w.cpu().numpy(),
             r=[x.cpu().numpy() for x in self.r],
         )
+
+
+class DeviceRef:
+    """The oracle's state after a step, uploaded once, for bit-exact comparison on the device against
+    several GpuSets (downloading 2 GB of residuals per set and step is what would dominate a long run)."""
+
+    def __init__(self, torch, w_ref, r_ref, idx_ref, val_ref, sum_ref, thr_ref):
+        up = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a).view(dt)).to("cuda:0")
+        self.torch = torch
+        self.host = (w_ref, r_ref, idx_ref, val_ref, sum_ref, thr_ref)
+        self.w = up(w_ref, np.int32)
+        self.r = [up(x, np.int32) for x in r_ref]
+        self.idx = up(idx_ref.astype(np.uint32), np.int32)
+        self.val = up(val_ref, np.int32)
+        self.sum = up(sum_ref, np.int32)
+
+    def check(self, gs, layers, tag=""):
+        t = self.torch
+        K = self.idx.numel()
+        i32 = lambda x: x.view(t.int32)
+        same = (t.equal(gs.idx[:K], self.idx) and t.equal(i32(gs.val)[:K], self.val)
+                and t.equal(i32(gs.sum)[:K], self.sum) and t.equal(i32(gs.w), self.w)
+                and all(t.equal(i32(a), b) for a, b in zip(gs.r, self.r)))
+        thr = gs.thr.cpu().numpy().view(np.uint32).reshape(-1, 3)
+        same = same and all(np.array_equal(thr[j], self.host[5][j]) for j, L in enumerate(layers) if L.k)
+        if not same:                                   # the host comparison names what differs
+            assert_step_equal(gs.download(), *self.host, layers, tag=tag)
+            raise AssertionError(tag + ": device comparison failed but the host comparison passed")
 
 
 def assert_step_equal(got, w_ref, r_ref, idx_ref, val_ref, sum_ref, thr_ref, layers, tag=""):

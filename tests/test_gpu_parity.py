@@ -322,22 +322,7 @@ def test_config3_resnet50_shaped(gpu_lib, fused):
     _run_steps(gpu_lib, ps, 3, pool=4, tag="cfg3", fused=fused, keep="cfg3")
 
 
-@ROUTES
-@pytest.mark.timeout(600)
-def test_config4_many_small_tie_heavy(gpu_lib, fused):
-    ps = wl.make_config(4)
-    gs = _run_steps(gpu_lib, ps, 2, pool=3, tag="cfg4", fused=fused, keep="cfg4")
-    # the tie-heavy layers really put their cut inside the run of equal scores
-    thr = gs.download()["thr"]
-    tie_cut = [j for j, L in enumerate(ps.layers) if L.block is not None and thr[j][0] == 0]
-    assert len(tie_cut) >= 10
-
-
-@ROUTES
-@pytest.mark.timeout(900)
-def test_config2_alexnet_shaped_full_size(gpu_lib, fused):
-    ps = wl.make_config(2)
-    _run_steps(gpu_lib, ps, 2, pool=3, tag="cfg2", fused=fused, keep="cfg2")
+# Configs 2 and 4 at full size, every route, over 12 and all 10 steps: tests/test_gpu_longrun.py.
 
 
 @ROUTES

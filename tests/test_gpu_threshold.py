@@ -183,6 +183,40 @@ def test_random_selection_sends_more_than_plain_threshold(gpu_lib):
     assert np.all(masks[1][masks[0]]) and masks[1].sum() > masks[0].sum() > 0
 
 
+def test_random_selection_boundary_draw_equals_probability(gpu_lib):
+    """Section 3.3, P(update) = importance / threshold, strictly u < p: residuals whose importance over the
+    threshold equals the draw bit for bit are not sent, one unit above is; an element of importance 0 is not
+    sent where the draw is exactly 0 (seed 0, step 0: the draws of tests/golden/hand_example_random.txt)."""
+    import os
+    d = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "hand_example_random.txt")):
+        if line.strip() and not line.startswith("#"):
+            d[line.split()[0]] = line.split()[1:]
+    layer, e = int(d["zero_draw_layer"][0]), int(d["zero_draw_elem"][0])
+    sizes = [(4100, 0)] + [(40, 0)] * (layer - 1) + [(e + 2, 0)]
+    ps = wl.custom_set(sizes, W=1, seed=1, align=64)
+    w = np.ones(ps.flat, np.float32)                           # |w| + 1e-8 rounds to 1: p = |r| / thr exactly
+    r = np.zeros(ps.flat, np.float32)
+    L0, Lz = ps.layers[0], ps.layers[layer]
+    u = np.array([float(oracle.uniform(0, 0, 0, i)) for i in range(4100)], np.float32)
+    r[L0.offset:L0.offset + 4100] = u                          # p == u everywhere in layer 0 ...
+    r[L0.offset + 2] = np.float32(int(d["caseD_r24"][2], 0) / 2 ** 24)      # ... except one grid step above here
+    r[L0.offset + 4099] = -np.nextafter(u[4099], np.float32(1))             # and here (ragged last tile)
+    r[Lz.offset + e + 1] = 1e-30
+    thr = np.ones(len(ps.layers), np.float32)
+    leaders = np.zeros((len(ps.layers), 1), np.uint32)
+    ts = ThresholdSet(gpu_lib, ps, w, [np.zeros(ps.flat, np.float32)], [r.copy()], 1, 64)
+    w_ref, r_ref = w.copy(), [r.copy()]
+    ref = oracle.step_threshold(w_ref, [np.zeros(1, np.float32)], r_ref, ps.rows(), leaders, thr, EPS, -0.5, 64,
+                                accumulate_mask=[False], random=(0, 0))
+    ts.step([None], leaders, thr, -0.5, random=(0, 0))
+    got = ts.download()
+    assert ref[2].tolist() == [L0.offset + 2, L0.offset + 4099]             # what the paper's rule fixes
+    assert np.array_equal(got["mask"], ref[0]) and np.array_equal(got["idx"][:2], ref[2])
+    assert got["count"].tolist() == [2] + [0] * (len(ps.layers) - 1) + [2, 0]
+    assert np.array_equal(bits(got["w"]), bits(w_ref)) and np.array_equal(bits(got["r"][0]), bits(r_ref[0]))
+
+
 @pytest.mark.parametrize("random_seed", [None, 4242])
 def test_threshold_step_with_momentum(gpu_lib, random_seed):
     """Eq. 3 accumulation (r <- m * r + g) on the chosen nodes and on the followers."""

@@ -56,6 +56,36 @@ def test_hand_worked_example():
     assert r.tolist() == [-0.25, 0.0, 0.0, 0.0]
 
 
+def test_boundary_draw_equal_to_probability_is_not_sent():
+    """P(update) = importance / threshold (Section 3.3): the element is sent iff u < p, strictly.  With
+    |w| = 1, eps = 0, thr = 1 and |r| set to the draws themselves, p == u bit for bit and nothing is sent;
+    one unit of the 24-bit grid above the draw is sent.  An element of importance 0 is never sent, not
+    even where the draw is exactly 0."""
+    d = _hand()
+    r = np.array([int(t, 0) / 2 ** 24 for t in d["caseD_r24"]], np.float32)
+    r[1] = -r[1]
+    for i in range(2):
+        assert np.float32(abs(r[i])) == oracle.uniform(0, 0, 0, i)          # p == u exactly
+    m = oracle.mask_threshold_random(np.ones(4, np.float32), r, 0.0, float(d["caseD_thr"][0]), 0, 0, 0)
+    assert m.tolist() == [int(d["caseD_mask"][0], 0), 0, 0, 0]
+    # the same boundary with thr = 0.5 and |r| = u / 2 (the divide is exact)
+    m = oracle.mask_threshold_random(np.ones(4, np.float32), r * np.float32(0.5), 0.0, 0.5, 0, 0, 0)
+    assert m.tolist() == [int(d["caseD_mask"][0], 0), 0, 0, 0]
+    # a draw of exactly zero against a probability of exactly zero
+    layer, e = int(d["zero_draw_layer"][0]), int(d["zero_draw_elem"][0])
+    ctr = [e // 4, layer, 0, 0]
+    assert int(oracle.philox4x32_10(ctr, [0, 0])[e % 4]) == int(d["zero_draw_word"][0], 0)
+    assert oracle.uniform(0, 0, layer, e) == 0.0
+    n = e + 2
+    rz = np.zeros(n, np.float32)
+    rz[e + 1] = 1e-30                          # the neighbour has a tiny positive probability and a non-zero draw
+    mz = _unpack(oracle.mask_threshold_random(np.ones(n, np.float32), rz, 0.0, 1.0, 0, 0, layer), n)
+    assert not mz.any()
+    rz[e] = 1e-30                              # any positive probability beats a draw of 0
+    mz = _unpack(oracle.mask_threshold_random(np.ones(n, np.float32), rz, 0.0, 1.0, 0, 0, layer), n)
+    assert np.nonzero(mz)[0].tolist() == [e]
+
+
 def test_uniform_mapping_and_counter_layout():
     """u = (word >> 8) * 2^-24 of output word i % 4 of the block with counter
     (i / 4, layer, step low, step high) and key (seed low, seed high)."""
