@@ -47,6 +47,7 @@ extern "C" {
 
 #define IWP_MAX_WORKERS 32
 #define IWP_MAX_FLAT 0xFFFF0000ull
+#define IWP_STATIC_SCRATCH_BYTES (64u << 20)   /* the library's own scratch, see compress_segmented_static */
 
 typedef enum {
     IWP_OK = 0,
@@ -54,7 +55,8 @@ typedef enum {
     IWP_EALIGN = -2,     /* a buffer is not 4-byte aligned */
     IWP_EWORKSPACE = -3, /* workspace missing or smaller than iwp_*workspace_bytes() */
     IWP_ERANGE = -4,     /* offset + n exceeds IWP_MAX_FLAT */
-    IWP_EHIP = -5        /* a HIP runtime call or a launch failed; see iwp_last_hip_error() */
+    IWP_EHIP = -5,       /* a HIP runtime call or a launch failed; see iwp_last_hip_error() */
+    IWP_ESCRATCH = -6    /* compress_segmented_static: the plan needs more than IWP_STATIC_SCRATCH_BYTES */
 } iwp_status;
 
 /* The threshold of one layer (stands for "choose threshold: thr" of Algorithm 1).
@@ -179,6 +181,21 @@ int compress_segmented(const iwp_plan* plan, const float* w, const float* const*
                        uint32_t W, const uint32_t* leader, const iwp_threshold* thr_hint, float eps,
                        uint32_t* idx_out, float* val_out, iwp_threshold* thr_out,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* compress_segmented for callers that cannot allocate or hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results
+ * and errors, minus the workspace: the kernels work in a scratch buffer of
+ * IWP_STATIC_SCRATCH_BYTES (64 MiB) that is part of the library's device image, so every GPU the
+ * library runs on holds one copy until the process ends.  The call allocates and frees nothing
+ * (its first call on a device looks the buffer's address up, nothing more).  A plan whose
+ * iwp_plan_workspace_bytes() exceeds the buffer is refused with IWP_ESCRATCH before anything is
+ * launched (the AlexNet-shaped set needs 46.5 MB, the ResNet-50-shaped one 24.6 MB).  All calls
+ * on one GPU share that one buffer, which keeps the last call's contents; each call clears what
+ * it needs cleared.  Calls that overlap on one GPU (two streams, two threads) race on it: run them
+ * one after the other on one stream, or use compress_segmented with separate workspaces. */
+int compress_segmented_static(const iwp_plan* plan, const float* w, const float* const* g, float* const* r,
+                              uint32_t W, const uint32_t* leader, const iwp_threshold* thr_hint, float eps,
+                              uint32_t* idx_out, float* val_out, iwp_threshold* thr_out, void* hip_stream);
 
 /* One whole iteration of Algorithm 1's outer loop for W workers emulated on one GPU:
  * compress_segmented, gather_sum_at_indices over r[0..W) and apply_sparse_update

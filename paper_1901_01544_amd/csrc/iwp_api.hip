@@ -8,6 +8,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -69,6 +70,31 @@ struct TimedLaunch {       // records an event pair around the launch made while
         hipError_t e_ = hipGetLastError();                            \
         if (e_ != hipSuccess) return hip_fail(e_, name);              \
     } while (0)
+
+// Scratch of compress_segmented_static: device memory that belongs to the library, one copy per
+// GPU, held until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; kernels and fills are given the address that call returns, looked up once
+// per device with that device current.
+static __device__ __align__(256) unsigned char scratch[IWP_STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_lock;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+
+int static_scratch(void** out) {
+    int dev = -1;
+    IWP_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return IWP_EINVAL;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        IWP_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || (reinterpret_cast<uintptr_t>(p) & 255u)) return IWP_EALIGN;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return IWP_OK;
+}
 
 inline bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
 inline size_t round256(size_t x) { return (x + 255) & ~size_t(255); }
@@ -213,6 +239,7 @@ const char* iwp_strerror(int code) {
         case IWP_EWORKSPACE: return "workspace missing or too small";
         case IWP_ERANGE: return "layer does not fit the 32-bit index range";
         case IWP_EHIP: return "HIP runtime error";
+        case IWP_ESCRATCH: return "plan needs more scratch than the library's static buffer holds";
         default: return "unknown status";
     }
 }
@@ -449,10 +476,11 @@ static int worker_tables(const float* const* g, float* const* r, uint32_t W, flo
     return IWP_OK;
 }
 
-int compress_segmented(const iwp_plan* plan, const float* w, const float* const* g, float* const* r, uint32_t W,
-                       const uint32_t* leader, const iwp_threshold* thr_hint, float eps, uint32_t* idx_out,
-                       float* val_out, iwp_threshold* thr_out, void* workspace, size_t workspace_bytes,
-                       void* hip_stream) {
+// compress_segmented on a workspace that is either the caller's or the library's static scratch.
+static int compress_segmented_on(const iwp_plan* plan, const float* w, const float* const* g, float* const* r,
+                                 uint32_t W, const uint32_t* leader, const iwp_threshold* thr_hint, float eps,
+                                 uint32_t* idx_out, float* val_out, iwp_threshold* thr_out, bool own_scratch,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!plan) return IWP_EINVAL;
     if (check_eps(eps)) return IWP_EINVAL;
     if (plan->any_k && (!w || !idx_out || !val_out)) return IWP_EINVAL;
@@ -464,6 +492,13 @@ int compress_segmented(const iwp_plan* plan, const float* w, const float* const*
     ResidualPtrs R;
     int rc = worker_tables(g, r, W, plan->momentum, &P, &R);
     if (rc) return rc;
+    if (own_scratch) {
+        // the size check comes first: a plan that does not fit is turned away before anything is looked up
+        if (carve(nullptr, plan->z).bytes > IWP_STATIC_SCRATCH_BYTES) return IWP_ESCRATCH;
+        rc = static_scratch(&workspace);
+        if (rc) return rc;
+        workspace_bytes = IWP_STATIC_SCRATCH_BYTES;
+    }
     Workspace ws = carve(workspace, plan->z);
     rc = check_ws(ws.bytes, workspace, workspace_bytes);
     if (rc) return rc;
@@ -478,6 +513,21 @@ int compress_segmented(const iwp_plan* plan, const float* w, const float* const*
     if (W > 1 || !plan->all_k)
         IWP_LAUNCH("k_accumulate_rest", k_accumulate_rest, W * T.tiles, s, P, T.layers, T.n_layers, T.tiles, leader, W);
     return run_select(T, ws, R, w, leader, W, eps, FULL, false, idx_out, val_out, thr_out, s);
+}
+
+int compress_segmented(const iwp_plan* plan, const float* w, const float* const* g, float* const* r, uint32_t W,
+                       const uint32_t* leader, const iwp_threshold* thr_hint, float eps, uint32_t* idx_out,
+                       float* val_out, iwp_threshold* thr_out, void* workspace, size_t workspace_bytes,
+                       void* hip_stream) {
+    return compress_segmented_on(plan, w, g, r, W, leader, thr_hint, eps, idx_out, val_out, thr_out, false, workspace,
+                                 workspace_bytes, hip_stream);
+}
+
+int compress_segmented_static(const iwp_plan* plan, const float* w, const float* const* g, float* const* r,
+                              uint32_t W, const uint32_t* leader, const iwp_threshold* thr_hint, float eps,
+                              uint32_t* idx_out, float* val_out, iwp_threshold* thr_out, void* hip_stream) {
+    return compress_segmented_on(plan, w, g, r, W, leader, thr_hint, eps, idx_out, val_out, thr_out, true, nullptr, 0,
+                                 hip_stream);
 }
 
 int iwp_step_segmented(const iwp_plan* plan, float* w, const float* const* g, float* const* r, uint32_t W,

@@ -15,7 +15,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libiwp.so")
 
 IWP_MAX_WORKERS = 32
-IWP_OK, IWP_EINVAL, IWP_EALIGN, IWP_EWORKSPACE, IWP_ERANGE, IWP_EHIP = 0, -1, -2, -3, -4, -5
+IWP_OK, IWP_EINVAL, IWP_EALIGN, IWP_EWORKSPACE, IWP_ERANGE, IWP_EHIP, IWP_ESCRATCH = 0, -1, -2, -3, -4, -5, -6
+IWP_STATIC_SCRATCH_BYTES = 64 << 20
 
 
 class IwpError(RuntimeError):
@@ -86,6 +87,9 @@ def load() -> C.CDLL:
     L.iwp_plan_total_pairs.restype = C.c_uint64
     L.compress_segmented.argtypes = [_vp, _vp, C.POINTER(_vp), C.POINTER(_vp), C.c_uint32, _vp, _vp, C.c_float,
                                      _vp, _vp, _vp, _vp, C.c_size_t, _vp]
+    L.compress_segmented_static.argtypes = [_vp, _vp, C.POINTER(_vp), C.POINTER(_vp), C.c_uint32, _vp, _vp, C.c_float,
+                                            _vp, _vp, _vp, _vp]
+    L.compress_segmented_static.restype = C.c_int
     L.select_threshold_segmented.argtypes = [_vp, _vp, _vp, C.c_float, _vp, _vp, C.c_size_t, _vp]
     L.compact_pairs_segmented.argtypes = [_vp, _vp, _vp, C.c_float, _vp, _vp, _vp, _vp, C.c_size_t, _vp]
     L.iwp_score_keys.argtypes = [_vp, _vp, C.c_uint32, C.c_float, _vp, _vp]
@@ -226,6 +230,14 @@ def compress_segmented(plan: Plan, w, g: Sequence, r: Sequence, leader, eps: flo
                                      _ptr(thr_hint), eps,
                                      _ptr(idx_out), _ptr(val_out), _ptr(thr_out), _ptr(workspace), ws_bytes,
                                      _stream(stream)), "compress_segmented")
+
+
+def compress_segmented_static(plan: Plan, w, g: Sequence, r: Sequence, leader, eps: float, idx_out, val_out, thr_out,
+                              stream=None, thr_hint=None):
+    assert len(g) == len(r)
+    _check(load().compress_segmented_static(plan._h, _ptr(w), _ptr_table(g), _ptr_table(r), len(r), _ptr(leader),
+                                            _ptr(thr_hint), eps, _ptr(idx_out), _ptr(val_out), _ptr(thr_out),
+                                            _stream(stream)), "compress_segmented_static")
 
 
 def step_segmented(plan: Plan, w, g: Sequence, r: Sequence, leader, eps: float, scale: float, idx_out, val_out,
