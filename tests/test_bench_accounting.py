@@ -40,8 +40,25 @@ def test_traffic_file_names_kernels_the_bench_times():
         for name, b in entries.items():
             assert name.startswith("step:") or name in set(bench.DOMINANT_KERNEL.values()) | {"k_leader_pass"}
             assert isinstance(b, int) and b > 0
-    assert bench.traffic_from_profiles("alexnet", "k_follow_gather") == d["alexnet"]["k_follow_gather"]
-    assert bench.traffic_from_profiles("alexnet", "no_such_kernel") is None
+    assert bench.traffic_from_profiles("alexnet", "k_follow_gather", check_hash=False) == d["alexnet"]["k_follow_gather"]
+    assert bench.traffic_from_profiles("alexnet", "no_such_kernel", check_hash=False) is None
+
+
+def test_traffic_is_reported_only_for_the_kernel_sources_it_was_measured_on(tmp_path, monkeypatch):
+    """The counter figures are constants on file; the bench line carries them only while the file's stamp
+    equals the hash of the kernel sources in the tree."""
+    h = bench.kernel_source_hash()
+    assert len(h) == 64 and h == bench.kernel_source_hash()
+    d = json.load(open(os.path.join(ROOT, "profiles", "traffic.json")))
+    want = d["alexnet"]["k_follow_gather"] if d.get("_csrc_sha256") == h else None
+    assert bench.traffic_from_profiles("alexnet", "k_follow_gather") == want
+    (tmp_path / "profiles").mkdir()
+    for stamp, expect in ((h, 123), ("0" * 64, None)):
+        json.dump({"_csrc_sha256": stamp, "alexnet": {"k_follow_gather": 123}},
+                  open(tmp_path / "profiles" / "traffic.json", "w"))
+        monkeypatch.setattr(bench, "ROOT", str(tmp_path))
+        monkeypatch.setattr(bench, "kernel_source_hash", lambda: h)
+        assert bench.traffic_from_profiles("alexnet", "k_follow_gather") == expect
 
 
 def test_more_than_one_gpu_is_refused():
