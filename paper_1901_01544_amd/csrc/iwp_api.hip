@@ -159,7 +159,12 @@ struct Table {                // what the launches need to know about a layer ta
     uint32_t n_layers, tiles, stiles;
     uint64_t pairs;
     bool any_k;
+    uint32_t max_layer_stiles;   // super-tiles of the longest layer
 };
+
+// Up to this many super-tiles per layer (128 Mi elements) k_write adds up the earlier super-tiles'
+// counts itself (16 loads per thread at most); beyond, a scan launch is cheaper.
+constexpr uint32_t FOLD_SCAN_MAX_STILES = 4096;
 
 int check_eps(float eps) { return (eps >= 0.0f && std::isfinite(eps)) ? IWP_OK : IWP_EINVAL; }
 
@@ -179,28 +184,44 @@ enum Stop { STOP_AT_THRESHOLD, FULL };
 // Selection on the leaders' residuals after look 1 has filled the first-digit
 // histograms, then (FULL) the ordered split.  fused: whole-step route (leader row
 // of the gather matrix, leader residual cleared).
+template <bool FUSED>
+int launch_write(const Table& T, const Workspace& ws, const ResidualPtrs& R, const float* w, const uint32_t* leader,
+                 uint32_t W, float eps, bool all_raw, uint32_t* idx_out, float* val_out, hipStream_t s) {
+    const uint32_t grid = T.stiles * (GROUP / (BLOCK / WAVE));
+    float* gathered = FUSED ? ws.gathered : nullptr;
+    if (T.max_layer_stiles <= FOLD_SCAN_MAX_STILES) {
+        IWP_LAUNCH("k_write", (k_write<FUSED, true>), grid, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state,
+                   ws.stage, ws.A, all_raw, ws.tile_counts, ws.stile_counts, ws.tile_out, idx_out, val_out, gathered,
+                   T.pairs);
+    } else {
+        IWP_LAUNCH("k_scan", k_scan, T.n_layers, s, T.layers, ws.stile_counts, false, nullptr);
+        IWP_LAUNCH("k_write", (k_write<FUSED, false>), grid, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state,
+                   ws.stage, ws.A, all_raw, ws.tile_counts, ws.stile_counts, ws.tile_out, idx_out, val_out, gathered,
+                   T.pairs);
+    }
+    return IWP_OK;
+}
+
+// Selection on the leaders' residuals after look 1 has filled the first-digit
+// histograms, then (FULL) the ordered split.  fused: whole-step route (leader row
+// of the gather matrix, leader residual cleared).
 int run_select(const Table& T, const Workspace& ws, const ResidualPtrs& R, const float* w, const uint32_t* leader,
                uint32_t W, float eps, Stop stop, bool fused, uint32_t* idx_out, float* val_out,
                iwp_threshold* thr_out, hipStream_t s) {
     if (!T.any_k || T.tiles == 0) return IWP_OK;
-    IWP_LAUNCH("k_pick<0>", k_pick<0>, T.n_layers, s, T.layers, ws.hist, ws.state, thr_out);
+    IWP_LAUNCH("k_first_pick", k_first_pick, T.n_layers, s, T.layers, ws.hist, ws.state);
     IWP_LAUNCH("k_stage", k_stage, T.tiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.hist,
                ws.stage, ws.A);
-    IWP_LAUNCH("k_pick<1>", k_pick<1>, T.n_layers, s, T.layers, ws.hist, ws.state, thr_out);
     IWP_LAUNCH("k_refine2", k_refine2, T.stiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.stage,
                ws.A, ws.hist);
-    IWP_LAUNCH("k_pick<2>", k_pick<2>, T.n_layers, s, T.layers, ws.hist, ws.state, thr_out);
-    if (stop == STOP_AT_THRESHOLD) return IWP_OK;
-    IWP_LAUNCH("k_count", k_count, T.stiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.stage, ws.A,
-               false, ws.tile_counts, ws.stile_counts);
-    IWP_LAUNCH("k_scan", k_scan, T.n_layers, s, T.layers, ws.stile_counts, false, nullptr);
-    if (fused)
-        IWP_LAUNCH("k_write", k_write<true>, (T.tiles + 3) / 4, s, R, w, T.layers, T.n_layers, T.tiles, leader, W, eps, ws.state, ws.stage,
-                   ws.A, false, ws.tile_counts, ws.stile_counts, ws.tile_out, idx_out, val_out, ws.gathered, T.pairs);
-    else
-        IWP_LAUNCH("k_write", k_write<false>, (T.tiles + 3) / 4, s, R, w, T.layers, T.n_layers, T.tiles, leader, W, eps, ws.state, ws.stage,
-                   ws.A, false, ws.tile_counts, ws.stile_counts, ws.tile_out, idx_out, val_out, nullptr, T.pairs);
-    return IWP_OK;
+    if (stop == STOP_AT_THRESHOLD) {
+        IWP_LAUNCH("k_final_pick", k_final_pick, T.n_layers, s, T.layers, ws.hist, ws.state, thr_out);
+        return IWP_OK;
+    }
+    IWP_LAUNCH("k_count", k_count<false>, T.stiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.hist,
+               thr_out, ws.stage, ws.A, ws.tile_counts, ws.stile_counts);
+    if (fused) return launch_write<true>(T, ws, R, w, leader, W, eps, false, idx_out, val_out, s);
+    return launch_write<false>(T, ws, R, w, leader, W, eps, false, idx_out, val_out, s);
 }
 
 // Ordered split from threshold records given by the caller (nothing is staged: every tile is re-read).
@@ -209,12 +230,9 @@ int run_compact_from(const Table& T, const Workspace& ws, const ResidualPtrs& R,
     if (!T.any_k || T.tiles == 0) return IWP_OK;
     IWP_LAUNCH("k_load_thresholds", k_load_thresholds, (T.n_layers + BLOCK - 1) / BLOCK, s, T.layers, T.n_layers, thr,
                ws.state);
-    IWP_LAUNCH("k_count", k_count, T.stiles, s, R, w, T.layers, T.n_layers, nullptr, 1u, eps, ws.state, ws.stage, ws.A,
-               true, ws.tile_counts, ws.stile_counts);
-    IWP_LAUNCH("k_scan", k_scan, T.n_layers, s, T.layers, ws.stile_counts, false, nullptr);
-    IWP_LAUNCH("k_write", k_write<false>, (T.tiles + 3) / 4, s, R, w, T.layers, T.n_layers, T.tiles, nullptr, 1u, eps, ws.state, ws.stage,
-               ws.A, true, ws.tile_counts, ws.stile_counts, ws.tile_out, idx_out, val_out, nullptr, T.pairs);
-    return IWP_OK;
+    IWP_LAUNCH("k_count", k_count<true>, T.stiles, s, R, w, T.layers, T.n_layers, nullptr, 1u, eps, ws.state, ws.hist,
+               nullptr, ws.stage, ws.A, ws.tile_counts, ws.stile_counts);
+    return launch_write<false>(T, ws, R, w, nullptr, 1u, eps, true, idx_out, val_out, s);
 }
 
 }  // namespace
@@ -226,6 +244,7 @@ struct iwp_plan {
     uint64_t flat_end = 0;        // one past the last element any layer covers
     bool any_k = false;
     bool all_k = true;            // every non-empty layer selects something
+    uint32_t max_layer_stiles = 0;
     float momentum = 1.0f;        // r <- momentum * r + g in every call that accumulates through this plan
 };
 
@@ -292,7 +311,7 @@ static int single_common(SingleOp op, const float* w, const float* g, float* r, 
     sentinel.tile_begin = z.tiles; sentinel.stile_begin = z.stiles; sentinel.out_offset = k;
     int rc = launch_init(ws, 1, nullptr, &row, &sentinel, s);
     if (rc) return rc;
-    Table T{ws.single_table, 1, z.tiles, z.stiles, k, k > 0};
+    Table T{ws.single_table, 1, z.tiles, z.stiles, k, k > 0, z.stiles};
     if (op == OP_COMPACT) return run_compact_from(T, ws, R, w, eps, from_thr, idx_out, val_out, s);
     if (k > 0)
         IWP_LAUNCH("k_leader_pass", k_leader_pass<LGROUP>, z.stiles * (GROUP / LGROUP), s, P, w, T.layers, 1u, nullptr, 1u, eps, ws.hist,
@@ -372,6 +391,7 @@ int iwp_plan_create(const iwp_layer* layers, uint32_t n_layers, iwp_plan** plan_
     std::vector<DevLayer> dev(n_layers + 1);
     uint64_t pairs = 0, slots = 0, tiles = 0, stiles = 0, end = 0, mask_words = 0;
     bool any_k = false, all_k = true;
+    uint32_t max_stiles = 0;
     for (uint32_t j = 0; j < n_layers; ++j) {
         const iwp_layer& L = layers[j];
         if (L.offset < 0 || L.k > L.n) return IWP_EINVAL;
@@ -396,6 +416,7 @@ int iwp_plan_create(const iwp_layer* layers, uint32_t n_layers, iwp_plan** plan_
         stiles += stiles_of(L.n);
         mask_words += ((uint64_t)L.n + 31) / 32;
         any_k = any_k || L.k > 0;
+        max_stiles = std::max(max_stiles, stiles_of(L.n));
         if (L.n > 0 && L.k == 0) all_k = false;
         if (pairs > 0xFFFFFFFFull || tiles > 0x7FFFFFFFull / IWP_MAX_WORKERS) return IWP_ERANGE;
     }
@@ -411,6 +432,7 @@ int iwp_plan_create(const iwp_layer* layers, uint32_t n_layers, iwp_plan** plan_
     plan->z = Sizes{n_layers, (uint32_t)tiles, (uint32_t)stiles, pairs, slots, mask_words, 0};
     plan->any_k = any_k;
     plan->all_k = all_k;
+    plan->max_layer_stiles = max_stiles;
     plan->flat_end = end;
     // the table, then the layer of every tile and of every super-tile (find_layer reads them)
     std::vector<uint32_t> map;
@@ -506,7 +528,7 @@ static int compress_segmented_on(const iwp_plan* plan, const float* w, const flo
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     rc = launch_init(ws, plan->z.n_layers, thr_hint, nullptr, nullptr, s);
     if (rc) return rc;
-    Table T{plan->dev, plan->z.n_layers, plan->z.tiles, plan->z.stiles, plan->z.pairs, plan->any_k};
+    Table T{plan->dev, plan->z.n_layers, plan->z.tiles, plan->z.stiles, plan->z.pairs, plan->any_k, plan->max_layer_stiles};
     if (T.any_k)
         IWP_LAUNCH("k_leader_pass", k_leader_pass<LGROUP>, T.stiles * (GROUP / LGROUP), s, P, w, T.layers, T.n_layers, leader, W, eps,
                    ws.hist, ws.state, ws.stage, ws.A);
@@ -555,7 +577,7 @@ int iwp_step_segmented(const iwp_plan* plan, float* w, const float* const* g, fl
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     rc = launch_init(ws, z.n_layers, thr_hint, nullptr, nullptr, s);
     if (rc) return rc;
-    Table T{plan->dev, z.n_layers, z.tiles, z.stiles, z.pairs, plan->any_k};
+    Table T{plan->dev, z.n_layers, z.tiles, z.stiles, z.pairs, plan->any_k, plan->max_layer_stiles};
     if (T.any_k) {
         IWP_LAUNCH("k_leader_pass", k_leader_pass<LGROUP>, T.stiles * (GROUP / LGROUP), s, P, w, T.layers, T.n_layers, leader, W, eps,
                    ws.hist, ws.state, ws.stage, ws.A);
@@ -599,7 +621,7 @@ int select_threshold_segmented(const iwp_plan* plan, const float* w, const float
     ResidualPtrs R;
     memset(&R, 0, sizeof R);
     R.r[0] = const_cast<float*>(r);
-    Table T{plan->dev, plan->z.n_layers, plan->z.tiles, plan->z.stiles, plan->z.pairs, plan->any_k};
+    Table T{plan->dev, plan->z.n_layers, plan->z.tiles, plan->z.stiles, plan->z.pairs, plan->any_k, plan->max_layer_stiles};
     IWP_LAUNCH("k_leader_pass", k_leader_pass<LGROUP>, T.stiles * (GROUP / LGROUP), s, P, w, T.layers, T.n_layers, nullptr, 1u, eps,
                ws.hist, ws.state, ws.stage, ws.A);
     return run_select(T, ws, R, w, nullptr, 1u, eps, STOP_AT_THRESHOLD, false, nullptr, nullptr, thr_out, s);
@@ -620,7 +642,7 @@ int compact_pairs_segmented(const iwp_plan* plan, const float* w, const float* r
     ResidualPtrs R;
     memset(&R, 0, sizeof R);
     R.r[0] = const_cast<float*>(r);
-    Table T{plan->dev, plan->z.n_layers, plan->z.tiles, plan->z.stiles, plan->z.pairs, plan->any_k};
+    Table T{plan->dev, plan->z.n_layers, plan->z.tiles, plan->z.stiles, plan->z.pairs, plan->any_k, plan->max_layer_stiles};
     return run_compact_from(T, ws, R, w, eps, thr, idx_out, val_out, s);
 }
 

@@ -67,14 +67,16 @@ struct DevLayer {
     uint32_t pad;
 };
 
-struct LayerState {        // selection state of one layer, lives in the workspace
-    uint32_t prefix;       // key bits resolved so far (right-aligned); finally the threshold key
-    uint32_t k_rem;        // rank still to be found inside the prefix group (1-based)
-    uint32_t n_gt;
-    uint32_t n_eq_take;
+struct LayerState {        // selection state of one layer, lives in the workspace.  Every field has one writer
+                           // (one elected workgroup of one kernel) and is read only by later launches.
+    uint32_t b1;           // top key digit of the threshold (first pick)
+    uint32_t k_rem0;       // rank of the threshold inside that bin (1-based, counted from the largest key)
+    uint32_t p22;          // top two digits (second pick)
+    uint32_t k_rem1;       // rank inside that 22-bit group
+    uint32_t thr;          // the threshold key (third pick, or given by the caller)
+    uint32_t n_eq_take;    // ties to keep
     uint32_t stage_bin;    // look 1 copies out every element whose top digit is >= this bin (from a threshold hint)
-    uint32_t prestaged;    // set by the first pick: stage_bin <= threshold bin, so look 1's copies are complete
-    uint32_t pad0, pad1;
+    uint32_t prestaged;    // set with the first pick: stage_bin <= b1, so look 1's copies are complete
 };
 
 struct StageArrays {       // staged candidates, structure of arrays; tile t of a layer owns entries

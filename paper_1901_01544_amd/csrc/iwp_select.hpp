@@ -4,20 +4,27 @@
 //
 // The selection is an MSB-first radix select on the 31-bit importance key
 // (digits of 12 + 10 + 9 bits).  Look 1 (iwp_stream.hpp) histograms the top digit
-// of every element.  k_pick<0> finds the bin b1 that holds rank k.  Look 2 (k_stage)
-// reads the leader's residual and weights once more and copies out, per tile, the
-// only elements that can still matter: those whose top digit is >= b1 (above b1 all
-// of them are kept, the threshold lies among those inside b1), and histograms the
-// second digit of those inside b1.  Every tile owns a fixed slot in the staging
-// arrays, so look 2 needs no cross-workgroup coordination at all.  With a threshold
-// hint (say, last step's thresholds) look 1 already copies out everything from a
-// bin slightly below the hinted one; if the new b1 is not below that bin the copies
-// are complete and look 2 only reads the slots, not the layer.  Everything after
-// that works on the staged copies, a few percent of the layer: k_pick<1>, k_refine2
-// and k_pick<2> finish the threshold, k_count / k_scan / k_write place every kept
-// element at its rank in index order.  A tile whose candidates do not fit its slot
-// (heavy ties, e.g. a tile that is all zeros) is marked RAW and is simply re-read
-// from r and w by the later passes.  Both routes are exact.
+// of every element.  Look 2 (k_stage) reads the leader's residual and weights once
+// more and copies out, per tile, the only elements that can still matter: those whose
+// top digit is >= b1, the bin that holds rank k (above b1 all of them are kept, the
+// threshold lies among those inside b1), and histograms the second digit of those
+// inside b1.  Every tile owns a fixed slot in the staging arrays, so look 2 needs no
+// cross-workgroup coordination at all.  With a threshold hint (say, last step's
+// thresholds) look 1 already copies out everything from a bin slightly below the
+// hinted one; if the new b1 is not below that bin the copies are complete and look 2
+// only reads the slots, not the layer.  Everything after that works on the staged
+// copies, a few percent of the layer: k_refine2 histograms the third digit, k_count /
+// k_write place every kept element at its rank in index order.  A tile whose
+// candidates do not fit its slot (heavy ties, e.g. a tile that is all zeros) is marked
+// RAW and is simply re-read from r and w by the later passes.  Both routes are exact.
+//
+// The second and third digit picks have no launches of their own: a finished histogram is
+// the same for every reader, so each workgroup of the consuming kernel redoes the pick of its
+// layer in its prologue (k_refine2 the second, k_count the third), and one elected workgroup
+// per layer records it.  Likewise
+// k_write sums the counts of the layer's earlier super-tiles itself unless a layer has so
+// many that a scan launch (k_scan) is cheaper.  Kernel boundaries are the only
+// synchronisation between workgroups.
 #pragma once
 
 #include "iwp_common.hpp"
@@ -40,7 +47,7 @@ __global__ __launch_bounds__(BLOCK) void k_init(uint32_t* __restrict__ words, ui
     for (uint64_t i = (uint64_t)blockIdx.x * BLOCK + threadIdx.x; i < n_words; i += stride) words[i] = 0u;
     for (uint64_t j = (uint64_t)blockIdx.x * BLOCK + threadIdx.x; j < n_layers; j += stride) {
         LayerState st;
-        st.prefix = 0; st.k_rem = 0; st.n_gt = 0; st.n_eq_take = 0; st.prestaged = 0; st.pad0 = 0; st.pad1 = 0;
+        st.b1 = 0; st.k_rem0 = 0; st.p22 = 0; st.k_rem1 = 0; st.thr = 0; st.n_eq_take = 0; st.prestaged = 0;
         // one bin of slack below the hinted threshold bin (a bin is 1/16 octave); a hint in bin 0
         // (threshold among zero scores) or no hint: look 1 stages nothing
         const uint32_t hb = hint ? ((hint[j].key & 0x7fffffffu) >> digit_shift(0)) : 0u;
@@ -54,33 +61,47 @@ __global__ __launch_bounds__(BLOCK) void k_init(uint32_t* __restrict__ words, ui
 }
 
 // ---------------------------------------------------------------------------
-// Digit pick, one workgroup per layer: the bin of digit LEVEL that holds rank
-// k_rem, appended to the key prefix.  After the last digit the prefix is the
-// exact k-th largest key and k_rem the number of ties to keep.
+// First digit pick, one workgroup per layer: the bin b1 of the 4096-bin histogram that holds
+// rank k, and whether look 1's copies (staged from a hinted bin) already cover it.  This pick
+// keeps a launch of its own: its histogram is too large for every tile's workgroup to re-read,
+// and a summary of it would have to be built with atomics on a handful of addresses that all
+// workgroups of look 1 hit (measured: look 1 nearly twice as slow).
 // ---------------------------------------------------------------------------
-template <int LEVEL>
-__global__ __launch_bounds__(BLOCK) void k_pick(const DevLayer* __restrict__ layers, const uint32_t* __restrict__ hist,
-                                                LayerState* __restrict__ state, iwp_threshold* __restrict__ thr_out) {
+__global__ __launch_bounds__(BLOCK) void k_first_pick(const DevLayer* __restrict__ layers, const uint32_t* __restrict__ hist,
+                                                      LayerState* __restrict__ state) {
     __shared__ uint32_t sh[BLOCK + 2];
     const uint32_t j = blockIdx.x;
     const DevLayer L = layers[j];
     if (L.k == 0) return;
-    const uint32_t* h = hist + (size_t)j * HIST_STRIDE + hist_base(LEVEL);
-    const uint32_t k_in = LEVEL == 0 ? L.k : state[j].k_rem;
-    const uint32_t prefix = LEVEL == 0 ? 0u : state[j].prefix;
     uint32_t bin, k_rem;
-    block_pick<(1 << digit_bits(LEVEL))>(h, k_in, sh, &bin, &k_rem);
+    block_pick<(int)HIST0>(hist + (size_t)j * HIST_STRIDE, L.k, sh, &bin, &k_rem);
     if (threadIdx.x == 0) {
-        LayerState st = state[j];
-        st.prefix = (prefix << digit_bits(LEVEL)) | bin;
-        st.k_rem = k_rem;
-        st.n_eq_take = k_rem;
-        st.n_gt = L.k - k_rem;
-        if (LEVEL == 0) st.prestaged = (st.stage_bin != NO_STAGE_BIN && st.stage_bin <= bin) ? 1u : 0u;
-        state[j] = st;
-        if (LEVEL == DIGITS - 1 && thr_out) {
+        const uint32_t stage_bin = state[j].stage_bin;
+        state[j].b1 = bin;
+        state[j].k_rem0 = k_rem;
+        state[j].prestaged = (stage_bin != NO_STAGE_BIN && stage_bin <= bin) ? 1u : 0u;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Last digit pick on its own, one workgroup per layer, for the call that stops at the
+// threshold (select_threshold): the exact k-th largest key and the number of ties to keep.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(BLOCK) void k_final_pick(const DevLayer* __restrict__ layers, const uint32_t* __restrict__ hist,
+                                                      LayerState* __restrict__ state, iwp_threshold* __restrict__ thr_out) {
+    __shared__ uint32_t sh[BLOCK + 2];
+    const uint32_t j = blockIdx.x;
+    const DevLayer L = layers[j];
+    if (L.k == 0) return;
+    const uint32_t p22 = state[j].p22, k_rem1 = state[j].k_rem1;
+    uint32_t bin, k_rem;
+    block_pick<(int)HIST2>(hist + (size_t)j * HIST_STRIDE + hist_base(2), k_rem1, sh, &bin, &k_rem);
+    if (threadIdx.x == 0) {
+        state[j].thr = (p22 << digit_bits(2)) | bin;
+        state[j].n_eq_take = k_rem;
+        if (thr_out) {
             iwp_threshold th;
-            th.key = st.prefix; th.n_gt = st.n_gt; th.n_eq_take = st.n_eq_take;
+            th.key = (p22 << digit_bits(2)) | bin; th.n_gt = L.k - k_rem; th.n_eq_take = k_rem;
             thr_out[j] = th;
         }
     }
@@ -93,8 +114,9 @@ __global__ __launch_bounds__(BLOCK) void k_load_thresholds(const DevLayer* __res
     const uint32_t j = blockIdx.x * BLOCK + threadIdx.x;
     if (j >= n_layers || layers[j].k == 0) return;
     LayerState st;
-    st.prefix = thr[j].key; st.k_rem = thr[j].n_eq_take; st.n_gt = thr[j].n_gt; st.n_eq_take = thr[j].n_eq_take;
-    st.stage_bin = NO_STAGE_BIN; st.prestaged = 0; st.pad0 = 0; st.pad1 = 0;
+    st.b1 = 0; st.k_rem0 = 0; st.p22 = 0; st.k_rem1 = 0;
+    st.thr = thr[j].key; st.n_eq_take = thr[j].n_eq_take;
+    st.stage_bin = NO_STAGE_BIN; st.prestaged = 0;
     state[j] = st;
 }
 
@@ -126,14 +148,14 @@ __global__ __launch_bounds__(BLOCK) void k_stage(ResidualPtrs R, const float* __
     const uint32_t j = find_layer<false>(layers, n_layers, t);
     const DevLayer L = layers[j];
     if (L.k == 0) return;
-    const LayerState st = state[j];
-    const uint32_t b1 = st.prefix;
     const uint32_t lt = t - L.tile_begin;
+    const uint32_t b1 = state[j].b1;
+    const bool prestaged = state[j].prestaged != 0;
     const uint32_t base = lt * TILE;
     const uint64_t sb = L.slot_begin + (uint64_t)lt * L.slot_cap;
     uint32_t* h1 = hist + (size_t)j * HIST_STRIDE + hist_base(1);
 
-    if (st.prestaged) {
+    if (prestaged) {
         const uint32_t cnt = stage_cnt[t];
         if (cnt != RAW_TILE) {
             // the slot already holds everything from a bin <= b1: histogram from it
@@ -227,23 +249,31 @@ __global__ __launch_bounds__(BLOCK) void k_stage(ResidualPtrs R, const float* __
 }
 
 // ---------------------------------------------------------------------------
-// Third digit: histogram over the elements whose first two digits match the prefix,
-// taken from the tile slots (or from r, w for RAW tiles).  One workgroup per
-// super-tile.
+// Third digit: histogram over the elements whose first two digits match the prefix
+// (the prologue's pick appended to b1), taken from the tile slots (or from r, w for RAW
+// tiles).  One workgroup per super-tile.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(BLOCK) void k_refine2(ResidualPtrs R, const float* __restrict__ w,
                                                    const DevLayer* __restrict__ layers, uint32_t n_layers,
                                                    const uint32_t* __restrict__ leader, uint32_t W, float eps,
-                                                   const LayerState* __restrict__ state,
+                                                   LayerState* __restrict__ state,
                                                    const uint32_t* __restrict__ stage_cnt, StageArrays A,
                                                    uint32_t* __restrict__ hist) {
     __shared__ uint32_t lh[HIST2];
+    __shared__ uint32_t sh[BLOCK + 2];
     const uint32_t tid = threadIdx.x;
     const uint32_t s = blockIdx.x;
     const uint32_t j = find_layer<true>(layers, n_layers, s);
     const DevLayer L = layers[j];
     if (L.k == 0) return;
-    const uint32_t prefix = state[j].prefix;                    // 22 bits
+    // second pick, redone by every workgroup of the layer, from the finished second-digit histogram
+    uint32_t bin1, k_rem1;
+    block_pick<(int)HIST1>(hist + (size_t)j * HIST_STRIDE + hist_base(1), state[j].k_rem0, sh, &bin1, &k_rem1);
+    const uint32_t prefix = (state[j].b1 << digit_bits(1)) | bin1;            // 22 bits
+    if (s == L.stile_begin && tid == 0) {
+        state[j].p22 = prefix;
+        state[j].k_rem1 = k_rem1;
+    }
     const uint32_t ntiles = (L.n + TILE - 1) / TILE;
     const uint32_t lt0 = (s - L.stile_begin) * GROUP;
     const uint32_t nt = min(GROUP, ntiles - lt0);
@@ -282,23 +312,46 @@ __global__ __launch_bounds__(BLOCK) void k_refine2(ResidualPtrs R, const float* 
 // ---------------------------------------------------------------------------
 // Ordered split, part 1: per tile, how many elements lie above the threshold and
 // how many tie with it.  One workgroup per super-tile; writes each tile's exclusive
-// prefix inside the super-tile and the super-tile's totals.  all_raw: there is no
-// stage table (compact_pairs), every tile is re-read.
+// prefix inside the super-tile and the super-tile's totals.  The threshold is the
+// prologue's third pick (recorded, with thr_out, by the layer's first workgroup), or with
+// FROM_RECORDS the caller's record (compact_pairs): then there is no stage table and
+// every tile is re-read.
 // ---------------------------------------------------------------------------
+template <bool FROM_RECORDS>
 __global__ __launch_bounds__(BLOCK) void k_count(ResidualPtrs R, const float* __restrict__ w,
                                                  const DevLayer* __restrict__ layers, uint32_t n_layers,
                                                  const uint32_t* __restrict__ leader, uint32_t W, float eps,
-                                                 const LayerState* __restrict__ state,
-                                                 const uint32_t* __restrict__ stage_cnt, StageArrays A, bool all_raw,
+                                                 LayerState* __restrict__ state, const uint32_t* __restrict__ hist,
+                                                 iwp_threshold* __restrict__ thr_out,
+                                                 const uint32_t* __restrict__ stage_cnt, StageArrays A,
                                                  uint2* __restrict__ tile_counts, uint2* __restrict__ stile_counts) {
     __shared__ uint32_t cg[GROUP], ce[GROUP];
+    __shared__ uint32_t sh[BLOCK + 2];
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & (WAVE - 1), wave = tid >> 6;
     const uint32_t s = blockIdx.x;
     const uint32_t j = find_layer<true>(layers, n_layers, s);
     const DevLayer L = layers[j];
     if (L.k == 0) return;
-    const uint32_t thr = state[j].prefix;
+    constexpr bool all_raw = FROM_RECORDS;
+    uint32_t thr;
+    if (FROM_RECORDS) {
+        thr = state[j].thr;
+    } else {
+        // third pick, redone by every workgroup of the layer: the exact k-th largest key
+        uint32_t bin2, k_rem2;
+        block_pick<(int)HIST2>(hist + (size_t)j * HIST_STRIDE + hist_base(2), state[j].k_rem1, sh, &bin2, &k_rem2);
+        thr = (state[j].p22 << digit_bits(2)) | bin2;
+        if (s == L.stile_begin && tid == 0) {
+            state[j].thr = thr;
+            state[j].n_eq_take = k_rem2;
+            if (thr_out) {
+                iwp_threshold th;
+                th.key = thr; th.n_gt = L.k - k_rem2; th.n_eq_take = k_rem2;
+                thr_out[j] = th;
+            }
+        }
+    }
     const uint32_t ntiles = (L.n + TILE - 1) / TILE;
     const uint32_t lt0 = (s - L.stile_begin) * GROUP;           // first tile of the super-tile, in the layer
     const uint32_t nt = min(GROUP, ntiles - lt0);
@@ -389,11 +442,12 @@ __global__ __launch_bounds__(BLOCK) void k_scan(const DevLayer* __restrict__ lay
 // residual itself).  tile_out[t] receives the position of the tile's first pair.
 // FUSED (whole-step entry point): the value also goes into the leader's row of the
 // gather matrix and the leader's residual is cleared at the sent position.
-// One wavefront per tile (four tiles per workgroup, nothing workgroup-wide).
-template <bool FUSED>
+// One wavefront per tile, four tiles (half a super-tile) per workgroup.  FOLD: the super-tile
+// totals are as k_count left them and the workgroup adds up the layer's earlier ones itself;
+// otherwise k_scan has turned them into prefixes.
+template <bool FUSED, bool FOLD>
 __global__ __launch_bounds__(BLOCK) void k_write(ResidualPtrs R, const float* __restrict__ w,
                                                  const DevLayer* __restrict__ layers, uint32_t n_layers,
-                                                 uint32_t tiles_total,
                                                  const uint32_t* __restrict__ leader, uint32_t W, float eps,
                                                  const LayerState* __restrict__ state,
                                                  const uint32_t* __restrict__ stage_cnt, StageArrays A, bool all_raw,
@@ -403,18 +457,43 @@ __global__ __launch_bounds__(BLOCK) void k_write(ResidualPtrs R, const float* __
                                                  uint32_t* __restrict__ idx_out, float* __restrict__ val_out,
                                                  float* __restrict__ gathered, uint64_t K) {
     __shared__ uint32_t maps[BLOCK / WAVE][4][TILE_WORDS];
+    __shared__ uint32_t red[2][BLOCK / WAVE];
     const uint32_t lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x >> 6;
-    const uint32_t t = blockIdx.x * (BLOCK / WAVE) + wave;
-    if (t >= tiles_total) return;
-    const uint32_t j = find_layer<false>(layers, n_layers, t);
+    const uint32_t s = blockIdx.x / (GROUP / (BLOCK / WAVE));            // the workgroup's super-tile
+    const uint32_t part = blockIdx.x % (GROUP / (BLOCK / WAVE));
+    const uint32_t j = find_layer<true>(layers, n_layers, s);
     const DevLayer L = layers[j];
     if (L.k == 0) return;
+    const uint32_t ntiles = (L.n + TILE - 1) / TILE;
+    const uint32_t lt = (s - L.stile_begin) * GROUP + part * (BLOCK / WAVE) + wave;
+    if (lt - wave >= ntiles) return;                                      // uniform: nothing of this part exists
+    uint2 sc;
+    if (FOLD) {
+        // elements above / tying in the layer's earlier super-tiles: summed here, by everybody
+        uint32_t g = 0, e = 0;
+        for (uint32_t q = L.stile_begin + threadIdx.x; q < s; q += BLOCK) {
+            const uint2 c = stile_counts[q];
+            g += c.x;
+            e += c.y;
+        }
+#pragma unroll
+        for (int d = WAVE / 2; d > 0; d >>= 1) {
+            g += __shfl_xor(g, d, WAVE);
+            e += __shfl_xor(e, d, WAVE);
+        }
+        if (lane == 0) { red[0][wave] = g; red[1][wave] = e; }
+        __syncthreads();
+        sc.x = red[0][0] + red[0][1] + red[0][2] + red[0][3];
+        sc.y = red[1][0] + red[1][1] + red[1][2] + red[1][3];
+    } else {
+        sc = stile_counts[s];                                             // already scanned (k_scan)
+    }
+    if (lt >= ntiles) return;
+    const uint32_t t = L.tile_begin + lt;
     const LayerState st = state[j];
-    const uint32_t thr = st.prefix, quota = st.n_eq_take;
+    const uint32_t thr = st.thr, quota = st.n_eq_take;
     const uint32_t lead = leader_of(leader, j, W);
     float* rl = R.r[lead] + L.offset;
-    const uint32_t lt = t - L.tile_begin;
-    const uint2 sc = stile_counts[L.stile_begin + lt / GROUP];
     const uint2 tc = tile_counts[t];
     const uint32_t Gt = sc.x + tc.x, Et = sc.y + tc.y;         // elements above / tying, before this tile
     const uint32_t out_base = Gt + min(Et, quota);
