@@ -42,7 +42,7 @@ def hipcc() -> str:
 
 def build(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
     """Compile csrc/ into libiwp.so (always recompiles); returns the path.
-    extra_flags / out: build a variant (say, with -save-temps or other compiler flags) somewhere else."""
+    extra_flags / out: build a tuning variant (e.g. -DIWP_LGROUP=4) somewhere else."""
     tmp = out + ".tmp.%d" % os.getpid()
     cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags, "-o", tmp, SRC]
     if verbose:

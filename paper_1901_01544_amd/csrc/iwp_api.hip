@@ -109,10 +109,20 @@ inline uint32_t slot_cap_of(uint32_t n, uint32_t k) {
     return (uint32_t)std::min<uint64_t>(TILE, 64 + 3 * per_tile);
 }
 
+// Copies of a layer's first-digit histogram: one per FLUSHES_PER_COPY look-1 workgroups, a power of two.
+inline uint32_t h0_copies_of(uint32_t n, uint32_t k) {
+    if (k == 0) return 1u;
+    const uint32_t groups = (tiles_of(n) + LGROUP - 1) / LGROUP;
+    uint32_t c = 1;
+    while (c < MAX_H0_COPIES && c * FLUSHES_PER_COPY < groups) c <<= 1;
+    return c;
+}
+
 struct Sizes {                // everything the workspace layout depends on
     uint32_t n_layers, tiles, stiles;
     uint64_t pairs, slots;    // slots: staging entries over all tiles
     uint64_t mask_words;      // 32-bit words of all layers' encoded masks (threshold mode)
+    uint64_t hist_words;      // words of all layers' histograms
     uint32_t W_gather;        // rows of the gather matrix (whole-step entry point), else 0
 };
 
@@ -120,7 +130,7 @@ struct Sizes {                // everything the workspace layout depends on
 struct Workspace {
     DevLayer* single_table;   // 2 rows, used by the single-layer entry points
     uint64_t hist_words;      // what k_init clears
-    uint32_t* hist;           // n_layers * HIST_STRIDE
+    uint32_t* hist;           // hist_words
     LayerState* state;        // n_layers
     uint32_t* stage;          // tiles: staged entries per tile, or RAW_TILE
     uint2* tile_counts;       // tiles
@@ -137,11 +147,11 @@ Workspace carve(void* base, const Sizes& z) {
     size_t off = 0;
     auto take = [&](size_t bytes) { uintptr_t p = b + off; off += round256(bytes); return p; };
     ws.single_table = reinterpret_cast<DevLayer*>(take(2 * sizeof(DevLayer)));
-    const size_t hist_bytes = round256((size_t)z.n_layers * HIST_STRIDE * sizeof(uint32_t));
+    const size_t hist_bytes = round256((size_t)z.hist_words * sizeof(uint32_t));
     const size_t state_bytes = round256((size_t)z.n_layers * sizeof(LayerState));
     ws.hist = reinterpret_cast<uint32_t*>(take(hist_bytes));
     ws.state = reinterpret_cast<LayerState*>(take(state_bytes));
-    ws.hist_words = (uint64_t)z.n_layers * HIST_STRIDE;
+    ws.hist_words = z.hist_words;
     ws.stage = reinterpret_cast<uint32_t*>(take((size_t)z.tiles * sizeof(uint32_t)));
     ws.tile_counts = reinterpret_cast<uint2*>(take((size_t)z.tiles * sizeof(uint2)));
     ws.stile_counts = reinterpret_cast<uint2*>(take((size_t)z.stiles * sizeof(uint2)));
@@ -271,6 +281,7 @@ static Sizes single_sizes(uint32_t n, uint32_t k) {
     Sizes z;
     z.n_layers = 1; z.tiles = tiles_of(n); z.stiles = stiles_of(n);
     z.pairs = k; z.slots = (uint64_t)z.tiles * slot_cap_of(n, k); z.mask_words = ((uint64_t)n + 31) / 32;
+    z.hist_words = layer_hist_words(h0_copies_of(n, k));
     z.W_gather = 0;
     return z;
 }
@@ -308,6 +319,7 @@ static int single_common(SingleOp op, const float* w, const float* g, float* r, 
     memset(&row, 0, sizeof row);
     memset(&sentinel, 0, sizeof sentinel);
     row.n = n; row.k = k; row.slot_cap = slot_cap_of(n, k);
+    row.hist_begin = 0; row.h0_copies = h0_copies_of(n, k);
     sentinel.tile_begin = z.tiles; sentinel.stile_begin = z.stiles; sentinel.out_offset = k;
     int rc = launch_init(ws, 1, nullptr, &row, &sentinel, s);
     if (rc) return rc;
@@ -389,7 +401,7 @@ int iwp_plan_create(const iwp_layer* layers, uint32_t n_layers, iwp_plan** plan_
     *plan_out = nullptr;
     if (!layers || n_layers == 0) return IWP_EINVAL;
     std::vector<DevLayer> dev(n_layers + 1);
-    uint64_t pairs = 0, slots = 0, tiles = 0, stiles = 0, end = 0, mask_words = 0;
+    uint64_t pairs = 0, slots = 0, tiles = 0, stiles = 0, end = 0, mask_words = 0, hist_words = 0;
     bool any_k = false, all_k = true;
     uint32_t max_stiles = 0;
     for (uint32_t j = 0; j < n_layers; ++j) {
@@ -409,6 +421,9 @@ int iwp_plan_create(const iwp_layer* layers, uint32_t n_layers, iwp_plan** plan_
         D.stile_begin = (uint32_t)stiles;
         D.slot_cap = slot_cap_of(L.n, L.k);
         D.mask_begin = (uint32_t)mask_words;
+        D.hist_begin = (uint32_t)hist_words;
+        D.h0_copies = h0_copies_of(L.n, L.k);
+        hist_words += layer_hist_words(D.h0_copies);
         end = (uint64_t)L.offset + L.n;
         pairs += L.k;
         slots += (uint64_t)tiles_of(L.n) * D.slot_cap;
@@ -418,7 +433,7 @@ int iwp_plan_create(const iwp_layer* layers, uint32_t n_layers, iwp_plan** plan_
         any_k = any_k || L.k > 0;
         max_stiles = std::max(max_stiles, stiles_of(L.n));
         if (L.n > 0 && L.k == 0) all_k = false;
-        if (pairs > 0xFFFFFFFFull || tiles > 0x7FFFFFFFull / IWP_MAX_WORKERS) return IWP_ERANGE;
+        if (pairs > 0xFFFFFFFFull || tiles > 0x7FFFFFFFull / IWP_MAX_WORKERS || hist_words > 0xFFFFFFFFull) return IWP_ERANGE;
     }
     DevLayer& S = dev[n_layers];
     memset(&S, 0, sizeof S);
@@ -429,7 +444,7 @@ int iwp_plan_create(const iwp_layer* layers, uint32_t n_layers, iwp_plan** plan_
     iwp_plan* plan = new (std::nothrow) iwp_plan;
     if (!plan) return IWP_EINVAL;
     plan->rows.assign(layers, layers + n_layers);
-    plan->z = Sizes{n_layers, (uint32_t)tiles, (uint32_t)stiles, pairs, slots, mask_words, 0};
+    plan->z = Sizes{n_layers, (uint32_t)tiles, (uint32_t)stiles, pairs, slots, mask_words, hist_words, 0};
     plan->any_k = any_k;
     plan->all_k = all_k;
     plan->max_layer_stiles = max_stiles;

@@ -35,7 +35,10 @@ constexpr uint32_t CHUNK = BLOCK * VEC;            // 1024 elements per workgrou
 constexpr uint32_t CHUNKS_PER_TILE = 4;
 constexpr uint32_t TILE = CHUNK * CHUNKS_PER_TILE; // 4096 elements: the streaming unit (measured best on MI355X)
 constexpr uint32_t GROUP = 8;                      // tiles per super-tile
-constexpr uint32_t LGROUP = 2;                     // tiles that share one LDS histogram in look 1 (divides GROUP;
+#ifndef IWP_LGROUP
+#define IWP_LGROUP 2                               // build-time tuning knob: -DIWP_LGROUP=1|2|4|8
+#endif
+constexpr uint32_t LGROUP = IWP_LGROUP;            // tiles that share one LDS histogram in look 1 (divides GROUP;
                                                    // 2 and 4 measure alike on large layers, 2 is ahead by about
                                                    // 1 % on sets of many small layers; 1 and 8 are behind)
 constexpr uint32_t STILE = TILE * GROUP;           // 32768 elements: unit of the leader-side passes
@@ -47,8 +50,13 @@ constexpr int DIGITS = 3;
 __host__ __device__ constexpr int digit_shift(int level) { return level == 0 ? 19 : (level == 1 ? 9 : 0); }
 __host__ __device__ constexpr int digit_bits(int level) { return level == 0 ? 12 : (level == 1 ? 10 : 9); }
 constexpr uint32_t HIST0 = 1u << 12, HIST1 = 1u << 10, HIST2 = 1u << 9;
-constexpr uint32_t HIST_STRIDE = HIST0 + HIST1 + HIST2;    // words per layer; each digit has its own region
-__host__ __device__ constexpr uint32_t hist_base(int level) { return level == 0 ? 0 : (level == 1 ? HIST0 : HIST0 + HIST1); }
+// A layer's histograms in the workspace: h0_copies copies of the first digit's (look 1 flushes one LDS
+// histogram per workgroup with atomics, and atomics on one address serialise at about 20 ns each on this
+// chip, so a layer with thousands of workgroups spreads them over several copies), then one of the second
+// digit's and one of the third's.
+constexpr uint32_t MAX_H0_COPIES = 16;
+constexpr uint32_t FLUSHES_PER_COPY = 512;                 // look-1 workgroups that share one copy
+__host__ __device__ constexpr uint32_t layer_hist_words(uint32_t copies) { return copies * HIST0 + HIST1 + HIST2; }
 
 constexpr uint32_t RAW_TILE = 0xFFFFFFFFu;        // stage count of a tile whose candidates did not fit its slot
 constexpr uint32_t NO_STAGE_BIN = 0xFFFFFFFFu;    // LayerState.stage_bin: look 1 stages nothing for this layer
@@ -64,8 +72,19 @@ struct DevLayer {
     uint32_t stile_begin;  // first STILE of the layer
     uint32_t slot_cap;     // staging entries per tile of this layer
     uint32_t mask_begin;   // first 32-bit word of the layer's encoded mask (threshold mode)
+    uint32_t hist_begin;   // first word of the layer's histograms
+    uint32_t h0_copies;    // copies of the first-digit histogram (a power of two)
     uint32_t pad;
 };
+
+// Where digit `level`'s histogram of a layer starts (level 0: the first copy).
+__device__ __forceinline__ uint32_t* layer_hist(uint32_t* hist, const DevLayer& L, int level) {
+    uint32_t* h = hist + L.hist_begin;
+    return level == 0 ? h : (level == 1 ? h + L.h0_copies * HIST0 : h + L.h0_copies * HIST0 + HIST1);
+}
+__device__ __forceinline__ const uint32_t* layer_hist(const uint32_t* hist, const DevLayer& L, int level) {
+    return layer_hist(const_cast<uint32_t*>(hist), L, level);
+}
 
 struct LayerState {        // selection state of one layer, lives in the workspace.  Every field has one writer
                            // (one elected workgroup of one kernel) and is read only by later launches.

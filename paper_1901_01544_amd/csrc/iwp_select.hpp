@@ -65,16 +65,47 @@ __global__ __launch_bounds__(BLOCK) void k_init(uint32_t* __restrict__ words, ui
 // rank k, and whether look 1's copies (staged from a hinted bin) already cover it.  This pick
 // keeps a launch of its own: its histogram is too large for every tile's workgroup to re-read,
 // and a summary of it would have to be built with atomics on a handful of addresses that all
-// workgroups of look 1 hit (measured: look 1 nearly twice as slow).
+// workgroups of look 1 hit (measured: look 1 nearly twice as slow).  A layer whose look 1
+// flushed into several copies has them added up here first.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(BLOCK) void k_first_pick(const DevLayer* __restrict__ layers, const uint32_t* __restrict__ hist,
+__global__ __launch_bounds__(BLOCK) void k_first_pick(const DevLayer* __restrict__ layers, uint32_t* __restrict__ hist,
                                                       LayerState* __restrict__ state) {
     __shared__ uint32_t sh[BLOCK + 2];
     const uint32_t j = blockIdx.x;
     const DevLayer L = layers[j];
     if (L.k == 0) return;
+    uint32_t* h0 = layer_hist(hist, L, 0);
+    if (L.h0_copies > 1) {
+        // fold the copies into the first one (this workgroup is the layer's only reader and writer here)
+        constexpr uint32_t PER = HIST0 / BLOCK;                  // 16 consecutive bins per thread
+        constexpr uint32_t Q = PER / 4;
+        uint4 acc[Q];
+#pragma unroll
+        for (uint32_t q = 0; q < Q; ++q) acc[q] = make_uint4(0u, 0u, 0u, 0u);
+        // the copies come in powers of two: two at a time, or four at a time with all loads issued first
+        const uint32_t step = L.h0_copies == 2 ? 2u : 4u;
+        for (uint32_t c0 = 0; c0 < L.h0_copies; c0 += step) {
+            uint4 v[4][Q];
+#pragma unroll
+            for (uint32_t c = 0; c < 4; ++c)
+#pragma unroll
+                for (uint32_t q = 0; q < Q; ++q)
+                    v[c][q] = c < step ? reinterpret_cast<const uint4*>(h0 + (size_t)(c0 + c) * HIST0 + threadIdx.x * PER)[q]
+                                       : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+            for (uint32_t c = 0; c < 4; ++c)
+#pragma unroll
+                for (uint32_t q = 0; q < Q; ++q) {
+                    acc[q].x += v[c][q].x; acc[q].y += v[c][q].y; acc[q].z += v[c][q].z; acc[q].w += v[c][q].w;
+                }
+        }
+        uint4* mine = reinterpret_cast<uint4*>(h0 + threadIdx.x * PER);
+#pragma unroll
+        for (uint32_t q = 0; q < Q; ++q) mine[q] = acc[q];
+        __syncthreads();                                         // the pick below reads what the others stored
+    }
     uint32_t bin, k_rem;
-    block_pick<(int)HIST0>(hist + (size_t)j * HIST_STRIDE, L.k, sh, &bin, &k_rem);
+    block_pick<(int)HIST0>(h0, L.k, sh, &bin, &k_rem);
     if (threadIdx.x == 0) {
         const uint32_t stage_bin = state[j].stage_bin;
         state[j].b1 = bin;
@@ -95,7 +126,7 @@ __global__ __launch_bounds__(BLOCK) void k_final_pick(const DevLayer* __restrict
     if (L.k == 0) return;
     const uint32_t p22 = state[j].p22, k_rem1 = state[j].k_rem1;
     uint32_t bin, k_rem;
-    block_pick<(int)HIST2>(hist + (size_t)j * HIST_STRIDE + hist_base(2), k_rem1, sh, &bin, &k_rem);
+    block_pick<(int)HIST2>(layer_hist(hist, L, 2), k_rem1, sh, &bin, &k_rem);
     if (threadIdx.x == 0) {
         state[j].thr = (p22 << digit_bits(2)) | bin;
         state[j].n_eq_take = k_rem;
@@ -153,7 +184,7 @@ __global__ __launch_bounds__(BLOCK) void k_stage(ResidualPtrs R, const float* __
     const bool prestaged = state[j].prestaged != 0;
     const uint32_t base = lt * TILE;
     const uint64_t sb = L.slot_begin + (uint64_t)lt * L.slot_cap;
-    uint32_t* h1 = hist + (size_t)j * HIST_STRIDE + hist_base(1);
+    uint32_t* h1 = layer_hist(hist, L, 1);
 
     if (prestaged) {
         const uint32_t cnt = stage_cnt[t];
@@ -268,7 +299,7 @@ __global__ __launch_bounds__(BLOCK) void k_refine2(ResidualPtrs R, const float* 
     if (L.k == 0) return;
     // second pick, redone by every workgroup of the layer, from the finished second-digit histogram
     uint32_t bin1, k_rem1;
-    block_pick<(int)HIST1>(hist + (size_t)j * HIST_STRIDE + hist_base(1), state[j].k_rem0, sh, &bin1, &k_rem1);
+    block_pick<(int)HIST1>(layer_hist(hist, L, 1), state[j].k_rem0, sh, &bin1, &k_rem1);
     const uint32_t prefix = (state[j].b1 << digit_bits(1)) | bin1;            // 22 bits
     if (s == L.stile_begin && tid == 0) {
         state[j].p22 = prefix;
@@ -306,7 +337,7 @@ __global__ __launch_bounds__(BLOCK) void k_refine2(ResidualPtrs R, const float* 
         }
     }
     __syncthreads();
-    flush_hist<HIST2>(lh, hist + (size_t)j * HIST_STRIDE + hist_base(2));
+    flush_hist<HIST2>(lh, layer_hist(hist, L, 2));
 }
 
 // ---------------------------------------------------------------------------
@@ -340,7 +371,7 @@ __global__ __launch_bounds__(BLOCK) void k_count(ResidualPtrs R, const float* __
     } else {
         // third pick, redone by every workgroup of the layer: the exact k-th largest key
         uint32_t bin2, k_rem2;
-        block_pick<(int)HIST2>(hist + (size_t)j * HIST_STRIDE + hist_base(2), state[j].k_rem1, sh, &bin2, &k_rem2);
+        block_pick<(int)HIST2>(layer_hist(hist, L, 2), state[j].k_rem1, sh, &bin2, &k_rem2);
         thr = (state[j].p22 << digit_bits(2)) | bin2;
         if (s == L.stile_begin && tid == 0) {
             state[j].thr = thr;

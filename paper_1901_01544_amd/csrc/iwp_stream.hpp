@@ -202,7 +202,9 @@ __global__ __launch_bounds__(BLOCK) void k_leader_pass(WorkerPtrs P, const float
     if (first * TILE >= L.n) return;
     const uint32_t p = leader_of(leader, j, W);
     LeadCtx C = lead_ctx(lh, slot, L, state, j, stage_cnt, A);
-    leader_group(P.g[p], P.r[p], w, L, first, LG, eps, P.momentum, C, hist + (size_t)j * HIST_STRIDE);
+    // consecutive workgroups of a layer flush into different copies of its first-digit histogram
+    uint32_t* h0 = layer_hist(hist, L, 0) + (size_t)((first / LG) & (L.h0_copies - 1u)) * HIST0;
+    leader_group(P.g[p], P.r[p], w, L, first, LG, eps, P.momentum, C, h0);
 }
 
 // The other workers, after the leader's pairs are known: accumulate, and where the
