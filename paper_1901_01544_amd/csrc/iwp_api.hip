@@ -178,14 +178,21 @@ constexpr uint32_t FOLD_SCAN_MAX_STILES = 4096;
 
 int check_eps(float eps) { return (eps >= 0.0f && std::isfinite(eps)) ? IWP_OK : IWP_EINVAL; }
 
-int launch_init(const Workspace& ws, uint32_t n_layers, const iwp_threshold* hint, const DevLayer* row,
-                const DevLayer* sentinel, hipStream_t s) {
-    uint32_t grid = (uint32_t)std::min<uint64_t>((ws.hist_words + BLOCK - 1) / BLOCK, 4096);
-    if (grid == 0) grid = 1;
+// Sampling source of a call: the leaders' residuals and gradients (NULL entries allowed), or nothing.
+SampleSource sample_from(const WorkerPtrs& P, const float* w, const uint32_t* leader, uint32_t W, float eps) {
+    SampleSource S;
+    S.P = P; S.w = w; S.leader = leader; S.W = W; S.eps = eps; S.on = w ? 1u : 0u;
+    return S;
+}
+
+int launch_init(const Workspace& ws, uint32_t n_layers, const iwp_threshold* hint, const DevLayer* layers,
+                const DevLayer* row, const DevLayer* sentinel, const SampleSource& S, hipStream_t s) {
+    uint32_t zero_blocks = (uint32_t)std::min<uint64_t>((ws.hist_words + BLOCK - 1) / BLOCK, 4096);
+    if (zero_blocks == 0) zero_blocks = 1;
     DevLayer zero;
     memset(&zero, 0, sizeof zero);
-    IWP_LAUNCH("k_init", k_init, grid, s, ws.hist, ws.hist_words, ws.state, n_layers, hint,
-               row ? ws.single_table : nullptr, row ? *row : zero, sentinel ? *sentinel : zero);
+    IWP_LAUNCH("k_init", k_init, n_layers + zero_blocks, s, ws.hist, ws.hist_words, ws.state, n_layers, hint, layers,
+               row ? ws.single_table : nullptr, row ? *row : zero, sentinel ? *sentinel : zero, S);
     return IWP_OK;
 }
 
@@ -321,7 +328,9 @@ static int single_common(SingleOp op, const float* w, const float* g, float* r, 
     row.n = n; row.k = k; row.slot_cap = slot_cap_of(n, k);
     row.hist_begin = 0; row.h0_copies = h0_copies_of(n, k);
     sentinel.tile_begin = z.tiles; sentinel.stile_begin = z.stiles; sentinel.out_offset = k;
-    int rc = launch_init(ws, 1, nullptr, &row, &sentinel, s);
+    SampleSource S = sample_from(P, w, nullptr, 1u, eps);
+    if (op == OP_COMPACT || k == 0) S.on = 0;
+    int rc = launch_init(ws, 1, nullptr, nullptr, &row, &sentinel, S, s);
     if (rc) return rc;
     Table T{ws.single_table, 1, z.tiles, z.stiles, k, k > 0, z.stiles};
     if (op == OP_COMPACT) return run_compact_from(T, ws, R, w, eps, from_thr, idx_out, val_out, s);
@@ -541,7 +550,7 @@ static int compress_segmented_on(const iwp_plan* plan, const float* w, const flo
     if (rc) return rc;
     if (plan->z.tiles == 0) return IWP_OK;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    rc = launch_init(ws, plan->z.n_layers, thr_hint, nullptr, nullptr, s);
+    rc = launch_init(ws, plan->z.n_layers, thr_hint, plan->dev, nullptr, nullptr, sample_from(P, w, leader, W, eps), s);
     if (rc) return rc;
     Table T{plan->dev, plan->z.n_layers, plan->z.tiles, plan->z.stiles, plan->z.pairs, plan->any_k, plan->max_layer_stiles};
     if (T.any_k)
@@ -590,7 +599,7 @@ int iwp_step_segmented(const iwp_plan* plan, float* w, const float* const* g, fl
     if (rc) return rc;
     if (z.tiles == 0) return IWP_OK;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    rc = launch_init(ws, z.n_layers, thr_hint, nullptr, nullptr, s);
+    rc = launch_init(ws, z.n_layers, thr_hint, plan->dev, nullptr, nullptr, sample_from(P, w, leader, W, eps), s);
     if (rc) return rc;
     Table T{plan->dev, z.n_layers, z.tiles, z.stiles, z.pairs, plan->any_k, plan->max_layer_stiles};
     if (T.any_k) {
@@ -627,12 +636,12 @@ int select_threshold_segmented(const iwp_plan* plan, const float* w, const float
     if (rc) return rc;
     if (plan->z.tiles == 0 || !plan->any_k) return IWP_OK;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    rc = launch_init(ws, plan->z.n_layers, nullptr, nullptr, nullptr, s);
-    if (rc) return rc;
     WorkerPtrs P;
     memset(&P, 0, sizeof P);
     P.r[0] = const_cast<float*>(r);       // no gradient pointer: the residual is only read
     P.momentum = 1.0f;
+    rc = launch_init(ws, plan->z.n_layers, nullptr, plan->dev, nullptr, nullptr, sample_from(P, w, nullptr, 1u, eps), s);
+    if (rc) return rc;
     ResidualPtrs R;
     memset(&R, 0, sizeof R);
     R.r[0] = const_cast<float*>(r);

@@ -31,32 +31,121 @@
 
 namespace iwp {
 
-constexpr uint32_t DIRECT_ATOMICS_MAX = 64;        // up to this many histogram updates per tile go straight to global memory
+constexpr uint32_t DIRECT_ATOMICS_MAX = 8;         // up to this many histogram updates per tile go straight to global memory
+                                                   // (single scattered atomics run at a few per nanosecond device-wide,
+                                                   // a flush of neighbouring bins is far cheaper per update)
+constexpr uint32_t STAGE_GROUP = 16;               // tiles whose slots one workgroup of look 2 histograms when look 1 staged them
 
 // ---------------------------------------------------------------------------
 // Workspace initialisation with vector stores (a fill kernel rather than a memset
 // node, so the call sequence can be graph-captured): histograms to zero, layer
-// states reset (with the staging bin a threshold hint implies); for the
-// single-layer entry points also the one-row layer table.
+// states reset; for the single-layer entry points also the one-row layer table.
+//
+// The first n_layers workgroups each reset one layer's state and decide from which bin
+// look 1 copies candidates out (LayerState.stage_bin): from the caller's threshold hint if
+// there is one; otherwise from a sample of the layer -- 16 to 256 evenly spaced runs of 256
+// elements (the whole layer if it has no more), scored exactly as look 1 will score them,
+// histogrammed in LDS, and the bin of the sample's rank k * (sample size / n) taken as the
+// estimate.  Either way the guess only decides whether look 2 has to read the layer again;
+// it never changes a result.  The other workgroups clear the histograms.
 // ---------------------------------------------------------------------------
+struct SampleSource {      // what the sample is taken from; on == 0: no sampling
+    WorkerPtrs P;
+    const float* w;
+    const uint32_t* leader;
+    uint32_t W;
+    float eps;
+    uint32_t on;
+};
+
+constexpr uint32_t SAMPLE_RUN = WAVE * VEC;        // 256 consecutive elements, one quad per lane
+constexpr uint32_t SAMPLE_RUNS = 256;              // at most 65536 sampled elements per layer
+constexpr uint32_t SAMPLE_RANK = 256;              // rank of the estimated threshold inside the sample, about
+
+__device__ __forceinline__ uint32_t sample_stage_bin(const DevLayer& L, const float* gp, const float* rp,
+                                                     const float* __restrict__ w, float eps, float m, uint32_t* lh,
+                                                     uint32_t* sh) {
+    const uint32_t tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid >> 6;
+    const float* rl = rp + L.offset;
+    const float* gl = gp ? gp + L.offset : nullptr;
+    const float* wl = w + L.offset;
+    const bool vec = is_aligned16(rl) && is_aligned16(wl) && (!gp || is_aligned16(gl));
+    const uint32_t runs_total = (uint32_t)(((uint64_t)L.n + SAMPLE_RUN - 1) / SAMPLE_RUN);
+    // enough runs for the sample's rank to be about SAMPLE_RANK (a relative error of a few percent in the
+    // count, well inside the slack of one bin), at most SAMPLE_RUNS, at least 16
+    const uint64_t want = ((uint64_t)SAMPLE_RANK * L.n / L.k + SAMPLE_RUN - 1) / SAMPLE_RUN;
+    const uint32_t runs = min(runs_total, (uint32_t)min((uint64_t)SAMPLE_RUNS, max((uint64_t)16, want)));
+    for (uint32_t b = tid; b < HIST0; b += BLOCK) lh[b] = 0u;
+    __syncthreads();
+    constexpr uint32_t PER_ROUND = 8;                // runs a wavefront has in flight
+    for (uint32_t i0 = wave; i0 < runs; i0 += (BLOCK / WAVE) * PER_ROUND) {
+        float rv[PER_ROUND][4], gv[PER_ROUND][4], wv[PER_ROUND][4];
+        uint32_t e[PER_ROUND];
+#pragma unroll
+        for (uint32_t c = 0; c < PER_ROUND; ++c) {
+            const uint32_t i = i0 + c * (BLOCK / WAVE);
+            const uint64_t run = (uint64_t)i * runs_total / runs;
+            const uint64_t pos = run * SAMPLE_RUN + lane * VEC;
+            e[c] = (i < runs && pos < L.n) ? (uint32_t)pos : 0xFFFFFFFFu;
+            if (e[c] != 0xFFFFFFFFu) {
+                load_quad(rl, e[c], L.n, vec, rv[c]);
+                if (gp) load_quad(gl, e[c], L.n, vec, gv[c]);
+                load_quad(wl, e[c], L.n, vec, wv[c], 1.0f);
+            }
+        }
+#pragma unroll
+        for (uint32_t c = 0; c < PER_ROUND; ++c) {
+            if (e[c] == 0xFFFFFFFFu) continue;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (e[c] + q >= L.n) break;
+                const float v = gp ? accum(rv[c][q], gv[c][q], m) : rv[c][q];
+                atomicAdd(&lh[score_key(v, wv[c][q], eps) >> digit_shift(0)], 1u);
+            }
+        }
+    }
+    __syncthreads();
+    // every run but the layer's last is full, and the last is only sampled when all are
+    const uint64_t sampled = runs == runs_total ? (uint64_t)L.n : (uint64_t)runs * SAMPLE_RUN;
+    const uint32_t ks = (uint32_t)max((uint64_t)1, ((uint64_t)L.k * sampled + L.n - 1) / L.n);
+    uint32_t bin, k_rem;
+    block_pick<(int)HIST0>(lh, ks, sh, &bin, &k_rem);
+    return bin;
+}
+
 __global__ __launch_bounds__(BLOCK) void k_init(uint32_t* __restrict__ words, uint64_t n_words,
                                                 LayerState* __restrict__ state, uint32_t n_layers,
                                                 const iwp_threshold* __restrict__ hint,
-                                                DevLayer* __restrict__ single_table, DevLayer row, DevLayer sentinel) {
-    const uint64_t stride = (uint64_t)gridDim.x * BLOCK;
-    for (uint64_t i = (uint64_t)blockIdx.x * BLOCK + threadIdx.x; i < n_words; i += stride) words[i] = 0u;
-    for (uint64_t j = (uint64_t)blockIdx.x * BLOCK + threadIdx.x; j < n_layers; j += stride) {
+                                                const DevLayer* __restrict__ layers,
+                                                DevLayer* __restrict__ single_table, DevLayer row, DevLayer sentinel,
+                                                SampleSource S) {
+    __shared__ uint32_t lh[HIST0];
+    __shared__ uint32_t sh[BLOCK + 2];
+    if (blockIdx.x >= n_layers) {
+        const uint64_t stride = (uint64_t)(gridDim.x - n_layers) * BLOCK;
+        for (uint64_t i = (uint64_t)(blockIdx.x - n_layers) * BLOCK + threadIdx.x; i < n_words; i += stride) words[i] = 0u;
+        if (single_table && blockIdx.x == n_layers && threadIdx.x == 0) {
+            single_table[0] = row;
+            single_table[1] = sentinel;
+        }
+        return;
+    }
+    const uint32_t j = blockIdx.x;
+    const DevLayer L = single_table ? row : layers[j];       // the one-row table is only being written by this launch
+    // one bin of slack below the hinted / estimated threshold bin (a bin is 1/16 octave); a threshold in
+    // bin 0 or 1 (among zero scores): look 1 stages nothing
+    uint32_t guess = 0;
+    if (hint) {
+        guess = (hint[j].key & 0x7fffffffu) >> digit_shift(0);
+    } else if (S.on && L.k > 0 && L.n > 0) {                 // uniform over the workgroup
+        const uint32_t p = leader_of(S.leader, j, S.W);
+        guess = sample_stage_bin(L, S.P.g[p], S.P.r[p], S.w, S.eps, S.P.momentum, lh, sh);
+    }
+    if (threadIdx.x == 0) {
         LayerState st;
         st.b1 = 0; st.k_rem0 = 0; st.p22 = 0; st.k_rem1 = 0; st.thr = 0; st.n_eq_take = 0; st.prestaged = 0;
-        // one bin of slack below the hinted threshold bin (a bin is 1/16 octave); a hint in bin 0
-        // (threshold among zero scores) or no hint: look 1 stages nothing
-        const uint32_t hb = hint ? ((hint[j].key & 0x7fffffffu) >> digit_shift(0)) : 0u;
-        st.stage_bin = hb >= 2u ? hb - 1u : NO_STAGE_BIN;
+        st.stage_bin = guess >= 2u ? guess - 1u : NO_STAGE_BIN;
         state[j] = st;
-    }
-    if (single_table && blockIdx.x == 0 && threadIdx.x == 0) {
-        single_table[0] = row;
-        single_table[1] = sentinel;
     }
 }
 
@@ -187,27 +276,54 @@ __global__ __launch_bounds__(BLOCK) void k_stage(ResidualPtrs R, const float* __
     uint32_t* h1 = layer_hist(hist, L, 1);
 
     if (prestaged) {
-        const uint32_t cnt = stage_cnt[t];
-        if (cnt != RAW_TILE) {
-            // the slot already holds everything from a bin <= b1: histogram from it
-            const bool use_lds = cnt > 8 * DIRECT_ATOMICS_MAX;                 // uniform
-            if (use_lds) {
-                for (uint32_t b = tid; b < HIST1; b += BLOCK) lh[b] = 0u;
-                __syncthreads();
+        // The slots already hold everything from a bin <= b1: the second digit's histogram comes from them.
+        // One workgroup does that for STAGE_GROUP tiles, in LDS, and flushes once: in steady state the
+        // threshold's bin holds about as many elements as are kept, and that many single atomics per tile
+        // (or one flush per tile) would queue up on the histogram's few cache lines.
+        const uint32_t cnt_own = stage_cnt[t];
+        if (lt % STAGE_GROUP == 0) {
+            const uint32_t lane = tid & (WAVE - 1), wave = tid >> 6;
+            const uint32_t ntiles = (L.n + TILE - 1) / TILE;
+            const uint32_t last = min(lt + STAGE_GROUP, ntiles);
+            for (uint32_t b = tid; b < HIST1; b += BLOCK) lh[b] = 0u;
+            __syncthreads();
+            // a wavefront takes every fourth tile of the group; the counts and the first 256 entries of all
+            // its tiles are requested before any of them is used
+            constexpr uint32_t MINE = STAGE_GROUP / (BLOCK / WAVE);
+            uint32_t cnt[MINE];
+            uint32_t key[MINE][4];
+#pragma unroll
+            for (uint32_t m = 0; m < MINE; ++m) {
+                const uint32_t tt = lt + wave + m * (BLOCK / WAVE);
+                cnt[m] = tt < last ? stage_cnt[L.tile_begin + tt] : 0u;
             }
-            for (uint32_t e = tid; e < cnt; e += BLOCK) {
-                const uint32_t key = A.key[sb + e];
-                if ((key >> digit_shift(0)) == b1) {
-                    const uint32_t d1 = (key >> digit_shift(1)) & (HIST1 - 1);
-                    if (use_lds) atomicAdd(&lh[d1], 1u); else atomicAdd(&h1[d1], 1u);
+#pragma unroll
+            for (uint32_t m = 0; m < MINE; ++m) {
+                if (cnt[m] == RAW_TILE) cnt[m] = 0u;       // re-read by the tile's own workgroup below
+                const uint64_t sbb = L.slot_begin + (uint64_t)(lt + wave + m * (BLOCK / WAVE)) * L.slot_cap;
+#pragma unroll
+                for (uint32_t q = 0; q < 4; ++q) {
+                    const uint32_t e = q * WAVE + lane;
+                    key[m][q] = e < cnt[m] ? A.key[sbb + e] : NOT_AN_ELEMENT;
                 }
             }
-            if (use_lds) {
-                __syncthreads();
-                flush_hist<HIST1>(lh, h1);
+#pragma unroll
+            for (uint32_t m = 0; m < MINE; ++m) {
+#pragma unroll
+                for (uint32_t q = 0; q < 4; ++q)
+                    if (key[m][q] != NOT_AN_ELEMENT && (key[m][q] >> digit_shift(0)) == b1)
+                        atomicAdd(&lh[(key[m][q] >> digit_shift(1)) & (HIST1 - 1)], 1u);
+                const uint64_t sbb = L.slot_begin + (uint64_t)(lt + wave + m * (BLOCK / WAVE)) * L.slot_cap;
+                for (uint32_t e = 4 * WAVE + lane; e < cnt[m]; e += WAVE) {        // fuller slots: the rest
+                    const uint32_t k2 = A.key[sbb + e];
+                    if ((k2 >> digit_shift(0)) == b1) atomicAdd(&lh[(k2 >> digit_shift(1)) & (HIST1 - 1)], 1u);
+                }
             }
-            return;
+            __syncthreads();
+            flush_hist<HIST1>(lh, h1);
         }
+        if (cnt_own != RAW_TILE) return;                   // uniform
+        __syncthreads();                                   // lh is used again below
     }
 
     const float* rl = R.r[leader_of(leader, j, W)] + L.offset;
