@@ -227,8 +227,8 @@ int run_select(const Table& T, const Workspace& ws, const ResidualPtrs& R, const
                iwp_threshold* thr_out, hipStream_t s) {
     if (!T.any_k || T.tiles == 0) return IWP_OK;
     IWP_LAUNCH("k_first_pick", k_first_pick, T.n_layers, s, T.layers, ws.hist, ws.state);
-    IWP_LAUNCH("k_stage", k_stage, T.tiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.hist,
-               ws.stage, ws.A);
+    IWP_LAUNCH("k_stage", k_stage, std::min<uint32_t>(T.tiles, STAGE_MAX_GRID), s, R, w, T.layers, T.n_layers, T.tiles,
+               leader, W, eps, ws.state, ws.hist, ws.stage, ws.A);
     IWP_LAUNCH("k_refine2", k_refine2, T.stiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.stage,
                ws.A, ws.hist);
     if (stop == STOP_AT_THRESHOLD) {

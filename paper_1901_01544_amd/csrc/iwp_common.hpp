@@ -59,6 +59,12 @@ constexpr uint32_t FLUSHES_PER_COPY = 512;                 // look-1 workgroups 
 __host__ __device__ constexpr uint32_t layer_hist_words(uint32_t copies) { return copies * HIST0 + HIST1 + HIST2; }
 
 constexpr uint32_t RAW_TILE = 0xFFFFFFFFu;        // stage count of a tile whose candidates did not fit its slot
+constexpr uint32_t RESTAGED = 0x40000000u;        // flag on a stage count: look 2 filled this slot again (from b1) after look 1
+                                                  // had overflowed it; look 2's reader of look-1 slots skips such tiles
+// Entries in a tile's slot for the passes after look 2 (RAW_TILE stays RAW_TILE).
+__device__ __forceinline__ uint32_t staged_entries(uint32_t stage_count) {
+    return stage_count == RAW_TILE ? RAW_TILE : stage_count & ~RESTAGED;
+}
 constexpr uint32_t NO_STAGE_BIN = 0xFFFFFFFFu;    // LayerState.stage_bin: look 1 stages nothing for this layer
 constexpr uint32_t NOT_AN_ELEMENT = 0xFFFFFFFFu;  // key slot of a lane position past the layer's end
 

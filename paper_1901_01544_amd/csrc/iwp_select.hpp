@@ -31,10 +31,6 @@
 
 namespace iwp {
 
-constexpr uint32_t DIRECT_ATOMICS_MAX = 8;         // up to this many histogram updates per tile go straight to global memory
-                                                   // (single scattered atomics run at a few per nanosecond device-wide,
-                                                   // a flush of neighbouring bins is far cheaper per update)
-constexpr uint32_t STAGE_GROUP = 16;               // tiles whose slots one workgroup of look 2 histograms when look 1 staged them
 
 // ---------------------------------------------------------------------------
 // Workspace initialisation with vector stores (a fill kernel rather than a memset
@@ -250,45 +246,52 @@ __device__ __forceinline__ void flush_hist(const uint32_t* lh, uint32_t* __restr
 }
 
 // ---------------------------------------------------------------------------
-// Look 2, one workgroup per tile of the leader's residual: copy the elements of the
-// tile whose top digit is >= b1 into the tile's slot (in index order) and histogram
-// the second digit of those inside b1.  A tile with more candidates than its slot
-// holds is marked RAW; its second-digit counts still go into the histogram.  If
-// look 1 already filled the slot from a bin <= b1, only the slot is read.
+// Look 2: the second digit's histogram of the elements inside b1, and staged candidates
+// for the passes that follow.  The unit of work is a tile; a workgroup takes the tiles
+// blockIdx.x, blockIdx.x + gridDim.x, ... (the grid is capped: a launch of hundreds of
+// thousands of workgroups that mostly have nothing to do costs more than their work).
+//  * Look 1 already filled the layer's slots from a bin <= b1 (threshold hint or sample):
+//    only the slots are read, by the first tile's unit of every STAGE_GROUP tiles, into one
+//    LDS histogram that is flushed once.  In the steady state of a training run the
+//    threshold's bin holds about as many elements as are kept; that many single atomics per
+//    tile, or one flush per tile, would queue up on the histogram's few cache lines.  A tile
+//    whose candidates overflowed its slot in look 1 (RAW) is read again from r and w by its
+//    own unit, as below; its new count carries the RESTAGED flag, so the reader of look-1
+//    slots leaves it alone whether it sees the old or the new count.
+//  * Otherwise the tile is read again from r and w: the elements whose top digit is >= b1
+//    are copied into the tile's slot in index order (a tile with more candidates than its
+//    slot holds is marked RAW), those inside b1 go into the histogram.
 // ---------------------------------------------------------------------------
+constexpr uint32_t STAGE_GROUP = 16;               // tiles whose slots one unit histograms
+constexpr uint32_t STAGE_MAX_GRID = 32768;
+
 __global__ __launch_bounds__(BLOCK) void k_stage(ResidualPtrs R, const float* __restrict__ w,
                                                  const DevLayer* __restrict__ layers, uint32_t n_layers,
-                                                 const uint32_t* __restrict__ leader, uint32_t W, float eps,
-                                                 const LayerState* __restrict__ state, uint32_t* __restrict__ hist,
-                                                 uint32_t* __restrict__ stage_cnt, StageArrays A) {
+                                                 uint32_t tiles, const uint32_t* __restrict__ leader, uint32_t W,
+                                                 float eps, const LayerState* __restrict__ state,
+                                                 uint32_t* __restrict__ hist, uint32_t* __restrict__ stage_cnt,
+                                                 StageArrays A) {
     __shared__ uint32_t lh[HIST1];
-    __shared__ uint32_t slot[2][4];
-    const uint32_t tid = threadIdx.x;
-    const uint32_t t = blockIdx.x;
-    const uint32_t j = find_layer<false>(layers, n_layers, t);
-    const DevLayer L = layers[j];
-    if (L.k == 0) return;
-    const uint32_t lt = t - L.tile_begin;
-    const uint32_t b1 = state[j].b1;
-    const bool prestaged = state[j].prestaged != 0;
-    const uint32_t base = lt * TILE;
-    const uint64_t sb = L.slot_begin + (uint64_t)lt * L.slot_cap;
-    uint32_t* h1 = layer_hist(hist, L, 1);
+    __shared__ uint32_t slot[4];
+    const uint32_t tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid >> 6;
+    for (uint32_t t = blockIdx.x; t < tiles; t += gridDim.x) {
+        const uint32_t j = find_layer<false>(layers, n_layers, t);
+        const DevLayer L = layers[j];
+        if (L.k == 0) continue;
+        const uint32_t b1 = state[j].b1;
+        const bool prestaged = state[j].prestaged != 0;
+        const uint32_t lt = t - L.tile_begin;
+        const bool do_slots = prestaged && lt % STAGE_GROUP == 0;
+        const bool raw = prestaged && stage_cnt[t] == RAW_TILE;
+        if (prestaged && !do_slots && !raw) continue;      // uniform
+        for (uint32_t b = tid; b < HIST1; b += BLOCK) lh[b] = 0u;
+        __syncthreads();
 
-    if (prestaged) {
-        // The slots already hold everything from a bin <= b1: the second digit's histogram comes from them.
-        // One workgroup does that for STAGE_GROUP tiles, in LDS, and flushes once: in steady state the
-        // threshold's bin holds about as many elements as are kept, and that many single atomics per tile
-        // (or one flush per tile) would queue up on the histogram's few cache lines.
-        const uint32_t cnt_own = stage_cnt[t];
-        if (lt % STAGE_GROUP == 0) {
-            const uint32_t lane = tid & (WAVE - 1), wave = tid >> 6;
-            const uint32_t ntiles = (L.n + TILE - 1) / TILE;
-            const uint32_t last = min(lt + STAGE_GROUP, ntiles);
-            for (uint32_t b = tid; b < HIST1; b += BLOCK) lh[b] = 0u;
-            __syncthreads();
+        if (do_slots) {
             // a wavefront takes every fourth tile of the group; the counts and the first 256 entries of all
             // its tiles are requested before any of them is used
+            const uint32_t ntiles = (L.n + TILE - 1) / TILE;
+            const uint32_t last = min(lt + STAGE_GROUP, ntiles);
             constexpr uint32_t MINE = STAGE_GROUP / (BLOCK / WAVE);
             uint32_t cnt[MINE];
             uint32_t key[MINE][4];
@@ -296,10 +299,11 @@ __global__ __launch_bounds__(BLOCK) void k_stage(ResidualPtrs R, const float* __
             for (uint32_t m = 0; m < MINE; ++m) {
                 const uint32_t tt = lt + wave + m * (BLOCK / WAVE);
                 cnt[m] = tt < last ? stage_cnt[L.tile_begin + tt] : 0u;
+                if (cnt[m] & RESTAGED) cnt[m] = 0u;        // overflowed in look 1 (RAW, or already filled again by
+                                                           // the tile's own unit, which also histograms it)
             }
 #pragma unroll
             for (uint32_t m = 0; m < MINE; ++m) {
-                if (cnt[m] == RAW_TILE) cnt[m] = 0u;       // re-read by the tile's own workgroup below
                 const uint64_t sbb = L.slot_begin + (uint64_t)(lt + wave + m * (BLOCK / WAVE)) * L.slot_cap;
 #pragma unroll
                 for (uint32_t q = 0; q < 4; ++q) {
@@ -314,84 +318,64 @@ __global__ __launch_bounds__(BLOCK) void k_stage(ResidualPtrs R, const float* __
                     if (key[m][q] != NOT_AN_ELEMENT && (key[m][q] >> digit_shift(0)) == b1)
                         atomicAdd(&lh[(key[m][q] >> digit_shift(1)) & (HIST1 - 1)], 1u);
                 const uint64_t sbb = L.slot_begin + (uint64_t)(lt + wave + m * (BLOCK / WAVE)) * L.slot_cap;
-                for (uint32_t e = 4 * WAVE + lane; e < cnt[m]; e += WAVE) {        // fuller slots: the rest
+                for (uint32_t e = 4 * WAVE + lane; e < cnt[m]; e += WAVE) {    // fuller slots: the rest
                     const uint32_t k2 = A.key[sbb + e];
                     if ((k2 >> digit_shift(0)) == b1) atomicAdd(&lh[(k2 >> digit_shift(1)) & (HIST1 - 1)], 1u);
                 }
             }
-            __syncthreads();
-            flush_hist<HIST1>(lh, h1);
         }
-        if (cnt_own != RAW_TILE) return;                   // uniform
-        __syncthreads();                                   // lh is used again below
-    }
 
-    const float* rl = R.r[leader_of(leader, j, W)] + L.offset;
-    const float* wl = w + L.offset;
-    const bool vec = is_aligned16(rl) && is_aligned16(wl);
-    uint32_t key[CHUNKS_PER_TILE][4];
-    float val[CHUNKS_PER_TILE][4];
-    float wgt[CHUNKS_PER_TILE][4];
-    const bool full = vec && base + TILE <= L.n;
-    if (full) {
+        if (!prestaged || raw) {                           // uniform: this tile is read again
+            const float* rl = R.r[leader_of(leader, j, W)] + L.offset;
+            const float* wl = w + L.offset;
+            const bool vec = is_aligned16(rl) && is_aligned16(wl);
+            const uint32_t base = lt * TILE;
+            uint32_t key[CHUNKS_PER_TILE][4];
+            float val[CHUNKS_PER_TILE][4];
+            float wgt[CHUNKS_PER_TILE][4];
+            const bool full = vec && base + TILE <= L.n;
+            if (full) {
 #pragma unroll
-        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
-            const uint32_t i = base + u * CHUNK + tid * VEC;
-            const v4f a = load_v4<true>(rl + i);
-            const v4f b = load_v4<true>(wl + i);
-            val[u][0] = a.x; val[u][1] = a.y; val[u][2] = a.z; val[u][3] = a.w;
-            wgt[u][0] = b.x; wgt[u][1] = b.y; wgt[u][2] = b.z; wgt[u][3] = b.w;
-        }
-    } else {
-#pragma unroll
-        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
-            const uint32_t i = base + u * CHUNK + tid * VEC;
-            if (i < L.n) {
-                load_quad(rl, i, L.n, vec, val[u]);
-                load_quad(wl, i, L.n, vec, wgt[u], 1.0f);
-            } else {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) { val[u][q] = 0.0f; wgt[u][q] = 1.0f; }
-            }
-        }
-    }
-    uint32_t maybes = 0;                      // this lane's elements inside b1
-#pragma unroll
-    for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
-        const uint32_t i = base + u * CHUNK + tid * VEC;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            if (full || i + q < L.n) {
-                key[u][q] = score_key(val[u][q], wgt[u][q], eps);
-                maybes += (key[u][q] >> digit_shift(0)) == b1 ? 1u : 0u;
-            } else {
-                key[u][q] = NOT_AN_ELEMENT;
-            }
-        }
-    }
-    const uint32_t cnt = stage_tile(key, val, base, b1, L.slot_cap, sb, A, slot[0]);
-    if (tid == 0) stage_cnt[t] = cnt;
-    uint32_t n_maybe;
-    (void)block_exclusive_scan(maybes, slot[1], &n_maybe);
-    if (n_maybe == 0) return;                              // uniform
-    const bool use_lds = n_maybe > DIRECT_ATOMICS_MAX;     // uniform
-    if (use_lds) {
-        for (uint32_t b = tid; b < HIST1; b += BLOCK) lh[b] = 0u;
-        __syncthreads();
-    }
-    if (maybes) {
-#pragma unroll
-        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u)
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                if (key[u][q] != NOT_AN_ELEMENT && (key[u][q] >> digit_shift(0)) == b1) {
-                    const uint32_t d1 = (key[u][q] >> digit_shift(1)) & (HIST1 - 1);
-                    if (use_lds) atomicAdd(&lh[d1], 1u); else atomicAdd(&h1[d1], 1u);
+                for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+                    const uint32_t i = base + u * CHUNK + tid * VEC;
+                    const v4f a = load_v4<true>(rl + i);
+                    const v4f b = load_v4<true>(wl + i);
+                    val[u][0] = a.x; val[u][1] = a.y; val[u][2] = a.z; val[u][3] = a.w;
+                    wgt[u][0] = b.x; wgt[u][1] = b.y; wgt[u][2] = b.z; wgt[u][3] = b.w;
                 }
-    }
-    if (use_lds) {
+            } else {
+#pragma unroll
+                for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+                    const uint32_t i = base + u * CHUNK + tid * VEC;
+                    if (i < L.n) {
+                        load_quad(rl, i, L.n, vec, val[u]);
+                        load_quad(wl, i, L.n, vec, wgt[u], 1.0f);
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) { val[u][q] = 0.0f; wgt[u][q] = 1.0f; }
+                    }
+                }
+            }
+#pragma unroll
+            for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+                const uint32_t i = base + u * CHUNK + tid * VEC;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (full || i + q < L.n) {
+                        key[u][q] = score_key(val[u][q], wgt[u][q], eps);
+                        if ((key[u][q] >> digit_shift(0)) == b1)
+                            atomicAdd(&lh[(key[u][q] >> digit_shift(1)) & (HIST1 - 1)], 1u);
+                    } else {
+                        key[u][q] = NOT_AN_ELEMENT;
+                    }
+                }
+            }
+            const uint32_t cnt = stage_tile(key, val, base, b1, L.slot_cap, L.slot_begin + (uint64_t)lt * L.slot_cap, A, slot);
+            if (tid == 0) stage_cnt[t] = (prestaged && cnt != RAW_TILE) ? (cnt | RESTAGED) : cnt;
+        }
         __syncthreads();
-        flush_hist<HIST1>(lh, h1);
+        flush_hist<HIST1>(lh, layer_hist(hist, L, 1));
+        __syncthreads();                                   // the next unit clears lh
     }
 }
 
@@ -430,7 +414,7 @@ __global__ __launch_bounds__(BLOCK) void k_refine2(ResidualPtrs R, const float* 
     for (uint32_t b = tid; b < HIST2; b += BLOCK) lh[b] = 0u;
     __syncthreads();
     for (uint32_t tl = 0; tl < nt; ++tl) {
-        const uint32_t cnt = stage_cnt[L.tile_begin + lt0 + tl];
+        const uint32_t cnt = staged_entries(stage_cnt[L.tile_begin + lt0 + tl]);
         if (cnt != RAW_TILE) {
             const uint64_t sb = L.slot_begin + (uint64_t)(lt0 + tl) * L.slot_cap;
             for (uint32_t e = tid; e < cnt; e += BLOCK) {
@@ -506,7 +490,7 @@ __global__ __launch_bounds__(BLOCK) void k_count(ResidualPtrs R, const float* __
     const float* wl = w + L.offset;
     // each wavefront takes tiles of its own (no workgroup-wide step until the end)
     for (uint32_t tl = wave; tl < nt; tl += BLOCK / WAVE) {
-        const uint32_t cnt = all_raw ? RAW_TILE : stage_cnt[L.tile_begin + lt0 + tl];
+        const uint32_t cnt = all_raw ? RAW_TILE : staged_entries(stage_cnt[L.tile_begin + lt0 + tl]);
         uint32_t gt = 0, eq = 0;
         if (cnt != RAW_TILE) {
             const uint64_t sb = L.slot_begin + (uint64_t)(lt0 + tl) * L.slot_cap;
@@ -649,7 +633,7 @@ __global__ __launch_bounds__(BLOCK) void k_write(ResidualPtrs R, const float* __
     float* vo = val_out + L.out_offset;
     float* go = FUSED ? gathered + (size_t)lead * K + L.out_offset : nullptr;
     if (lane == 0) tile_out[t] = out_base;
-    const uint32_t cnt = all_raw ? RAW_TILE : stage_cnt[t];
+    const uint32_t cnt = all_raw ? RAW_TILE : staged_entries(stage_cnt[t]);
 
     if (cnt != RAW_TILE) {
         if (cnt == 0) return;
