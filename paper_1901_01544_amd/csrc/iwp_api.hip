@@ -227,16 +227,19 @@ int run_select(const Table& T, const Workspace& ws, const ResidualPtrs& R, const
                iwp_threshold* thr_out, hipStream_t s) {
     if (!T.any_k || T.tiles == 0) return IWP_OK;
     IWP_LAUNCH("k_first_pick", k_first_pick, T.n_layers, s, T.layers, ws.hist, ws.state);
-    IWP_LAUNCH("k_stage", k_stage, std::min<uint32_t>(T.tiles, STAGE_MAX_GRID), s, R, w, T.layers, T.n_layers, T.tiles,
+    // consecutive tiles per workgroup, at most 64 of them (their look-1 counts are fetched one per lane)
+    const uint32_t stage_grid = std::max<uint32_t>(std::min<uint32_t>(T.tiles, STAGE_MAX_GRID), (T.tiles + WAVE - 1) / WAVE);
+    IWP_LAUNCH("k_stage", k_stage, stage_grid, s, R, w, T.layers, T.n_layers, T.tiles,
                leader, W, eps, ws.state, ws.hist, ws.stage, ws.A);
-    IWP_LAUNCH("k_refine2", k_refine2, T.stiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.stage,
-               ws.A, ws.hist);
+    const uint32_t stile_grid = std::min<uint32_t>(T.stiles, STILE_MAX_GRID);
+    IWP_LAUNCH("k_refine2", k_refine2, stile_grid, s, R, w, T.layers, T.n_layers, T.stiles, leader, W, eps, ws.state,
+               ws.stage, ws.A, ws.hist);
     if (stop == STOP_AT_THRESHOLD) {
         IWP_LAUNCH("k_final_pick", k_final_pick, T.n_layers, s, T.layers, ws.hist, ws.state, thr_out);
         return IWP_OK;
     }
-    IWP_LAUNCH("k_count", k_count<false>, T.stiles, s, R, w, T.layers, T.n_layers, leader, W, eps, ws.state, ws.hist,
-               thr_out, ws.stage, ws.A, ws.tile_counts, ws.stile_counts);
+    IWP_LAUNCH("k_count", k_count<false>, stile_grid, s, R, w, T.layers, T.n_layers, T.stiles, leader, W, eps, ws.state,
+               ws.hist, thr_out, ws.stage, ws.A, ws.tile_counts, ws.stile_counts);
     if (fused) return launch_write<true>(T, ws, R, w, leader, W, eps, false, idx_out, val_out, s);
     return launch_write<false>(T, ws, R, w, leader, W, eps, false, idx_out, val_out, s);
 }
@@ -247,8 +250,8 @@ int run_compact_from(const Table& T, const Workspace& ws, const ResidualPtrs& R,
     if (!T.any_k || T.tiles == 0) return IWP_OK;
     IWP_LAUNCH("k_load_thresholds", k_load_thresholds, (T.n_layers + BLOCK - 1) / BLOCK, s, T.layers, T.n_layers, thr,
                ws.state);
-    IWP_LAUNCH("k_count", k_count<true>, T.stiles, s, R, w, T.layers, T.n_layers, nullptr, 1u, eps, ws.state, ws.hist,
-               nullptr, ws.stage, ws.A, ws.tile_counts, ws.stile_counts);
+    IWP_LAUNCH("k_count", k_count<true>, std::min<uint32_t>(T.stiles, STILE_MAX_GRID), s, R, w, T.layers, T.n_layers,
+               T.stiles, nullptr, 1u, eps, ws.state, ws.hist, nullptr, ws.stage, ws.A, ws.tile_counts, ws.stile_counts);
     return launch_write<false>(T, ws, R, w, nullptr, 1u, eps, true, idx_out, val_out, s);
 }
 

@@ -36,11 +36,12 @@ constexpr uint32_t CHUNKS_PER_TILE = 4;
 constexpr uint32_t TILE = CHUNK * CHUNKS_PER_TILE; // 4096 elements: the streaming unit (measured best on MI355X)
 constexpr uint32_t GROUP = 8;                      // tiles per super-tile
 #ifndef IWP_LGROUP
-#define IWP_LGROUP 2                               // build-time tuning knob: -DIWP_LGROUP=1|2|4|8
+#define IWP_LGROUP 1                               // build-time tuning knob: -DIWP_LGROUP=1|2|4|8
 #endif
-constexpr uint32_t LGROUP = IWP_LGROUP;            // tiles that share one LDS histogram in look 1 (divides GROUP;
-                                                   // 2 and 4 measure alike on large layers, 2 is ahead by about
-                                                   // 1 % on sets of many small layers; 1 and 8 are behind)
+constexpr uint32_t LGROUP = IWP_LGROUP;            // tiles that share one LDS histogram in look 1 (divides GROUP).
+                                                   // With the first-digit histogram in several copies 1, 2 and 4 measure
+                                                   // alike on the model-shaped sets; on a 10^9-element layer 1 streams
+                                                   // about 6 % faster than 2
 constexpr uint32_t STILE = TILE * GROUP;           // 32768 elements: unit of the leader-side passes
 constexpr uint32_t TILE_WORDS = TILE / 32;         // words of a one-bit-per-element tile bitmap
 

@@ -263,7 +263,7 @@ __device__ __forceinline__ void flush_hist(const uint32_t* lh, uint32_t* __restr
 //    slot holds is marked RAW), those inside b1 go into the histogram.
 // ---------------------------------------------------------------------------
 constexpr uint32_t STAGE_GROUP = 16;               // tiles whose slots one unit histograms
-constexpr uint32_t STAGE_MAX_GRID = 32768;
+constexpr uint32_t STAGE_MAX_GRID = 32768;         // with at most 2^20 tiles per table: at most 32 tiles per workgroup
 
 __global__ __launch_bounds__(BLOCK) void k_stage(ResidualPtrs R, const float* __restrict__ w,
                                                  const DevLayer* __restrict__ layers, uint32_t n_layers,
@@ -274,15 +274,27 @@ __global__ __launch_bounds__(BLOCK) void k_stage(ResidualPtrs R, const float* __
     __shared__ uint32_t lh[HIST1];
     __shared__ uint32_t slot[4];
     const uint32_t tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid >> 6;
-    for (uint32_t t = blockIdx.x; t < tiles; t += gridDim.x) {
+    // the workgroup's tiles are consecutive (at most 64: the host sizes the grid accordingly); their counts
+    // from look 1 are fetched in one go, and a layer's row and state only when the layer changes, so that a
+    // tile with nothing to do costs no memory access at all
+    const uint32_t per = (tiles + gridDim.x - 1) / gridDim.x;
+    const uint32_t t0 = blockIdx.x * per, t1 = min(t0 + per, tiles);
+    const uint32_t my_cnt = (t0 + lane < t1) ? stage_cnt[t0 + lane] : 0u;
+    uint32_t cur_j = 0xFFFFFFFFu, b1 = 0;
+    bool prestaged = false;
+    DevLayer L;
+    for (uint32_t t = t0; t < t1; ++t) {
         const uint32_t j = find_layer<false>(layers, n_layers, t);
-        const DevLayer L = layers[j];
+        if (j != cur_j) {
+            L = layers[j];
+            b1 = state[j].b1;
+            prestaged = state[j].prestaged != 0;
+            cur_j = j;
+        }
         if (L.k == 0) continue;
-        const uint32_t b1 = state[j].b1;
-        const bool prestaged = state[j].prestaged != 0;
         const uint32_t lt = t - L.tile_begin;
         const bool do_slots = prestaged && lt % STAGE_GROUP == 0;
-        const bool raw = prestaged && stage_cnt[t] == RAW_TILE;
+        const bool raw = prestaged && __shfl(my_cnt, (int)(t - t0), WAVE) == RAW_TILE;
         if (prestaged && !do_slots && !raw) continue;      // uniform
         for (uint32_t b = tid; b < HIST1; b += BLOCK) lh[b] = 0u;
         __syncthreads();
@@ -384,60 +396,106 @@ __global__ __launch_bounds__(BLOCK) void k_stage(ResidualPtrs R, const float* __
 // (the prologue's pick appended to b1), taken from the tile slots (or from r, w for RAW
 // tiles).  One workgroup per super-tile.
 // ---------------------------------------------------------------------------
+constexpr uint32_t STILE_MAX_GRID = 8192;          // k_refine2 / k_count: beyond this many super-tiles a workgroup takes
+                                                   // several consecutive ones (one pick, one flush for all of them)
+
 __global__ __launch_bounds__(BLOCK) void k_refine2(ResidualPtrs R, const float* __restrict__ w,
                                                    const DevLayer* __restrict__ layers, uint32_t n_layers,
-                                                   const uint32_t* __restrict__ leader, uint32_t W, float eps,
-                                                   LayerState* __restrict__ state,
+                                                   uint32_t stiles, const uint32_t* __restrict__ leader, uint32_t W,
+                                                   float eps, LayerState* __restrict__ state,
                                                    const uint32_t* __restrict__ stage_cnt, StageArrays A,
                                                    uint32_t* __restrict__ hist) {
     __shared__ uint32_t lh[HIST2];
     __shared__ uint32_t sh[BLOCK + 2];
-    const uint32_t tid = threadIdx.x;
-    const uint32_t s = blockIdx.x;
-    const uint32_t j = find_layer<true>(layers, n_layers, s);
-    const DevLayer L = layers[j];
-    if (L.k == 0) return;
-    // second pick, redone by every workgroup of the layer, from the finished second-digit histogram
-    uint32_t bin1, k_rem1;
-    block_pick<(int)HIST1>(layer_hist(hist, L, 1), state[j].k_rem0, sh, &bin1, &k_rem1);
-    const uint32_t prefix = (state[j].b1 << digit_bits(1)) | bin1;            // 22 bits
-    if (s == L.stile_begin && tid == 0) {
-        state[j].p22 = prefix;
-        state[j].k_rem1 = k_rem1;
-    }
-    const uint32_t ntiles = (L.n + TILE - 1) / TILE;
-    const uint32_t lt0 = (s - L.stile_begin) * GROUP;
-    const uint32_t nt = min(GROUP, ntiles - lt0);
-    const float* rl = R.r[leader_of(leader, j, W)] + L.offset;
-    const float* wl = w + L.offset;
-    const bool vec = is_aligned16(rl) && is_aligned16(wl);
-    for (uint32_t b = tid; b < HIST2; b += BLOCK) lh[b] = 0u;
-    __syncthreads();
-    for (uint32_t tl = 0; tl < nt; ++tl) {
-        const uint32_t cnt = staged_entries(stage_cnt[L.tile_begin + lt0 + tl]);
-        if (cnt != RAW_TILE) {
-            const uint64_t sb = L.slot_begin + (uint64_t)(lt0 + tl) * L.slot_cap;
-            for (uint32_t e = tid; e < cnt; e += BLOCK) {
-                const uint32_t key = A.key[sb + e];
-                if ((key >> digit_shift(1)) == prefix) atomicAdd(&lh[key & (HIST2 - 1)], 1u);
+    const uint32_t tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid >> 6;
+    const uint32_t per = (stiles + gridDim.x - 1) / gridDim.x;
+    const uint32_t s0 = blockIdx.x * per, s1 = min(s0 + per, stiles);
+    uint32_t cur_j = 0xFFFFFFFFu, prefix = 0;
+    bool filled = false;                                   // lh holds counts of layer cur_j
+    DevLayer L;
+    for (uint32_t s = s0; s < s1; ++s) {
+        const uint32_t j = find_layer<true>(layers, n_layers, s);
+        if (j != cur_j) {
+            if (filled) {
+                __syncthreads();
+                flush_hist<HIST2>(lh, layer_hist(hist, L, 2));
+                filled = false;
             }
-        } else {
-            for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
-                const uint32_t i = (lt0 + tl) * TILE + u * CHUNK + tid * VEC;
-                if (i >= L.n) break;
-                float rv[4], wv[4];
-                load_quad(rl, i, L.n, vec, rv);
-                load_quad(wl, i, L.n, vec, wv, 1.0f);
+            L = layers[j];
+            cur_j = j;
+            if (L.k == 0) continue;
+            // second pick, redone by every workgroup of the layer, from the finished second-digit histogram
+            uint32_t bin1, k_rem1;
+            block_pick<(int)HIST1>(layer_hist(hist, L, 1), state[j].k_rem0, sh, &bin1, &k_rem1);
+            prefix = (state[j].b1 << digit_bits(1)) | bin1;                   // 22 bits
+            if (s == L.stile_begin && tid == 0) {
+                state[j].p22 = prefix;
+                state[j].k_rem1 = k_rem1;
+            }
+            __syncthreads();                               // the flush above has read lh
+            for (uint32_t b = tid; b < HIST2; b += BLOCK) lh[b] = 0u;
+            __syncthreads();
+            filled = true;
+        }
+        if (L.k == 0) continue;
+        const uint32_t ntiles = (L.n + TILE - 1) / TILE;
+        const uint32_t lt0 = (s - L.stile_begin) * GROUP;
+        const uint32_t nt = min(GROUP, ntiles - lt0);
+        // the super-tile's eight counts, one per lane; a wavefront takes tiles wave and wave + 4, the counts
+        // and the first 256 entries of both requested before any of them is used
+        const uint32_t my_cnt = lane < nt ? staged_entries(stage_cnt[L.tile_begin + lt0 + lane]) : 0u;
+        constexpr uint32_t MINE = GROUP / (BLOCK / WAVE);
+        uint32_t cnt[MINE];
+        uint32_t key[MINE][4];
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const uint32_t key = score_key(rv[q], wv[q], eps);
-                    if (i + q < L.n && (key >> digit_shift(1)) == prefix) atomicAdd(&lh[key & (HIST2 - 1)], 1u);
+        for (uint32_t m = 0; m < MINE; ++m) {
+            cnt[m] = __shfl(my_cnt, (int)(wave + m * (BLOCK / WAVE)), WAVE);
+            if (cnt[m] == RAW_TILE) cnt[m] = 0u;           // read again below
+            const uint64_t sb = L.slot_begin + (uint64_t)(lt0 + wave + m * (BLOCK / WAVE)) * L.slot_cap;
+#pragma unroll
+            for (uint32_t q = 0; q < 4; ++q) {
+                const uint32_t e = q * WAVE + lane;
+                key[m][q] = e < cnt[m] ? A.key[sb + e] : NOT_AN_ELEMENT;
+            }
+        }
+#pragma unroll
+        for (uint32_t m = 0; m < MINE; ++m) {
+#pragma unroll
+            for (uint32_t q = 0; q < 4; ++q)
+                if (key[m][q] != NOT_AN_ELEMENT && (key[m][q] >> digit_shift(1)) == prefix)
+                    atomicAdd(&lh[key[m][q] & (HIST2 - 1)], 1u);
+            const uint64_t sb = L.slot_begin + (uint64_t)(lt0 + wave + m * (BLOCK / WAVE)) * L.slot_cap;
+            for (uint32_t e = 4 * WAVE + lane; e < cnt[m]; e += WAVE) {        // fuller slots: the rest
+                const uint32_t k2 = A.key[sb + e];
+                if ((k2 >> digit_shift(1)) == prefix) atomicAdd(&lh[k2 & (HIST2 - 1)], 1u);
+            }
+        }
+        const uint64_t raw_tiles = __ballot(my_cnt == RAW_TILE) & 0xFFull;    // the same in every wavefront
+        if (raw_tiles) {                                                       // uniform
+            const float* rl = R.r[leader_of(leader, j, W)] + L.offset;
+            const float* wl = w + L.offset;
+            const bool vec = is_aligned16(rl) && is_aligned16(wl);
+            for (uint32_t tl = 0; tl < nt; ++tl) {
+                if (!((raw_tiles >> tl) & 1ull)) continue;
+                for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+                    const uint32_t i = (lt0 + tl) * TILE + u * CHUNK + tid * VEC;
+                    if (i >= L.n) break;
+                    float rv[4], wv[4];
+                    load_quad(rl, i, L.n, vec, rv);
+                    load_quad(wl, i, L.n, vec, wv, 1.0f);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const uint32_t key2 = score_key(rv[q], wv[q], eps);
+                        if (i + q < L.n && (key2 >> digit_shift(1)) == prefix) atomicAdd(&lh[key2 & (HIST2 - 1)], 1u);
+                    }
                 }
             }
         }
     }
-    __syncthreads();
-    flush_hist<HIST2>(lh, layer_hist(hist, L, 2));
+    if (filled) {
+        __syncthreads();
+        flush_hist<HIST2>(lh, layer_hist(hist, L, 2));
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -450,7 +508,7 @@ __global__ __launch_bounds__(BLOCK) void k_refine2(ResidualPtrs R, const float* 
 // ---------------------------------------------------------------------------
 template <bool FROM_RECORDS>
 __global__ __launch_bounds__(BLOCK) void k_count(ResidualPtrs R, const float* __restrict__ w,
-                                                 const DevLayer* __restrict__ layers, uint32_t n_layers,
+                                                 const DevLayer* __restrict__ layers, uint32_t n_layers, uint32_t stiles,
                                                  const uint32_t* __restrict__ leader, uint32_t W, float eps,
                                                  LayerState* __restrict__ state, const uint32_t* __restrict__ hist,
                                                  iwp_threshold* __restrict__ thr_out,
@@ -460,70 +518,102 @@ __global__ __launch_bounds__(BLOCK) void k_count(ResidualPtrs R, const float* __
     __shared__ uint32_t sh[BLOCK + 2];
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & (WAVE - 1), wave = tid >> 6;
-    const uint32_t s = blockIdx.x;
-    const uint32_t j = find_layer<true>(layers, n_layers, s);
-    const DevLayer L = layers[j];
-    if (L.k == 0) return;
     constexpr bool all_raw = FROM_RECORDS;
-    uint32_t thr;
-    if (FROM_RECORDS) {
-        thr = state[j].thr;
-    } else {
-        // third pick, redone by every workgroup of the layer: the exact k-th largest key
-        uint32_t bin2, k_rem2;
-        block_pick<(int)HIST2>(layer_hist(hist, L, 2), state[j].k_rem1, sh, &bin2, &k_rem2);
-        thr = (state[j].p22 << digit_bits(2)) | bin2;
-        if (s == L.stile_begin && tid == 0) {
-            state[j].thr = thr;
-            state[j].n_eq_take = k_rem2;
-            if (thr_out) {
-                iwp_threshold th;
-                th.key = thr; th.n_gt = L.k - k_rem2; th.n_eq_take = k_rem2;
-                thr_out[j] = th;
+    const uint32_t per = (stiles + gridDim.x - 1) / gridDim.x;
+    const uint32_t s0 = blockIdx.x * per, s1 = min(s0 + per, stiles);
+    uint32_t cur_j = 0xFFFFFFFFu, thr = 0;
+    DevLayer L;
+    for (uint32_t s = s0; s < s1; ++s) {
+        const uint32_t j = find_layer<true>(layers, n_layers, s);
+        if (j != cur_j) {
+            L = layers[j];
+            cur_j = j;
+            if (L.k == 0) continue;
+            if (FROM_RECORDS) {
+                thr = state[j].thr;
+            } else {
+                // third pick, redone by every workgroup of the layer: the exact k-th largest key
+                uint32_t bin2, k_rem2;
+                block_pick<(int)HIST2>(layer_hist(hist, L, 2), state[j].k_rem1, sh, &bin2, &k_rem2);
+                thr = (state[j].p22 << digit_bits(2)) | bin2;
+                if (s == L.stile_begin && tid == 0) {
+                    state[j].thr = thr;
+                    state[j].n_eq_take = k_rem2;
+                    if (thr_out) {
+                        iwp_threshold th;
+                        th.key = thr; th.n_gt = L.k - k_rem2; th.n_eq_take = k_rem2;
+                        thr_out[j] = th;
+                    }
+                }
             }
         }
-    }
-    const uint32_t ntiles = (L.n + TILE - 1) / TILE;
-    const uint32_t lt0 = (s - L.stile_begin) * GROUP;           // first tile of the super-tile, in the layer
-    const uint32_t nt = min(GROUP, ntiles - lt0);
-    const float* rl = R.r[leader_of(leader, j, W)] + L.offset;
-    const float* wl = w + L.offset;
-    // each wavefront takes tiles of its own (no workgroup-wide step until the end)
-    for (uint32_t tl = wave; tl < nt; tl += BLOCK / WAVE) {
-        const uint32_t cnt = all_raw ? RAW_TILE : staged_entries(stage_cnt[L.tile_begin + lt0 + tl]);
-        uint32_t gt = 0, eq = 0;
-        if (cnt != RAW_TILE) {
+        if (L.k == 0) continue;
+        const uint32_t ntiles = (L.n + TILE - 1) / TILE;
+        const uint32_t lt0 = (s - L.stile_begin) * GROUP;       // first tile of the super-tile, in the layer
+        const uint32_t nt = min(GROUP, ntiles - lt0);
+        const float* rl = R.r[leader_of(leader, j, W)] + L.offset;
+        const float* wl = w + L.offset;
+        // each wavefront takes tiles of its own (tiles wave and wave + 4; the counts and the first 256 entries of
+        // both requested before any of them is used); nothing workgroup-wide until the end
+        const uint32_t my_cnt = (!all_raw && lane < nt) ? staged_entries(stage_cnt[L.tile_begin + lt0 + lane]) : RAW_TILE;
+        constexpr uint32_t MINE = GROUP / (BLOCK / WAVE);
+        uint32_t cnt[MINE];
+        uint32_t key[MINE][4];
+#pragma unroll
+        for (uint32_t m = 0; m < MINE; ++m) {
+            const uint32_t tl = wave + m * (BLOCK / WAVE);
+            cnt[m] = __shfl(my_cnt, (int)tl, WAVE);
             const uint64_t sb = L.slot_begin + (uint64_t)(lt0 + tl) * L.slot_cap;
-            for (uint32_t e = lane; e < cnt; e += WAVE) {
-                const uint32_t key = A.key[sb + e];
-                gt += key > thr ? 1u : 0u;
-                eq += key == thr ? 1u : 0u;
-            }
-        } else {
-            const uint32_t first = (lt0 + tl) * TILE;
-            const uint32_t end = min(L.n, first + TILE);
-            for (uint32_t i = first + lane; i < end; i += WAVE) {
-                const uint32_t key = score_key(rl[i], wl[i], eps);
-                gt += key > thr ? 1u : 0u;
-                eq += key == thr ? 1u : 0u;
+#pragma unroll
+            for (uint32_t q = 0; q < 4; ++q) {
+                const uint32_t e = q * WAVE + lane;
+                key[m][q] = (tl < nt && cnt[m] != RAW_TILE && e < cnt[m]) ? A.key[sb + e] : NOT_AN_ELEMENT;
             }
         }
 #pragma unroll
-        for (int d = WAVE / 2; d > 0; d >>= 1) {
-            gt += __shfl_xor(gt, d, WAVE);
-            eq += __shfl_xor(eq, d, WAVE);
+        for (uint32_t m = 0; m < MINE; ++m) {
+            const uint32_t tl = wave + m * (BLOCK / WAVE);
+            if (tl >= nt) continue;
+            uint32_t gt = 0, eq = 0;
+            if (cnt[m] != RAW_TILE) {
+#pragma unroll
+                for (uint32_t q = 0; q < 4; ++q) {
+                    gt += (key[m][q] != NOT_AN_ELEMENT && key[m][q] > thr) ? 1u : 0u;
+                    eq += key[m][q] == thr ? 1u : 0u;          // a key is never NOT_AN_ELEMENT (bit 31 is clear)
+                }
+                const uint64_t sb = L.slot_begin + (uint64_t)(lt0 + tl) * L.slot_cap;
+                for (uint32_t e = 4 * WAVE + lane; e < cnt[m]; e += WAVE) {
+                    const uint32_t k2 = A.key[sb + e];
+                    gt += k2 > thr ? 1u : 0u;
+                    eq += k2 == thr ? 1u : 0u;
+                }
+            } else {
+                const uint32_t first = (lt0 + tl) * TILE;
+                const uint32_t end = min(L.n, first + TILE);
+                for (uint32_t i = first + lane; i < end; i += WAVE) {
+                    const uint32_t k2 = score_key(rl[i], wl[i], eps);
+                    gt += k2 > thr ? 1u : 0u;
+                    eq += k2 == thr ? 1u : 0u;
+                }
+            }
+#pragma unroll
+            for (int d = WAVE / 2; d > 0; d >>= 1) {
+                gt += __shfl_xor(gt, d, WAVE);
+                eq += __shfl_xor(eq, d, WAVE);
+            }
+            if (lane == 0) { cg[tl] = gt; ce[tl] = eq; }
         }
-        if (lane == 0) { cg[tl] = gt; ce[tl] = eq; }
-    }
-    __syncthreads();
-    if (tid == 0) {
-        uint32_t G = 0, E = 0;
-        for (uint32_t tl = 0; tl < nt; ++tl) {
-            tile_counts[L.tile_begin + lt0 + tl] = make_uint2(G, E);
-            G += cg[tl];
-            E += ce[tl];
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t G = 0, E = 0;
+            for (uint32_t tl = 0; tl < nt; ++tl) {
+                tile_counts[L.tile_begin + lt0 + tl] = make_uint2(G, E);
+                G += cg[tl];
+                E += ce[tl];
+            }
+            stile_counts[s] = make_uint2(G, E);
         }
-        stile_counts[s] = make_uint2(G, E);
+        __syncthreads();                                        // cg / ce are written again for the next super-tile
     }
 }
 
