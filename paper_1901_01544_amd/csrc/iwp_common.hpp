@@ -60,11 +60,14 @@ constexpr uint32_t FLUSHES_PER_COPY = 512;                 // look-1 workgroups 
 __host__ __device__ constexpr uint32_t layer_hist_words(uint32_t copies) { return copies * HIST0 + HIST1 + HIST2; }
 
 constexpr uint32_t RAW_TILE = 0xFFFFFFFFu;        // stage count of a tile whose candidates did not fit its slot
+constexpr uint32_t UNIFORM_TILE = 0xFFFFFFFEu;    // stage count of such a tile whose keys are all the same (say, a tile of zero
+                                                  // residuals): the key is the slot's only entry, and the later passes handle
+                                                  // the tile from its element count instead of reading it again
 constexpr uint32_t RESTAGED = 0x40000000u;        // flag on a stage count: look 2 filled this slot again (from b1) after look 1
                                                   // had overflowed it; look 2's reader of look-1 slots skips such tiles
-// Entries in a tile's slot for the passes after look 2 (RAW_TILE stays RAW_TILE).
+// Entries in a tile's slot for the passes after look 2 (RAW_TILE and UNIFORM_TILE stay what they are).
 __device__ __forceinline__ uint32_t staged_entries(uint32_t stage_count) {
-    return stage_count == RAW_TILE ? RAW_TILE : stage_count & ~RESTAGED;
+    return stage_count >= UNIFORM_TILE ? stage_count : stage_count & ~RESTAGED;
 }
 constexpr uint32_t NO_STAGE_BIN = 0xFFFFFFFFu;    // LayerState.stage_bin: look 1 stages nothing for this layer
 constexpr uint32_t NOT_AN_ELEMENT = 0xFFFFFFFFu;  // key slot of a lane position past the layer's end
@@ -168,11 +171,12 @@ __device__ __forceinline__ void store_v4(float* p, v4f v) {
 
 // Four consecutive elements starting at element i of a layer of n elements.
 // vec: the layer base is 16-byte aligned, so a whole quad is one 128-bit load.
-// Lanes past the end read nothing and get `fill`.
+// Lanes past the end read nothing and get `fill`.  NT: streaming (non-temporal) access for whole quads.
+template <bool NT = false>
 __device__ __forceinline__ void load_quad(const float* __restrict__ base, uint32_t i, uint32_t n, bool vec,
                                           float (&v)[4], float fill = 0.0f) {
     if (vec && i + 4 <= n) {
-        const v4f t = *reinterpret_cast<const v4f*>(base + i);
+        const v4f t = load_v4<NT>(base + i);
         v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
     } else {
 #pragma unroll
@@ -180,10 +184,11 @@ __device__ __forceinline__ void load_quad(const float* __restrict__ base, uint32
     }
 }
 
+template <bool NT = false>
 __device__ __forceinline__ void store_quad(float* __restrict__ base, uint32_t i, uint32_t n, bool vec, const float (&v)[4]) {
     if (vec && i + 4 <= n) {
         v4f t; t.x = v[0]; t.y = v[1]; t.z = v[2]; t.w = v[3];
-        *reinterpret_cast<v4f*>(base + i) = t;
+        store_v4<NT>(base + i, t);
     } else {
 #pragma unroll
         for (int c = 0; c < 4; ++c) if (i + c < n) base[i + c] = v[c];

@@ -375,15 +375,38 @@ __global__ __launch_bounds__(BLOCK) void k_stage(ResidualPtrs R, const float* __
                 for (int q = 0; q < 4; ++q) {
                     if (full || i + q < L.n) {
                         key[u][q] = score_key(val[u][q], wgt[u][q], eps);
-                        if ((key[u][q] >> digit_shift(0)) == b1)
-                            atomicAdd(&lh[(key[u][q] >> digit_shift(1)) & (HIST1 - 1)], 1u);
                     } else {
                         key[u][q] = NOT_AN_ELEMENT;
                     }
                 }
             }
-            const uint32_t cnt = stage_tile(key, val, base, b1, L.slot_cap, L.slot_begin + (uint64_t)lt * L.slot_cap, A, slot);
-            if (tid == 0) stage_cnt[t] = (prestaged && cnt != RAW_TILE) ? (cnt | RESTAGED) : cnt;
+            // a tile whose keys are all the same (typically a tile of zero residuals in a layer whose threshold is
+            // zero, where everything ties) is recorded as such: one entry instead of an overflowing slot
+            const uint32_t k0 = score_key(rl[base], wl[base], eps);            // the tile's first element
+            bool same = true;
+#pragma unroll
+            for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) same = same && (key[u][q] == k0 || key[u][q] == NOT_AN_ELEMENT);
+            const bool uniform_tile = __syncthreads_and(same ? 1 : 0) != 0;
+            const uint64_t sb = L.slot_begin + (uint64_t)lt * L.slot_cap;
+            if (uniform_tile) {
+                if (tid == 0) {
+                    if ((k0 >> digit_shift(0)) == b1)
+                        atomicAdd(&lh[(k0 >> digit_shift(1)) & (HIST1 - 1)], min(TILE, L.n - base));
+                    A.key[sb] = k0;
+                    stage_cnt[t] = UNIFORM_TILE;
+                }
+            } else {
+#pragma unroll
+                for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        if (key[u][q] != NOT_AN_ELEMENT && (key[u][q] >> digit_shift(0)) == b1)
+                            atomicAdd(&lh[(key[u][q] >> digit_shift(1)) & (HIST1 - 1)], 1u);
+                const uint32_t cnt = stage_tile(key, val, base, b1, L.slot_cap, sb, A, slot);
+                if (tid == 0) stage_cnt[t] = (prestaged && cnt != RAW_TILE) ? (cnt | RESTAGED) : cnt;
+            }
         }
         __syncthreads();
         flush_hist<HIST1>(lh, layer_hist(hist, L, 1));
@@ -449,9 +472,16 @@ __global__ __launch_bounds__(BLOCK) void k_refine2(ResidualPtrs R, const float* 
         uint32_t key[MINE][4];
 #pragma unroll
         for (uint32_t m = 0; m < MINE; ++m) {
-            cnt[m] = __shfl(my_cnt, (int)(wave + m * (BLOCK / WAVE)), WAVE);
+            const uint32_t tl = wave + m * (BLOCK / WAVE);
+            cnt[m] = __shfl(my_cnt, (int)tl, WAVE);
+            const uint64_t sb = L.slot_begin + (uint64_t)(lt0 + tl) * L.slot_cap;
+            if (cnt[m] == UNIFORM_TILE) {                  // all keys of the tile are the slot's one entry
+                const uint32_t k0 = A.key[sb];
+                if (lane == 0 && (k0 >> digit_shift(1)) == prefix)
+                    atomicAdd(&lh[k0 & (HIST2 - 1)], min(TILE, L.n - (lt0 + tl) * TILE));
+                cnt[m] = 0u;
+            }
             if (cnt[m] == RAW_TILE) cnt[m] = 0u;           // read again below
-            const uint64_t sb = L.slot_begin + (uint64_t)(lt0 + wave + m * (BLOCK / WAVE)) * L.slot_cap;
 #pragma unroll
             for (uint32_t q = 0; q < 4; ++q) {
                 const uint32_t e = q * WAVE + lane;
@@ -567,7 +597,7 @@ __global__ __launch_bounds__(BLOCK) void k_count(ResidualPtrs R, const float* __
 #pragma unroll
             for (uint32_t q = 0; q < 4; ++q) {
                 const uint32_t e = q * WAVE + lane;
-                key[m][q] = (tl < nt && cnt[m] != RAW_TILE && e < cnt[m]) ? A.key[sb + e] : NOT_AN_ELEMENT;
+                key[m][q] = (tl < nt && cnt[m] < UNIFORM_TILE && e < cnt[m]) ? A.key[sb + e] : NOT_AN_ELEMENT;
             }
         }
 #pragma unroll
@@ -575,7 +605,11 @@ __global__ __launch_bounds__(BLOCK) void k_count(ResidualPtrs R, const float* __
             const uint32_t tl = wave + m * (BLOCK / WAVE);
             if (tl >= nt) continue;
             uint32_t gt = 0, eq = 0;
-            if (cnt[m] != RAW_TILE) {
+            if (cnt[m] == UNIFORM_TILE) {                  // all keys of the tile are the slot's one entry
+                const uint32_t k0 = A.key[L.slot_begin + (uint64_t)(lt0 + tl) * L.slot_cap];
+                const uint32_t n_tile = min(TILE, L.n - (lt0 + tl) * TILE);
+                if (lane == 0) { gt = k0 > thr ? n_tile : 0u; eq = k0 == thr ? n_tile : 0u; }
+            } else if (cnt[m] != RAW_TILE) {
 #pragma unroll
                 for (uint32_t q = 0; q < 4; ++q) {
                     gt += (key[m][q] != NOT_AN_ELEMENT && key[m][q] > thr) ? 1u : 0u;
@@ -725,6 +759,26 @@ __global__ __launch_bounds__(BLOCK) void k_write(ResidualPtrs R, const float* __
     if (lane == 0) tile_out[t] = out_base;
     const uint32_t cnt = all_raw ? RAW_TILE : staged_entries(stage_cnt[t]);
 
+    if (cnt == UNIFORM_TILE) {
+        // all keys of the tile are the slot's one entry: above the threshold everything is kept, at the
+        // threshold the first elements until the quota of ties is used up, below it nothing
+        const uint32_t k0 = A.key[L.slot_begin + (uint64_t)lt * L.slot_cap];
+        const uint32_t n_tile = min(TILE, L.n - tile_first);
+        uint32_t take = 0;
+        if (k0 > thr) take = n_tile;
+        else if (k0 == thr && Et < quota) take = min(n_tile, quota - Et);
+        for (uint32_t i = lane; i < take; i += WAVE) {
+            const uint32_t pos = out_base + i;
+            const uint32_t li = tile_first + i;
+            if (pos < L.k) {
+                const float v = rl[li];
+                io[pos] = (uint32_t)(L.offset + li);
+                vo[pos] = v;
+                if (FUSED) { go[pos] = v; rl[li] = 0.0f; }
+            }
+        }
+        return;
+    }
     if (cnt != RAW_TILE) {
         if (cnt == 0) return;
         uint32_t* eqmap = maps[wave][0];

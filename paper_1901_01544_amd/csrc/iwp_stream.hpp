@@ -47,16 +47,25 @@ __device__ __forceinline__ void stream_tile(const float* __restrict__ gl, float*
             store_v4<true>(rl + i, accum(rr[u], gg[u], m));
         }
     } else {
-        // ragged tail of a layer, or a layer whose base is not 16-byte aligned
+        // ragged tail of a layer, or a layer whose base is not 16-byte aligned: the same shape, every load of
+        // the tile that lies inside the layer issued before the first use
+        float rv[CHUNKS_PER_TILE][4], gv[CHUNKS_PER_TILE][4];
+#pragma unroll
         for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
             const uint32_t i = base + u * CHUNK + tid * VEC;
-            if (i >= n) break;
-            float rv[4], gv[4];
-            load_quad(rl, i, n, vec, rv);
-            load_quad(gl, i, n, vec, gv);
+            if (i < n) {
+                load_quad<true>(rl, i, n, vec, rv[u]);
+                load_quad<true>(gl, i, n, vec, gv[u]);
+            }
+        }
 #pragma unroll
-            for (int q = 0; q < 4; ++q) rv[q] = accum(rv[q], gv[q], m);
-            store_quad(rl, i, n, vec, rv);
+        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+            const uint32_t i = base + u * CHUNK + tid * VEC;
+            if (i < n) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) rv[u][q] = accum(rv[u][q], gv[u][q], m);
+                store_quad<true>(rl, i, n, vec, rv[u]);
+            }
         }
     }
 }
@@ -98,23 +107,28 @@ __device__ __forceinline__ void lead_tile(const float* __restrict__ gl, float* _
             key[u][3] = score_key(rr[u].w, ww[u].w, eps);
         }
     } else {
-        // ragged tail of a layer, or a layer whose base is not 16-byte aligned
+        // ragged tail of a layer, or a layer whose base is not 16-byte aligned: the same shape, every load of
+        // the tile that lies inside the layer issued before the first use
+        float gv[CHUNKS_PER_TILE][4], wv[CHUNKS_PER_TILE][4];
 #pragma unroll
         for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
             const uint32_t i = base + u * CHUNK + tid * VEC;
-            float gv[4], wv[4];
             if (i < n) {
-                load_quad(rl, i, n, vec, val[u]);
-                if (ACC) {
-                    load_quad(gl, i, n, vec, gv);
+                load_quad<true>(rl, i, n, vec, val[u]);
+                if (ACC) load_quad<true>(gl, i, n, vec, gv[u]);
+                load_quad<true>(wl, i, n, vec, wv[u], 1.0f);
+            }
+        }
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) val[u][q] = accum(val[u][q], gv[q], m);
-                    store_quad(rl, i, n, vec, val[u]);
-                }
-                load_quad(wl, i, n, vec, wv, 1.0f);
+        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+            const uint32_t i = base + u * CHUNK + tid * VEC;
+            if (ACC && i < n) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) val[u][q] = accum(val[u][q], gv[u][q], m);
+                store_quad<true>(rl, i, n, vec, val[u]);
             }
 #pragma unroll
-            for (int q = 0; q < 4; ++q) key[u][q] = (i + q < n) ? score_key(val[u][q], wv[q], eps) : NOT_AN_ELEMENT;
+            for (int q = 0; q < 4; ++q) key[u][q] = (i + q < n) ? score_key(val[u][q], wv[u][q], eps) : NOT_AN_ELEMENT;
         }
     }
 #pragma unroll
@@ -247,13 +261,24 @@ __global__ __launch_bounds__(BLOCK) void k_follow_gather(WorkerPtrs P, WorkerLis
     const bool vec = is_aligned16(rl) && is_aligned16(gl);
     const bool full = vec && base + TILE <= L.n;
     // the tile's loads go out first; the bitmap of sent positions is built while they are in flight
-    v4f rr[CHUNKS_PER_TILE], gg[CHUNKS_PER_TILE];
+    float rv[CHUNKS_PER_TILE][4], gv[CHUNKS_PER_TILE][4];      // one set of registers for both forms of the tile
     if (full) {
 #pragma unroll
         for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
             const uint32_t i = base + u * CHUNK + tid * VEC;
-            rr[u] = load_v4<true>(rl + i);
-            gg[u] = load_v4<true>(gl + i);
+            const v4f a = load_v4<true>(rl + i);
+            const v4f b = load_v4<true>(gl + i);
+            rv[u][0] = a.x; rv[u][1] = a.y; rv[u][2] = a.z; rv[u][3] = a.w;
+            gv[u][0] = b.x; gv[u][1] = b.y; gv[u][2] = b.z; gv[u][3] = b.w;
+        }
+    } else {
+#pragma unroll
+        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+            const uint32_t i = base + u * CHUNK + tid * VEC;
+            if (i < L.n) {
+                load_quad<true>(rl, i, L.n, vec, rv[u]);
+                load_quad<true>(gl, i, L.n, vec, gv[u]);
+            }
         }
     }
     if (cnt) {                                                   // uniform
@@ -270,34 +295,34 @@ __global__ __launch_bounds__(BLOCK) void k_follow_gather(WorkerPtrs P, WorkerLis
 #pragma unroll
         for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
             const uint32_t loc = u * CHUNK + tid * VEC;
-            rr[u] = accum(rr[u], gg[u], P.momentum);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) rv[u][q] = accum(rv[u][q], gv[u][q], P.momentum);
             const uint32_t nib = cnt ? (map[loc >> 5] >> (loc & 31u)) & 0xFu : 0u;
             if (nib) {
                 uint32_t rank = bitmap_rank(map, pre, loc);
-                if (nib & 1u) { go[rank++] = rr[u].x; rr[u].x = 0.0f; }
-                if (nib & 2u) { go[rank++] = rr[u].y; rr[u].y = 0.0f; }
-                if (nib & 4u) { go[rank++] = rr[u].z; rr[u].z = 0.0f; }
-                if (nib & 8u) { go[rank++] = rr[u].w; rr[u].w = 0.0f; }
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if ((nib >> q) & 1u) { go[rank++] = rv[u][q]; rv[u][q] = 0.0f; }
             }
-            store_v4<true>(rl + base + loc, rr[u]);
+            v4f out; out.x = rv[u][0]; out.y = rv[u][1]; out.z = rv[u][2]; out.w = rv[u][3];
+            store_v4<true>(rl + base + loc, out);
         }
     } else {
-        // ragged tail of a layer, or a layer whose base is not 16-byte aligned
+        // ragged tail of a layer, or a layer whose base is not 16-byte aligned (loaded above)
+#pragma unroll
         for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
             const uint32_t loc = u * CHUNK + tid * VEC;
             const uint32_t i = base + loc;
-            if (i >= L.n) break;
-            float rv[4], gv[4];
-            load_quad(rl, i, L.n, vec, rv);
-            load_quad(gl, i, L.n, vec, gv);
-            const uint32_t nib = cnt ? (map[loc >> 5] >> (loc & 31u)) & 0xFu : 0u;
-            uint32_t rank = nib ? bitmap_rank(map, pre, loc) : 0u;
+            if (i < L.n) {
+                const uint32_t nib = cnt ? (map[loc >> 5] >> (loc & 31u)) & 0xFu : 0u;
+                uint32_t rank = nib ? bitmap_rank(map, pre, loc) : 0u;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                rv[q] = accum(rv[q], gv[q], P.momentum);
-                if ((nib >> q) & 1u) { go[rank++] = rv[q]; rv[q] = 0.0f; }
+                for (int q = 0; q < 4; ++q) {
+                    rv[u][q] = accum(rv[u][q], gv[u][q], P.momentum);
+                    if ((nib >> q) & 1u) { go[rank++] = rv[u][q]; rv[u][q] = 0.0f; }
+                }
+                store_quad<true>(rl, i, L.n, vec, rv[u]);
             }
-            store_quad(rl, i, L.n, vec, rv);
         }
     }
 }

@@ -92,21 +92,28 @@ __device__ __forceinline__ void chosen_tile(const float* gp, float* rl, const fl
             wv[u][0] = ww[u].x; wv[u][1] = ww[u].y; wv[u][2] = ww[u].z; wv[u][3] = ww[u].w;
         }
     } else {
+        // ragged tail or misaligned base: the same shape, every load inside the layer issued before the first use
+        float gv[CHUNKS_PER_TILE][4];
 #pragma unroll
         for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
             const uint32_t i = base + u * CHUNK + tid * VEC;
 #pragma unroll
             for (int c = 0; c < 4; ++c) { rv[u][c] = 0.0f; wv[u][c] = 1.0f; }
             if (i < n) {
-                load_quad(rl, i, n, vec, rv[u]);
-                if (gp) {
-                    float gv[4];
-                    load_quad(gl, i, n, vec, gv);
+                load_quad<true>(rl, i, n, vec, rv[u]);
+                if (gp) load_quad<true>(gl, i, n, vec, gv[u]);
+                load_quad<true>(wl, i, n, vec, wv[u], 1.0f);
+            }
+        }
+        if (gp) {
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) rv[u][c] = accum(rv[u][c], gv[c], m);
-                    store_quad(rl, i, n, vec, rv[u]);
+            for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+                const uint32_t i = base + u * CHUNK + tid * VEC;
+                if (i < n) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) rv[u][c] = accum(rv[u][c], gv[u][c], m);
+                    store_quad<true>(rl, i, n, vec, rv[u]);
                 }
-                load_quad(wl, i, n, vec, wv[u], 1.0f);
             }
         }
     }
@@ -413,13 +420,24 @@ __global__ __launch_bounds__(BLOCK) void k_follow_mask(WorkerPtrs P, const DevLa
     const float* gl = gp + L.offset;
     const bool vec = is_aligned16(rl) && is_aligned16(gl);
     const bool full = vec && base + TILE <= L.n;
-    v4f rr[CHUNKS_PER_TILE], gg[CHUNKS_PER_TILE];
+    float rv[CHUNKS_PER_TILE][4], gv[CHUNKS_PER_TILE][4];      // one set of registers for both forms of the tile
     if (full) {
 #pragma unroll
         for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
             const uint32_t i = base + u * CHUNK + tid * VEC;
-            rr[u] = load_v4<true>(rl + i);
-            gg[u] = load_v4<true>(gl + i);
+            const v4f a = load_v4<true>(rl + i);
+            const v4f b = load_v4<true>(gl + i);
+            rv[u][0] = a.x; rv[u][1] = a.y; rv[u][2] = a.z; rv[u][3] = a.w;
+            gv[u][0] = b.x; gv[u][1] = b.y; gv[u][2] = b.z; gv[u][3] = b.w;
+        }
+    } else {
+#pragma unroll
+        for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
+            const uint32_t i = base + u * CHUNK + tid * VEC;
+            if (i < L.n) {
+                load_quad<true>(rl, i, L.n, vec, rv[u]);
+                load_quad<true>(gl, i, L.n, vec, gv[u]);
+            }
         }
     }
     const bool exchange = !overflowed(count_out, n_layers);
@@ -437,33 +455,33 @@ __global__ __launch_bounds__(BLOCK) void k_follow_mask(WorkerPtrs P, const DevLa
 #pragma unroll
         for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
             const uint32_t loc = u * CHUNK + tid * VEC;
-            rr[u] = accum(rr[u], gg[u], P.momentum);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) rv[u][q] = accum(rv[u][q], gv[u][q], P.momentum);
             const uint32_t nib = (map[loc >> 5] >> (loc & 31u)) & 0xFu;
             if (nib) {
                 uint32_t rank = bitmap_rank(map, pre, loc);
-                if (nib & 1u) { if (rank < room) go[rank] = rr[u].x; ++rank; rr[u].x = 0.0f; }
-                if (nib & 2u) { if (rank < room) go[rank] = rr[u].y; ++rank; rr[u].y = 0.0f; }
-                if (nib & 4u) { if (rank < room) go[rank] = rr[u].z; ++rank; rr[u].z = 0.0f; }
-                if (nib & 8u) { if (rank < room) go[rank] = rr[u].w; ++rank; rr[u].w = 0.0f; }
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if ((nib >> q) & 1u) { if (rank < room) go[rank] = rv[u][q]; ++rank; rv[u][q] = 0.0f; }
             }
-            store_v4<true>(rl + base + loc, rr[u]);
+            v4f out; out.x = rv[u][0]; out.y = rv[u][1]; out.z = rv[u][2]; out.w = rv[u][3];
+            store_v4<true>(rl + base + loc, out);
         }
     } else {
+#pragma unroll
         for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
             const uint32_t loc = u * CHUNK + tid * VEC;
             const uint32_t i = base + loc;
-            if (i >= L.n) break;
-            float rv[4], gv[4];
-            load_quad(rl, i, L.n, vec, rv);
-            load_quad(gl, i, L.n, vec, gv);
-            const uint32_t nib = (map[loc >> 5] >> (loc & 31u)) & 0xFu;
-            uint32_t rank = nib ? bitmap_rank(map, pre, loc) : 0u;
+            if (i < L.n) {
+                const uint32_t nib = (map[loc >> 5] >> (loc & 31u)) & 0xFu;
+                uint32_t rank = nib ? bitmap_rank(map, pre, loc) : 0u;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                rv[q] = accum(rv[q], gv[q], P.momentum);
-                if ((nib >> q) & 1u) { if (rank < room) go[rank] = rv[q]; ++rank; rv[q] = 0.0f; }
+                for (int q = 0; q < 4; ++q) {
+                    rv[u][q] = accum(rv[u][q], gv[u][q], P.momentum);
+                    if ((nib >> q) & 1u) { if (rank < room) go[rank] = rv[u][q]; ++rank; rv[u][q] = 0.0f; }
+                }
+                store_quad<true>(rl, i, L.n, vec, rv[u]);
             }
-            store_quad(rl, i, L.n, vec, rv);
         }
     }
 }
