@@ -17,7 +17,9 @@ cpu_baseline) are the AlexNet-shaped set, whole-step route, hinted with the prev
 step's thresholds.  With the default workload ("headline") the same line carries, under
 "also", the same measurement without hints and the ResNet-50-shaped set with and without
 hints, each with its own roofline and (per workload) cpu_baseline: the target names both
-sets.  Timing: the K timed steps run back to back with nothing else on the stream; the
+sets.  All of these are taken in the steady state of the residuals (--preroll un-timed steps
+first; hinted and unhinted run the same steps from the same saved state); the cold start
+(first steps from zero residuals, where the selection has less to do) is listed beside them.  Timing: the K timed steps run back to back with nothing else on the stream; the
 dominant kernel's launch durations and the per-step spread come from a second loop of K
 steps, after the first.
 """
@@ -576,6 +578,12 @@ def main():
         b = bench_topk(iwp, wl, torch, np, args, "resnet50", [True, False], not args.no_parts, not args.no_cpu_baseline)
         out = a[0]
         out["also"] = {"alexnet_shaped_unhinted": a[1], "resnet50_shaped": b[0], "resnet50_shaped_unhinted": b[1]}
+        if args.preroll:
+            # the same two sets from zero residuals (the first steps of a run), hinted, for comparison
+            cold = argparse.Namespace(**vars(args))
+            cold.preroll = 0
+            out["also"]["alexnet_shaped_cold_start"] = bench_topk(iwp, wl, torch, np, cold, "alexnet", [True], False, False)[0]
+            out["also"]["resnet50_shaped_cold_start"] = bench_topk(iwp, wl, torch, np, cold, "resnet50", [True], False, False)[0]
     else:
         modes = [False] if args.no_hint else [True, False]
         blocks = bench_topk(iwp, wl, torch, np, args, args.workload, modes, not args.no_parts, not args.no_cpu_baseline)

@@ -131,11 +131,21 @@ __device__ __forceinline__ void lead_tile(const float* __restrict__ gl, float* _
             for (int q = 0; q < 4; ++q) key[u][q] = (i + q < n) ? score_key(val[u][q], wv[u][q], eps) : NOT_AN_ELEMENT;
         }
     }
+    // zero scores (zero residuals: a layer's untouched part) are counted in a register and added once per
+    // wavefront: a tile of zeros would otherwise be 4096 atomics on one LDS word
+    uint32_t zeros = 0;
 #pragma unroll
     for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u)
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-            if (key[u][q] != NOT_AN_ELEMENT) atomicAdd(&C.lh[key[u][q] >> digit_shift(0)], 1u);
+        for (int q = 0; q < 4; ++q) {
+            if (key[u][q] == 0u) ++zeros;
+            else if (key[u][q] != NOT_AN_ELEMENT) atomicAdd(&C.lh[key[u][q] >> digit_shift(0)], 1u);
+        }
+    if (__any(zeros != 0)) {
+#pragma unroll
+        for (int d = WAVE / 2; d > 0; d >>= 1) zeros += __shfl_xor(zeros, d, WAVE);
+        if ((tid & (WAVE - 1)) == 0) atomicAdd(&C.lh[0], zeros);
+    }
     if (C.stage_bin != NO_STAGE_BIN) {                      // uniform
         const uint32_t cnt = stage_tile(key, val, base, C.stage_bin, C.cap, C.slot_begin + (uint64_t)lt * C.cap, C.A,
                                         C.slot + (lt & 1u) * 4u);
