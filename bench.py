@@ -548,6 +548,8 @@ def main():
                     help="top-k routes, single workload: measure only without the previous step's thresholds as a "
                          "hint (results are identical either way; the hint saves the second pass over the "
                          "leaders' layers)")
+    ap.add_argument("--hinted-only", action="store_true",
+                    help="top-k routes, single workload: skip the unhinted measurement (for profiler runs)")
     ap.add_argument("--preroll", type=int, default=200,
                     help="top-k routes: un-timed steps from zero residuals before the warm-up, so that the timed "
                          "steps see the steady state of the residuals (0 = cold start)")
@@ -585,7 +587,7 @@ def main():
             out["also"]["alexnet_shaped_cold_start"] = bench_topk(iwp, wl, torch, np, cold, "alexnet", [True], False, False)[0]
             out["also"]["resnet50_shaped_cold_start"] = bench_topk(iwp, wl, torch, np, cold, "resnet50", [True], False, False)[0]
     else:
-        modes = [False] if args.no_hint else [True, False]
+        modes = [False] if args.no_hint else ([True] if args.hinted_only else [True, False])
         blocks = bench_topk(iwp, wl, torch, np, args, args.workload, modes, not args.no_parts, not args.no_cpu_baseline)
         out = blocks[0]
         if len(blocks) > 1:
