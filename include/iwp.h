@@ -189,7 +189,7 @@ int compress_segmented(const iwp_plan* plan, const float* w, const float* const*
  * library runs on holds one copy until the process ends.  The call allocates and frees nothing
  * (its first call on a device looks the buffer's address up, nothing more).  A plan whose
  * iwp_plan_workspace_bytes() exceeds the buffer is refused with IWP_ESCRATCH before anything is
- * launched (the AlexNet-shaped set needs 46.5 MB, the ResNet-50-shaped one 24.6 MB).  All calls
+ * launched (the AlexNet-shaped set needs 46.8 MB, the ResNet-50-shaped one 24.7 MB).  All calls
  * on one GPU share that one buffer, which keeps the last call's contents; each call clears what
  * it needs cleared.  Calls that overlap on one GPU (two streams, two threads) race on it: run them
  * one after the other on one stream, or use compress_segmented with separate workspaces. */
@@ -215,7 +215,10 @@ int compress_segmented_static(const iwp_plan* plan, const float* w, const float*
  * first pass over a leader's layer already copy out every element from slightly
  * below the hinted threshold, which makes the second pass over that layer
  * unnecessary whenever the new threshold is not below that mark; otherwise, and
- * for records that are wrong or garbage, the layer just takes the two-pass route. */
+ * for records that are wrong or garbage, the layer just takes the two-pass route.
+ * With NULL the library derives the same mark itself from a small sample of each
+ * layer (read-only, inside the call's first launch); equally without influence on
+ * any output. */
 int iwp_step_segmented(const iwp_plan* plan, float* w, const float* const* g, float* const* r, uint32_t W,
                        const uint32_t* leader, const iwp_threshold* thr_hint, float eps, float scale,
                        uint32_t* idx_out, float* val_out, float* sum_out, iwp_threshold* thr_out,
