@@ -227,8 +227,12 @@ int run_select(const Table& T, const Workspace& ws, const ResidualPtrs& R, const
                iwp_threshold* thr_out, hipStream_t s) {
     if (!T.any_k || T.tiles == 0) return IWP_OK;
     IWP_LAUNCH("k_first_pick", k_first_pick, T.n_layers, s, T.layers, ws.hist, ws.state);
-    // consecutive tiles per workgroup, at most 64 of them (their look-1 counts are fetched one per lane)
-    const uint32_t stage_grid = std::max<uint32_t>(std::min<uint32_t>(T.tiles, STAGE_MAX_GRID), (T.tiles + WAVE - 1) / WAVE);
+    // Consecutive tiles per workgroup: STAGE_TILES on tables of long layers (most tiles have nothing to do when look 1
+    // staged their layer), one on tables of short layers (a layer that has to be read again wants all the workgroups
+    // it can get), more on very large tables, at most 64 (their look-1 counts are fetched one per lane).
+    const uint32_t per_wg = T.tiles / std::max<uint32_t>(1u, T.n_layers) >= STAGE_LONG_LAYER_TILES ? STAGE_TILES : 1u;
+    const uint32_t stage_grid = std::max<uint32_t>(std::min<uint32_t>((T.tiles + per_wg - 1) / per_wg, STAGE_MAX_GRID),
+                                                   (T.tiles + WAVE - 1) / WAVE);
     IWP_LAUNCH("k_stage", k_stage, stage_grid, s, R, w, T.layers, T.n_layers, T.tiles,
                leader, W, eps, ws.state, ws.hist, ws.stage, ws.A);
     const uint32_t stile_grid = std::min<uint32_t>(T.stiles, STILE_MAX_GRID);

@@ -264,6 +264,11 @@ __device__ __forceinline__ void flush_hist(const uint32_t* lh, uint32_t* __restr
 // ---------------------------------------------------------------------------
 constexpr uint32_t STAGE_GROUP = 16;               // tiles whose slots one unit histograms
 constexpr uint32_t STAGE_MAX_GRID = 32768;         // with at most 2^20 tiles per table: at most 32 tiles per workgroup
+constexpr uint32_t STAGE_TILES = 4;                // tiles per workgroup on tables whose layers average STAGE_LONG_LAYER_TILES
+constexpr uint32_t STAGE_LONG_LAYER_TILES = 256;   // tiles or more: most tiles have nothing to do when look 1 staged the
+                                                   // layer, and a workgroup that only finds that out still costs a launch
+                                                   // slot and two dependent loads (AlexNet-shaped: 3 us per step less; on
+                                                   // the ResNet-50-shaped set, whose hints miss more often, 8 us more)
 
 __global__ __launch_bounds__(BLOCK) void k_stage(ResidualPtrs R, const float* __restrict__ w,
                                                  const DevLayer* __restrict__ layers, uint32_t n_layers,
