@@ -301,11 +301,12 @@ def bench_topk(iwp, wl, torch, np, args, workload, hint_modes, want_parts, want_
         else:
             g = [grads[wl.gradient_set_of(ps, p, t, pool)] for p in range(ps.W)]
         hint = thr2[(t + 1) % 2] if (use_hint[0] and t > 0) else None
+        lead_t = None if flat_cfg else leaders[t]      # no leader table: the local worker (0) leads its one layer
         if fused:
-            iwp.step_segmented(plan, w, g, r, leaders[t], eps, scale, idx, val, sm, thr2[t % 2], ws, stream,
+            iwp.step_segmented(plan, w, g, r, lead_t, eps, scale, idx, val, sm, thr2[t % 2], ws, stream,
                                thr_hint=hint)
         else:
-            iwp.compress_segmented(plan, w, g, r, leaders[t], eps, idx, val, thr2[t % 2], ws, stream, thr_hint=hint)
+            iwp.compress_segmented(plan, w, g, r, lead_t, eps, idx, val, thr2[t % 2], ws, stream, thr_hint=hint)
             iwp.gather_sum_at_indices(r, idx, ps.K, sm, stream)
             iwp.apply_sparse_update(w, idx, sm, ps.K, scale, r, stream)
 

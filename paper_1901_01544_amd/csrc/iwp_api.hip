@@ -201,6 +201,32 @@ enum Stop { STOP_AT_THRESHOLD, FULL };
 // Selection on the leaders' residuals after look 1 has filled the first-digit
 // histograms, then (FULL) the ordered split.  fused: whole-step route (leader row
 // of the gather matrix, leader residual cleared).
+// Workgroups of look 1: one per tile, or GROUP / LGROUP per super-tile when a workgroup takes several tiles.
+constexpr uint32_t leader_grid(uint32_t tiles, uint32_t stiles) {
+    return LGROUP == 1 ? tiles : stiles * (GROUP / LGROUP);
+}
+
+// Up to these table sizes (bytes of one flat buffer's share of the table) look 1 leaves the weights, or the weights
+// and the residual it writes, in the memory-side cache for the kernels that come back to them (see lead_tile).
+constexpr uint64_t KEEP_W_AND_R_MAX_BYTES = 104ull << 20, KEEP_W_MAX_BYTES = 160ull << 20;
+
+int launch_leader_pass(const Table& T, const Workspace& ws, const WorkerPtrs& P, const float* w, const uint32_t* leader,
+                       uint32_t W, float eps, hipStream_t s) {
+    const uint32_t grid = leader_grid(T.tiles, T.stiles);
+    const uint64_t bytes = (uint64_t)T.tiles * TILE * sizeof(float);
+    if (bytes <= KEEP_W_AND_R_MAX_BYTES) {
+        IWP_LAUNCH("k_leader_pass", (k_leader_pass<LGROUP, KEEP_W_AND_R>), grid, s, P, w, T.layers, T.n_layers, leader, W,
+                   eps, ws.hist, ws.state, ws.stage, ws.A);
+    } else if (bytes <= KEEP_W_MAX_BYTES) {
+        IWP_LAUNCH("k_leader_pass", (k_leader_pass<LGROUP, KEEP_W>), grid, s, P, w, T.layers, T.n_layers, leader, W, eps,
+                   ws.hist, ws.state, ws.stage, ws.A);
+    } else {
+        IWP_LAUNCH("k_leader_pass", (k_leader_pass<LGROUP, KEEP_NOTHING>), grid, s, P, w, T.layers, T.n_layers, leader, W,
+                   eps, ws.hist, ws.state, ws.stage, ws.A);
+    }
+    return IWP_OK;
+}
+
 template <bool FUSED>
 int launch_write(const Table& T, const Workspace& ws, const ResidualPtrs& R, const float* w, const uint32_t* leader,
                  uint32_t W, float eps, bool all_raw, uint32_t* idx_out, float* val_out, hipStream_t s) {
@@ -229,8 +255,11 @@ int run_select(const Table& T, const Workspace& ws, const ResidualPtrs& R, const
     IWP_LAUNCH("k_first_pick", k_first_pick, T.n_layers, s, T.layers, ws.hist, ws.state);
     // Consecutive tiles per workgroup: STAGE_TILES on tables of long layers (most tiles have nothing to do when look 1
     // staged their layer), one on tables of short layers (a layer that has to be read again wants all the workgroups
-    // it can get), more on very large tables, at most 64 (their look-1 counts are fetched one per lane).
-    const uint32_t per_wg = T.tiles / std::max<uint32_t>(1u, T.n_layers) >= STAGE_LONG_LAYER_TILES ? STAGE_TILES : 1u;
+    // it can get), more on tables of very long layers (fewer flushes into a layer's one histogram), at most 64 (their
+    // look-1 counts are fetched one per lane).
+    const uint32_t avg_tiles = T.tiles / std::max<uint32_t>(1u, T.n_layers);
+    const uint32_t per_wg = avg_tiles < STAGE_LONG_LAYER_TILES ? 1u :
+        std::min<uint32_t>(std::max<uint32_t>(avg_tiles / STAGE_TILES_PER_AVG, STAGE_TILES), STAGE_TILES_MAX);
     const uint32_t stage_grid = std::max<uint32_t>(std::min<uint32_t>((T.tiles + per_wg - 1) / per_wg, STAGE_MAX_GRID),
                                                    (T.tiles + WAVE - 1) / WAVE);
     IWP_LAUNCH("k_stage", k_stage, stage_grid, s, R, w, T.layers, T.n_layers, T.tiles,
@@ -341,10 +370,10 @@ static int single_common(SingleOp op, const float* w, const float* g, float* r, 
     if (rc) return rc;
     Table T{ws.single_table, 1, z.tiles, z.stiles, k, k > 0, z.stiles};
     if (op == OP_COMPACT) return run_compact_from(T, ws, R, w, eps, from_thr, idx_out, val_out, s);
-    if (k > 0)
-        IWP_LAUNCH("k_leader_pass", k_leader_pass<LGROUP>, z.stiles * (GROUP / LGROUP), s, P, w, T.layers, 1u, nullptr, 1u, eps, ws.hist,
-                   ws.state, ws.stage, ws.A);
-    else if (g)
+    if (k > 0) {
+        rc = launch_leader_pass(T, ws, P, w, nullptr, 1u, eps, s);
+        if (rc) return rc;
+    } else if (g)
         IWP_LAUNCH("k_accumulate_rest", k_accumulate_rest, z.tiles, s, P, T.layers, 1u, z.tiles, nullptr, 1u);
     return run_select(T, ws, R, w, nullptr, 1u, eps, op == OP_SELECT ? STOP_AT_THRESHOLD : FULL, false, idx_out,
                       val_out, thr_out, s);
@@ -560,9 +589,10 @@ static int compress_segmented_on(const iwp_plan* plan, const float* w, const flo
     rc = launch_init(ws, plan->z.n_layers, thr_hint, plan->dev, nullptr, nullptr, sample_from(P, w, leader, W, eps), s);
     if (rc) return rc;
     Table T{plan->dev, plan->z.n_layers, plan->z.tiles, plan->z.stiles, plan->z.pairs, plan->any_k, plan->max_layer_stiles};
-    if (T.any_k)
-        IWP_LAUNCH("k_leader_pass", k_leader_pass<LGROUP>, T.stiles * (GROUP / LGROUP), s, P, w, T.layers, T.n_layers, leader, W, eps,
-                   ws.hist, ws.state, ws.stage, ws.A);
+    if (T.any_k) {
+        rc = launch_leader_pass(T, ws, P, w, leader, W, eps, s);
+        if (rc) return rc;
+    }
     if (W > 1 || !plan->all_k)
         IWP_LAUNCH("k_accumulate_rest", k_accumulate_rest, W * T.tiles, s, P, T.layers, T.n_layers, T.tiles, leader, W);
     return run_select(T, ws, R, w, leader, W, eps, FULL, false, idx_out, val_out, thr_out, s);
@@ -610,8 +640,8 @@ int iwp_step_segmented(const iwp_plan* plan, float* w, const float* const* g, fl
     if (rc) return rc;
     Table T{plan->dev, z.n_layers, z.tiles, z.stiles, z.pairs, plan->any_k, plan->max_layer_stiles};
     if (T.any_k) {
-        IWP_LAUNCH("k_leader_pass", k_leader_pass<LGROUP>, T.stiles * (GROUP / LGROUP), s, P, w, T.layers, T.n_layers, leader, W, eps,
-                   ws.hist, ws.state, ws.stage, ws.A);
+        rc = launch_leader_pass(T, ws, P, w, leader, W, eps, s);
+        if (rc) return rc;
         rc = run_select(T, ws, R, w, leader, W, eps, FULL, true, idx_out, val_out, thr_out, s);
         if (rc) return rc;
     }
@@ -621,7 +651,10 @@ int iwp_step_segmented(const iwp_plan* plan, float* w, const float* const* g, fl
     for (uint32_t p = 0; p < W; ++p) {
         if (g[p]) acc.id[acc.n++] = (uint8_t)p; else stat.id[stat.n++] = (uint8_t)p;
     }
-    if (acc.n)
+    // a single accumulating worker that leads every layer (no leader table: worker 0) has been through look 1 on
+    // every tile: nothing follows
+    const bool leader_did_all = acc.n == 1 && acc.id[0] == 0 && !leader && plan->all_k;
+    if (acc.n && !leader_did_all)
         IWP_LAUNCH("k_follow_gather", k_follow_gather, acc.n * T.tiles, s, P, acc, T.layers, T.n_layers, T.tiles, leader,
                    W, idx_out, ws.tile_out, ws.gathered, T.pairs);
     if (T.any_k) {
@@ -653,8 +686,8 @@ int select_threshold_segmented(const iwp_plan* plan, const float* w, const float
     memset(&R, 0, sizeof R);
     R.r[0] = const_cast<float*>(r);
     Table T{plan->dev, plan->z.n_layers, plan->z.tiles, plan->z.stiles, plan->z.pairs, plan->any_k, plan->max_layer_stiles};
-    IWP_LAUNCH("k_leader_pass", k_leader_pass<LGROUP>, T.stiles * (GROUP / LGROUP), s, P, w, T.layers, T.n_layers, nullptr, 1u, eps,
-               ws.hist, ws.state, ws.stage, ws.A);
+    rc = launch_leader_pass(T, ws, P, w, nullptr, 1u, eps, s);
+    if (rc) return rc;
     return run_select(T, ws, R, w, nullptr, 1u, eps, STOP_AT_THRESHOLD, false, nullptr, nullptr, thr_out, s);
 }
 

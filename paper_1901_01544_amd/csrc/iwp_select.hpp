@@ -264,6 +264,10 @@ __device__ __forceinline__ void flush_hist(const uint32_t* lh, uint32_t* __restr
 // ---------------------------------------------------------------------------
 constexpr uint32_t STAGE_GROUP = 16;               // tiles whose slots one unit histograms
 constexpr uint32_t STAGE_MAX_GRID = 32768;         // with at most 2^20 tiles per table: at most 32 tiles per workgroup
+constexpr uint32_t STAGE_TILES_MAX = 64;           // ... and one per STAGE_TILES_PER_AVG tiles of the average layer beyond
+constexpr uint32_t STAGE_TILES_PER_AVG = 4096;     // that, up to the 64 the kernel handles: every workgroup flushes into
+                                                   // its layer's one second-digit histogram, and same-address atomics
+                                                   // queue up (a 2^30-element layer: 15 000 flushes of up to 1024 bins)
 constexpr uint32_t STAGE_TILES = 4;                // tiles per workgroup on tables whose layers average STAGE_LONG_LAYER_TILES
 constexpr uint32_t STAGE_LONG_LAYER_TILES = 256;   // tiles or more: most tiles have nothing to do when look 1 staged the
                                                    // layer, and a workgroup that only finds that out still costs a launch
@@ -287,10 +291,17 @@ __global__ __launch_bounds__(BLOCK) void k_stage(ResidualPtrs R, const float* __
     const uint32_t my_cnt = (t0 + lane < t1) ? stage_cnt[t0 + lane] : 0u;
     uint32_t cur_j = 0xFFFFFFFFu, b1 = 0;
     bool prestaged = false;
+    bool filled = false;                                   // lh holds counts of layer cur_j that are not flushed yet:
+                                                           // one flush per workgroup and layer, however many tiles
     DevLayer L;
     for (uint32_t t = t0; t < t1; ++t) {
         const uint32_t j = find_layer<false>(layers, n_layers, t);
         if (j != cur_j) {
+            if (filled) {
+                __syncthreads();
+                flush_hist<HIST1>(lh, layer_hist(hist, L, 1));
+                filled = false;
+            }
             L = layers[j];
             b1 = state[j].b1;
             prestaged = state[j].prestaged != 0;
@@ -301,8 +312,12 @@ __global__ __launch_bounds__(BLOCK) void k_stage(ResidualPtrs R, const float* __
         const bool do_slots = prestaged && lt % STAGE_GROUP == 0;
         const bool raw = prestaged && __shfl(my_cnt, (int)(t - t0), WAVE) == RAW_TILE;
         if (prestaged && !do_slots && !raw) continue;      // uniform
-        for (uint32_t b = tid; b < HIST1; b += BLOCK) lh[b] = 0u;
-        __syncthreads();
+        if (!filled) {
+            __syncthreads();                               // a flush above has read lh
+            for (uint32_t b = tid; b < HIST1; b += BLOCK) lh[b] = 0u;
+            __syncthreads();
+            filled = true;
+        }
 
         if (do_slots) {
             // a wavefront takes every fourth tile of the group; the counts and the first 256 entries of all
@@ -413,9 +428,10 @@ __global__ __launch_bounds__(BLOCK) void k_stage(ResidualPtrs R, const float* __
                 if (tid == 0) stage_cnt[t] = (prestaged && cnt != RAW_TILE) ? (cnt | RESTAGED) : cnt;
             }
         }
+    }
+    if (filled) {
         __syncthreads();
         flush_hist<HIST1>(lh, layer_hist(hist, L, 1));
-        __syncthreads();                                   // the next unit clears lh
     }
 }
 

@@ -72,11 +72,17 @@ __device__ __forceinline__ void stream_tile(const float* __restrict__ gl, float*
 
 // One tile of a layer's leader: accumulate (ACC), score every element, histogram
 // the top key digit, and with a staging bin copy the candidates into the tile's
-// slot.  Everything streams with non-temporal accesses, the leader's residual
-// included: the second look comes after the whole first look, far too late for any
-// cache (the counters show it fetching every byte from HBM either way), and the
-// non-temporal form measured about 10 % faster here.
-template <bool ACC>
+// slot.  On large tables everything streams with non-temporal accesses, the leader's
+// residual included: the second look comes after the whole first look, far too late for
+// any cache (the counters show it fetching every byte from HBM either way), and the
+// non-temporal form measured about 10 % faster.  KEEP: on tables small enough for the
+// chip's 256 MB memory-side cache the weights (KEEP_W) or the weights and the written
+// residual (KEEP_W_AND_R) are accessed with ordinary loads and stores instead, so that
+// what touches them again within the step (the ordered write clears the sent positions
+// of the residual, the update adds to the weights at them) finds them there: 1-2 % of
+// the step on a 25 M-element table, a loss from about 45 M elements on.
+constexpr int KEEP_NOTHING = 0, KEEP_W = 1, KEEP_W_AND_R = 2;
+template <bool ACC, int KEEP>
 __device__ __forceinline__ void lead_tile(const float* __restrict__ gl, float* __restrict__ rl,
                                           const float* __restrict__ wl, uint32_t n, uint32_t lt, bool vec,
                                           float eps, float m, const LeadCtx& C) {
@@ -91,14 +97,14 @@ __device__ __forceinline__ void lead_tile(const float* __restrict__ gl, float* _
             const uint32_t i = base + u * CHUNK + tid * VEC;
             rr[u] = load_v4<true>(rl + i);
             if (ACC) gg[u] = load_v4<true>(gl + i);
-            ww[u] = load_v4<true>(wl + i);
+            ww[u] = load_v4<(KEEP < KEEP_W)>(wl + i);
         }
 #pragma unroll
         for (uint32_t u = 0; u < CHUNKS_PER_TILE; ++u) {
             const uint32_t i = base + u * CHUNK + tid * VEC;
             if (ACC) {
                 rr[u] = accum(rr[u], gg[u], m);
-                store_v4<true>(rl + i, rr[u]);
+                store_v4<(KEEP < KEEP_W_AND_R)>(rl + i, rr[u]);
             }
             val[u][0] = rr[u].x; val[u][1] = rr[u].y; val[u][2] = rr[u].z; val[u][3] = rr[u].w;
             key[u][0] = score_key(rr[u].x, ww[u].x, eps);
@@ -155,6 +161,7 @@ __device__ __forceinline__ void lead_tile(const float* __restrict__ gl, float* _
 
 // The leader's share of one group (up to LGROUP tiles of the same layer):
 // one LDS histogram of the top digit for the whole group, flushed once.
+template <int KEEP>
 __device__ __forceinline__ void leader_group(const float* gp, float* rp, const float* __restrict__ w, const DevLayer& L,
                                              uint32_t first_tile /*in layer*/, uint32_t group_tiles, float eps, float m,
                                              LeadCtx& C, uint32_t* __restrict__ ghist) {
@@ -167,8 +174,8 @@ __device__ __forceinline__ void leader_group(const float* gp, float* rp, const f
     const uint32_t ntiles = (L.n + TILE - 1) / TILE;
     const uint32_t last = min(first_tile + group_tiles, ntiles);
     for (uint32_t t = first_tile; t < last; ++t) {
-        if (gp) lead_tile<true>(gl, rl, wl, L.n, t, vec, eps, m, C);
-        else lead_tile<false>(gl, rl, wl, L.n, t, vec, eps, m, C);
+        if (gp) lead_tile<true, KEEP>(gl, rl, wl, L.n, t, vec, eps, m, C);
+        else lead_tile<false, KEEP>(gl, rl, wl, L.n, t, vec, eps, m, C);
     }
     __syncthreads();
     for (uint32_t b = threadIdx.x; b < HIST0; b += BLOCK) {
@@ -207,8 +214,10 @@ __global__ __launch_bounds__(BLOCK) void k_accumulate_rest(WorkerPtrs P, const D
     stream_tile(gl, rl, L.n, (t - L.tile_begin) * TILE, is_aligned16(rl) && is_aligned16(gl), P.momentum);
 }
 
-// Leaders only: one workgroup per group of LGROUP tiles of every layer with k > 0.
-template <uint32_t LG>
+// Leaders only: one workgroup per group of LG tiles of every layer with k > 0.  The grid:
+// with LG == 1 one workgroup per tile of the table, otherwise GROUP / LG per super-tile (some of them past the end
+// of a short layer).
+template <uint32_t LG, int KEEP>
 __global__ __launch_bounds__(BLOCK) void k_leader_pass(WorkerPtrs P, const float* __restrict__ w,
                                                        const DevLayer* __restrict__ layers, uint32_t n_layers,
                                                        const uint32_t* __restrict__ leader, uint32_t W, float eps,
@@ -217,18 +226,26 @@ __global__ __launch_bounds__(BLOCK) void k_leader_pass(WorkerPtrs P, const float
                                                        uint32_t* __restrict__ stage_cnt, StageArrays A) {
     __shared__ uint32_t lh[HIST0];
     __shared__ uint32_t slot[8];
-    constexpr uint32_t SUB = GROUP / LG;                     // workgroups per super-tile
-    const uint32_t s = blockIdx.x / SUB;
-    const uint32_t j = find_layer<true>(layers, n_layers, s);
+    uint32_t j, first;
+    if (LG == 1) {
+        j = find_layer<false>(layers, n_layers, blockIdx.x);
+    } else {
+        j = find_layer<true>(layers, n_layers, blockIdx.x / (GROUP / LG));
+    }
     const DevLayer L = layers[j];
     if (L.k == 0) return;
-    const uint32_t first = (s - L.stile_begin) * GROUP + (blockIdx.x % SUB) * LG;
-    if (first * TILE >= L.n) return;
+    if (LG == 1) {
+        first = blockIdx.x - L.tile_begin;
+    } else {
+        constexpr uint32_t SUB = GROUP / LG;                 // workgroups per super-tile
+        first = (blockIdx.x / SUB - L.stile_begin) * GROUP + (blockIdx.x % SUB) * LG;
+        if (first * TILE >= L.n) return;
+    }
     const uint32_t p = leader_of(leader, j, W);
     LeadCtx C = lead_ctx(lh, slot, L, state, j, stage_cnt, A);
     // consecutive workgroups of a layer flush into different copies of its first-digit histogram
     uint32_t* h0 = layer_hist(hist, L, 0) + (size_t)((first / LG) & (L.h0_copies - 1u)) * HIST0;
-    leader_group(P.g[p], P.r[p], w, L, first, LG, eps, P.momentum, C, h0);
+    leader_group<KEEP>(P.g[p], P.r[p], w, L, first, LG, eps, P.momentum, C, h0);
 }
 
 // The other workers, after the leader's pairs are known: accumulate, and where the

@@ -48,12 +48,16 @@ class GpuSet:
 
     def step(self, g_ids, leader_np, scale=None, hint_records=None):
         """g_ids[p]: index into the gradient pool for worker p, or None (no accumulate).
+        leader_np: the chosen node per layer, or None to pass no leader table at all.
         hint_records: (layers, 3) uint32 records to pass as this step's threshold hint, whatever the set's
         hint mode says (a set with hint mode "none" ignores them)."""
         iwp, ps = self.iwp, self.ps
         self.idx.fill_(-1)
         self.val.fill_(float("nan"))
-        self.leader.copy_(self.torch.from_numpy(leader_np.astype(np.int32)))
+        lead = None                                # leader_np None: no leader table (worker 0 leads every layer)
+        if leader_np is not None:
+            self.leader.copy_(self.torch.from_numpy(leader_np.astype(np.int32)))
+            lead = self.leader
         g = [None if i is None else self.grads[i] for i in g_ids]
         sc = float(ps.scale if scale is None else scale)
         hint = None
@@ -76,11 +80,11 @@ class GpuSet:
         self.steps_done += 1
         if self.fused:
             self.sum.fill_(float("nan"))
-            iwp.step_segmented(self.plan, self.w, g, self.r, self.leader, float(ps.eps), sc, self.idx, self.val,
+            iwp.step_segmented(self.plan, self.w, g, self.r, lead, float(ps.eps), sc, self.idx, self.val,
                                self.sum, self.thr, self.ws, thr_hint=hint)
             self.torch.cuda.synchronize()
             return
-        iwp.compress_segmented(self.plan, self.w, g, self.r, self.leader, float(ps.eps), self.idx, self.val,
+        iwp.compress_segmented(self.plan, self.w, g, self.r, lead, float(ps.eps), self.idx, self.val,
                                self.thr, self.ws, thr_hint=hint)
         iwp.gather_sum_at_indices(self.r, self.idx, ps.K, self.sum)
         iwp.apply_sparse_update(self.w, self.idx, self.sum, ps.K, sc, self.r)

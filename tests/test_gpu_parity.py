@@ -253,7 +253,7 @@ def _oracle_run(ps, steps, pool, W, r0, g_ids_fn, leader_fn, momentum, sets):
 
 
 def _run_steps(iwp, ps, steps, pool, W=None, r0=None, g_ids_fn=None, leader_fn=None, tag="", fused=False,
-               momentum=None, sets=None, keep=None):
+               momentum=None, sets=None, keep=None, leader_table=True):
     """keep: a name under which the oracle's run is kept for the other routes (only for calls whose
     inputs are fully determined by the configuration)."""
     W = ps.W if W is None else W
@@ -267,7 +267,7 @@ def _run_steps(iwp, ps, steps, pool, W=None, r0=None, g_ids_fn=None, leader_fn=N
     if momentum is not None:
         gs.plan.set_momentum(momentum)
     for t, (lead, ids, (idx_ref, val_ref, sum_ref, thr_ref), w_ref, r_ref) in enumerate(per_step):
-        gs.step(ids, lead)
+        gs.step(ids, lead if leader_table else None)
         assert_step_equal(gs.download(), w_ref, r_ref, idx_ref, val_ref, sum_ref, thr_ref, ps.layers,
                           tag="%s step %d" % (tag, t))
     return gs
@@ -338,6 +338,24 @@ def test_config5_scaled_local_plus_static_peers(gpu_lib, fused):
     ps.W = 9
     _run_steps(gpu_lib, ps, 3, pool=2, W=W, r0=r0, tag="cfg5/50", fused=fused, keep="cfg5/50",
                g_ids_fn=lambda t: [t % 2] + [None] * 8, leader_fn=lambda t: np.zeros(1, np.uint32))
+
+
+@ROUTES
+@pytest.mark.timeout(600)
+def test_config5_scaled_without_a_leader_table(gpu_lib, fused):
+    """The same run with no leader table (NULL: worker 0 leads everything), which is how a single local worker
+    calls the library; the whole-step entry point then launches no followers' pass at all (the one worker with
+    a gradient has been through look 1 on every tile).  Also with a second layer that selects nothing, where
+    that pass is still needed for the local worker."""
+    ps = wl.make_config(5, scale_down=50)
+    peers = [wl.gen_gradient(ps, 100 + p) for p in range(8)]
+    r0 = [np.zeros(ps.flat, np.float32)] + peers
+    ps.W = 9
+    _run_steps(gpu_lib, ps, 3, pool=2, W=9, r0=r0, tag="cfg5/50 no leader table", fused=fused, keep="cfg5/50",
+               g_ids_fn=lambda t: [t % 2] + [None] * 8, leader_fn=lambda t: np.zeros(1, np.uint32), leader_table=False)
+    ps2 = wl.custom_set([(300000, 300), (70000, 0), (5000, 50)], W=3, seed=97, align=4)
+    _run_steps(gpu_lib, ps2, 3, pool=2, W=3, tag="k=0 layer, no leader table", fused=fused,
+               g_ids_fn=lambda t: [t % 2, None, None], leader_fn=lambda t: np.zeros(3, np.uint32), leader_table=False)
 
 
 @ROUTES
