@@ -89,6 +89,28 @@ def test_layers_with_several_first_digit_histogram_copies(gpu_lib, n):
         _check(gpu_lib, torch, w, g, r, k, "n=%d k=%d" % (n, k))
 
 
+@pytest.mark.timeout(600)
+def test_table_between_the_two_cache_policy_bounds(gpu_lib):
+    """The first look keeps the weights and the residual it writes cacheable on small tables, only the weights
+    on medium ones, nothing on large ones (three instantiations of the same kernel).  The configurations cover
+    the small and the large variant; this layer of 7000 tiles (109 MiB per buffer) takes the middle one.  Two
+    compressions in a row, the second on the residual the first left."""
+    import torch
+    n = 7000 * TILE + 11
+    rng = np.random.default_rng(7000)
+    w = (rng.standard_normal(n) * 0.05).astype(np.float32)
+    g = (rng.standard_t(3, n) * 1e-3).astype(np.float32)
+    r = np.zeros(n, np.float32)
+    k = n // 64
+    r_ref = r.copy()
+    for rep in range(2):
+        idx_ref, val_ref, _ = oracle.compress_layer(w, g, r_ref, k, EPS)
+        idx, val, r = _compress(gpu_lib, torch, w, g, r, k)
+        # what compress_layer leaves: the accumulated residual (nothing is cleared by this call)
+        assert np.array_equal(bits(r), bits(r_ref)), "residual, call %d" % rep
+        assert np.array_equal(idx, idx_ref) and np.array_equal(bits(val), bits(val_ref)), "pairs, call %d" % rep
+
+
 def test_tiles_of_equal_keys_above_at_and_below_the_threshold(gpu_lib):
     import torch
     rng = np.random.default_rng(77)
