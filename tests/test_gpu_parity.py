@@ -353,6 +353,9 @@ def test_config5_scaled_without_a_leader_table(gpu_lib, fused):
     ps.W = 9
     _run_steps(gpu_lib, ps, 3, pool=2, W=9, r0=r0, tag="cfg5/50 no leader table", fused=fused, keep="cfg5/50",
                g_ids_fn=lambda t: [t % 2] + [None] * 8, leader_fn=lambda t: np.zeros(1, np.uint32), leader_table=False)
+    ps1 = wl.custom_set([(300000, 300), (4097, 65), (5000, 50)], W=1, seed=96, align=4)
+    _run_steps(gpu_lib, ps1, 3, pool=2, W=1, tag="one worker, no leader table", fused=fused,
+               leader_fn=lambda t: np.zeros(3, np.uint32), leader_table=False)
     ps2 = wl.custom_set([(300000, 300), (70000, 0), (5000, 50)], W=3, seed=97, align=4)
     _run_steps(gpu_lib, ps2, 3, pool=2, W=3, tag="k=0 layer, no leader table", fused=fused,
                g_ids_fn=lambda t: [t % 2, None, None], leader_fn=lambda t: np.zeros(3, np.uint32), leader_table=False)
